@@ -1,0 +1,160 @@
+/*
+ * ape.h -- C ABI of the MI355X (gfx950) APE attention library.
+ *
+ * APE = Adaptive Parallel Encoding (arXiv 2502.05431).  The library computes
+ * the attention of that method for ONE transformer layer:
+ *
+ *   ape_encode_chunks      offline pre-caching of N contexts (Section 2.2) that
+ *                          share one prefix (Section 4.1): block-diagonal causal
+ *                          attention, every context at the same positions.
+ *   ape_attention_prefill  query rows over prefix + all cached contexts + the
+ *   ape_attention_decode   query's own causal KV with the refined attention of
+ *                          Section 4.4 ("Eq.5"): context scores use 1/(T sqrt d),
+ *                          the pooled context partition sum is raised to S.
+ *
+ * General conventions
+ *   - Every data pointer marked DEVICE points to GPU memory owned by the caller;
+ *     the library never allocates, frees or copies device memory and keeps no
+ *     state between calls.  Pointers marked HOST are read during the call only.
+ *   - Tensors are row-major [tokens, heads, head_dim]; K/V have n_kv_heads heads,
+ *     Q/O have n_q_heads heads; query head h reads KV head h / (n_q_heads/n_kv_heads).
+ *     Q and K arrive already position-rotated.
+ *   - dtype APE_F32: fp32 in/out, fp32 arithmetic.  APE_BF16: bf16 in/out, bf16
+ *     matrix-core products with fp32 accumulation and fp32 softmax.
+ *   - Kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     null stream); calls return without synchronising.
+ *   - Return value: APE_OK or a negative ape_status.  Argument errors are found on
+ *     the host before anything is launched and leave all outputs untouched.
+ *     ape_last_error() gives a thread-local description of the last failure.
+ *   - LogSumExp outputs are natural-log, fp32.
+ */
+#ifndef APE_H
+#define APE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    APE_OK = 0,
+    APE_ERR_INVALID_ARG = -1,   /* null pointer, bad length, T or S not finite and > 0, ...      */
+    APE_ERR_UNSUPPORTED = -2,   /* head_dim / head ratio / dtype the kernels do not cover         */
+    APE_ERR_WORKSPACE = -3,     /* workspace missing or smaller than ape_workspace_bytes says     */
+    APE_ERR_DEVICE = -4         /* HIP reported a launch error                                    */
+} ape_status;
+
+typedef enum { APE_F32 = 0, APE_BF16 = 1 } ape_dtype;
+/* OR-ed into ape_shape.dtype: run the portable vector-ALU kernels even where the matrix-core
+ * kernels apply.  Same results within tolerance; meant for cross-checking, not for speed. */
+#define APE_DTYPE_FLAG_GENERIC 0x100
+typedef enum { APE_OP_ENCODE = 0, APE_OP_PREFILL = 1, APE_OP_DECODE = 2 } ape_op;
+
+/* Attention head geometry.  Supported: head_dim multiple of 8 and <= 256 for APE_F32 and
+ * APE_BF16; n_q_heads a multiple of n_kv_heads.  bf16 with head_dim == 128 and
+ * n_q_heads/n_kv_heads in {1,2,4,8} runs on the matrix-core kernels. */
+typedef struct {
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;              /* ape_dtype */
+} ape_shape;
+
+/*
+ * One request's cached KV as the query sees it (Section 2.2 "Generating Response",
+ * Section 4.4).  The contexts are used in place through a table, so that any subset
+ * of pre-cached contexts can be attended without copying.
+ */
+typedef struct {
+    const void *k_prefix;              /* DEVICE [prefix_len, n_kv_heads, head_dim]; may be NULL if prefix_len == 0 */
+    const void *v_prefix;              /* DEVICE, same shape                                                         */
+    int32_t prefix_len;                /* >= 0                                                                       */
+    int32_t n_chunks;                  /* >= 0; 0 = no context (plain causal attention over prefix + self)          */
+    const void *const *k_chunks;       /* DEVICE array [n_chunks] of DEVICE pointers, chunk i: [l_i, n_kv_heads, d] */
+    const void *const *v_chunks;       /* DEVICE array [n_chunks] of DEVICE pointers                                */
+    const int32_t *cu_chunk_lens;      /* DEVICE [n_chunks + 1]: 0, l_1, l_1+l_2, ..., total_ctx_len                */
+    int32_t total_ctx_len;             /* HOST copy of cu_chunk_lens[n_chunks]; the caller keeps the two equal      */
+    int32_t self_len;                  /* tokens in k_self/v_self INCLUDING the rows being queried; >= q_len >= 1   */
+    const void *k_self;                /* DEVICE [self_len, n_kv_heads, head_dim]: query + generated tokens         */
+    const void *v_self;                /* DEVICE                                                                     */
+    float temperature;                 /* T of Eq.5, finite and > 0 (the paper uses T <= 1)                         */
+    float scale;                       /* S of Eq.5, finite and > 0 (the paper uses S <= 1)                         */
+} ape_request;
+
+/*
+ * Bytes of caller-provided DEVICE workspace an operation needs (0 is possible).
+ * An upper bound that depends only on the arguments given, never on the data.
+ *   op       ape_op
+ *   batch    requests (decode); 1 otherwise
+ *   q_len    query rows per request (prefill); 1 for decode; ignored for encode
+ * Returns 0 on invalid arguments as well; the entry points re-validate.
+ */
+size_t ape_workspace_bytes(int op, const ape_shape *shape, int32_t batch, int32_t q_len);
+
+/*
+ * Pre-caching attention of Section 2.2 with the shared prefix of Section 4.1.
+ * Context i is encoded as [prefix ; C_i]: row r of context i attends to every prefix
+ * token and to rows 0..r of its own context with scores q.k/sqrt(d) (Section 2.3);
+ * contexts never see each other; no T, no S.
+ *
+ *   q_prefix/o_prefix   DEVICE [prefix_len, n_q_heads, d] or both NULL: when given, the
+ *                       prefix rows are computed too (plain causal attention over the prefix).
+ *   k_prefix,v_prefix   DEVICE [prefix_len, n_kv_heads, d]
+ *   q_chunks,o_chunks   DEVICE packed contexts [M, n_q_heads, d], M = cu_chunk_lens_host[n_chunks]
+ *   k_chunks,v_chunks   DEVICE packed contexts [M, n_kv_heads, d]
+ *   cu_chunk_lens_host  HOST  [n_chunks + 1] prefix sums of the context lengths (sizes the grid)
+ *   cu_chunk_lens_dev   DEVICE copy of the same array (read by the kernels)
+ *   lse_prefix          DEVICE fp32 [n_q_heads, prefix_len] or NULL
+ *   lse_chunks          DEVICE fp32 [n_q_heads, M] or NULL: LogSumExp of each row's scores
+ *   workspace           unused by the current kernels (ape_workspace_bytes gives 0); may be NULL
+ */
+int ape_encode_chunks(const ape_shape *shape,
+                      const void *q_prefix, const void *k_prefix, const void *v_prefix, int32_t prefix_len,
+                      const void *q_chunks, const void *k_chunks, const void *v_chunks,
+                      const int32_t *cu_chunk_lens_host, const int32_t *cu_chunk_lens_dev, int32_t n_chunks,
+                      void *o_prefix, void *o_chunks, float *lse_prefix, float *lse_chunks,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Query prefill with the refined attention of Section 4.4 (Eq.5), computed in the
+ * two-block form of Appendix C.3/C.4: context block with scores q.k/(T sqrt d) and its
+ * LogSumExp multiplied by S, non-context block (prefix + causal self) unscaled, merged by
+ * a softmax over the two LogSumExps.  S is applied to the POOLED context block.
+ *
+ *   req       HOST  one request; the last q_len tokens of k_self/v_self are the query rows'
+ *             own KV: row r sees self tokens 0 .. self_len - q_len + r.
+ *   q, out    DEVICE [q_len, n_q_heads, d]
+ *   lse_out   DEVICE fp32 [n_q_heads, q_len] or NULL: log(Z_prefix + Z_ctx^S + Z_self)
+ *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_PREFILL, shape, 1, q_len), 256-byte aligned
+ */
+int ape_attention_prefill(const ape_shape *shape, const ape_request *req,
+                          const void *q, int32_t q_len, void *out, float *lse_out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One decode step for a batch of independent requests: Eq.5 with a single query row per
+ * request, which sees all self_len self tokens (the newest being its own; the caller has
+ * appended its K/V before the call).  Each request carries its own T and S.
+ *
+ *   reqs      HOST array [batch]
+ *   q, out    DEVICE [batch, n_q_heads, d]
+ *   lse_out   DEVICE fp32 [batch, n_q_heads] or NULL
+ *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_DECODE, shape, batch, 1), 256-byte aligned
+ */
+int ape_attention_decode(const ape_shape *shape, const ape_request *reqs, int32_t batch,
+                         const void *q, void *out, float *lse_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Text for a status code (static storage). */
+const char *ape_status_string(int status);
+/* Description of the calling thread's last failing call ("" if none). */
+const char *ape_last_error(void);
+/* Library version, "major.minor.patch". */
+const char *ape_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APE_H */

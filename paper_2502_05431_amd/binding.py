@@ -1,0 +1,215 @@
+"""Thin ctypes binding of ``libape_hip.so`` (the C ABI in ``include/ape.h``).
+
+Argument marshalling only: every step of the attention path runs in the HIP
+kernels.  torch is used for device memory and streams.  The library must have
+been built (``python -m paper_2502_05431_amd.build``); loading fails loudly if it
+is missing -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libape_hip.so")
+
+APE_OK = 0
+APE_ERR_INVALID_ARG, APE_ERR_UNSUPPORTED, APE_ERR_WORKSPACE, APE_ERR_DEVICE = -1, -2, -3, -4
+APE_F32, APE_BF16 = 0, 1
+APE_DTYPE_FLAG_GENERIC = 0x100
+APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
+
+EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
+           "ape_status_string", "ape_last_error", "ape_version")
+
+
+class ApeShape(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class ApeRequest(ctypes.Structure):
+    _fields_ = [("k_prefix", ctypes.c_void_p), ("v_prefix", ctypes.c_void_p),
+                ("prefix_len", ctypes.c_int32), ("n_chunks", ctypes.c_int32),
+                ("k_chunks", ctypes.c_void_p), ("v_chunks", ctypes.c_void_p),
+                ("cu_chunk_lens", ctypes.c_void_p),
+                ("total_ctx_len", ctypes.c_int32), ("self_len", ctypes.c_int32),
+                ("k_self", ctypes.c_void_p), ("v_self", ctypes.c_void_p),
+                ("temperature", ctypes.c_float), ("scale", ctypes.c_float)]
+
+
+class ApeError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("ape status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is missing: build it with `python -m paper_2502_05431_amd.build` "
+                               "(there is no fallback path)" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        lib.ape_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(ApeShape), i32, i32]
+        lib.ape_workspace_bytes.restype = sz
+        lib.ape_encode_chunks.argtypes = [ctypes.POINTER(ApeShape), vp, vp, vp, i32, vp, vp, vp, vp, vp, i32,
+                                          vp, vp, vp, vp, vp, sz, vp]
+        lib.ape_encode_chunks.restype = ctypes.c_int
+        lib.ape_attention_prefill.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, i32, vp, vp,
+                                              vp, sz, vp]
+        lib.ape_attention_prefill.restype = ctypes.c_int
+        lib.ape_attention_decode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), i32, vp, vp, vp,
+                                             vp, sz, vp]
+        lib.ape_attention_decode.restype = ctypes.c_int
+        lib.ape_status_string.argtypes = [ctypes.c_int]
+        lib.ape_status_string.restype = ctypes.c_char_p
+        lib.ape_last_error.restype = ctypes.c_char_p
+        lib.ape_version.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != APE_OK:
+        lib = load()
+        raise ApeError(rc, "%s: %s" % (lib.ape_status_string(rc).decode(), lib.ape_last_error().decode()))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors handed to the library must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def make_shape(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype, generic: bool = False) -> ApeShape:
+    code = {torch.float32: APE_F32, torch.bfloat16: APE_BF16}.get(dtype, dtype)
+    if not isinstance(code, int):
+        raise ValueError("dtype must be torch.float32 or torch.bfloat16")
+    return ApeShape(n_q_heads, n_kv_heads, head_dim, code | (APE_DTYPE_FLAG_GENERIC if generic else 0))
+
+
+def workspace_bytes(op: int, shape: ApeShape, batch: int = 1, q_len: int = 1) -> int:
+    return int(load().ape_workspace_bytes(op, ctypes.byref(shape), batch, q_len))
+
+
+@dataclass
+class Request:
+    """One request's KV for ``attention_prefill`` / ``attention_decode``: holds the device
+    tensors (keeping them alive) and the device-resident chunk table."""
+    k_prefix: Optional[torch.Tensor]
+    v_prefix: Optional[torch.Tensor]
+    k_chunks: Sequence[torch.Tensor]
+    v_chunks: Sequence[torch.Tensor]
+    k_self: torch.Tensor
+    v_self: torch.Tensor
+    self_len: int
+    temperature: float
+    scale: float
+    _k_table: Optional[torch.Tensor] = field(default=None, repr=False)
+    _v_table: Optional[torch.Tensor] = field(default=None, repr=False)
+    _cu: Optional[torch.Tensor] = field(default=None, repr=False)
+    total_ctx_len: int = 0
+
+    def __post_init__(self):
+        dev = self.k_self.device
+        n = len(self.k_chunks)
+        assert n == len(self.v_chunks)
+        if n:
+            for t in list(self.k_chunks) + list(self.v_chunks):
+                assert t.is_contiguous()
+            self._k_table = torch.tensor([t.data_ptr() for t in self.k_chunks], dtype=torch.int64, device=dev)
+            self._v_table = torch.tensor([t.data_ptr() for t in self.v_chunks], dtype=torch.int64, device=dev)
+            cu = [0]
+            for t in self.k_chunks:
+                cu.append(cu[-1] + t.shape[0])
+            self.total_ctx_len = cu[-1]
+            self._cu = torch.tensor(cu, dtype=torch.int32, device=dev)
+
+    def as_struct(self, self_len: Optional[int] = None) -> ApeRequest:
+        r = ApeRequest()
+        lp = 0 if self.k_prefix is None else self.k_prefix.shape[0]
+        r.k_prefix = self.k_prefix.data_ptr() if lp else None
+        r.v_prefix = self.v_prefix.data_ptr() if lp else None
+        r.prefix_len = lp
+        r.n_chunks = len(self.k_chunks)
+        r.k_chunks = self._k_table.data_ptr() if self._k_table is not None else None
+        r.v_chunks = self._v_table.data_ptr() if self._v_table is not None else None
+        r.cu_chunk_lens = self._cu.data_ptr() if self._cu is not None else None
+        r.total_ctx_len = self.total_ctx_len
+        r.self_len = self.self_len if self_len is None else self_len
+        r.k_self = self.k_self.data_ptr()
+        r.v_self = self.v_self.data_ptr()
+        r.temperature = self.temperature
+        r.scale = self.scale
+        return r
+
+
+def encode_chunks(shape: ApeShape, q_prefix, k_prefix, v_prefix, q_chunks, k_chunks, v_chunks,
+                  cu_chunk_lens: Sequence[int], cu_chunk_lens_dev: Optional[torch.Tensor],
+                  o_prefix, o_chunks, lse_prefix=None, lse_chunks=None, workspace=None, stream=None):
+    """``ape_encode_chunks``: packed contexts [M, H, d]; ``cu_chunk_lens`` is the host prefix-sum list,
+    ``cu_chunk_lens_dev`` its int32 device copy."""
+    n_chunks = len(cu_chunk_lens) - 1 if cu_chunk_lens is not None and len(cu_chunk_lens) else 0
+    cu_host = (ctypes.c_int32 * (n_chunks + 1))(*cu_chunk_lens) if n_chunks else None
+    prefix_len = 0 if k_prefix is None else k_prefix.shape[0]
+    rc = load().ape_encode_chunks(ctypes.byref(shape), _ptr(q_prefix), _ptr(k_prefix), _ptr(v_prefix), prefix_len,
+                                  _ptr(q_chunks), _ptr(k_chunks), _ptr(v_chunks),
+                                  ctypes.cast(cu_host, ctypes.c_void_p) if cu_host is not None else None,
+                                  _ptr(cu_chunk_lens_dev), n_chunks,
+                                  _ptr(o_prefix), _ptr(o_chunks), _ptr(lse_prefix), _ptr(lse_chunks),
+                                  _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                  _stream(stream))
+    _check(rc)
+
+
+def attention_prefill(shape: ApeShape, req: Request, q: torch.Tensor, out: torch.Tensor,
+                      lse_out: Optional[torch.Tensor], workspace: torch.Tensor, stream=None, self_len=None):
+    """``ape_attention_prefill``: q/out [q_len, Hq, d]; lse_out fp32 [Hq, q_len] or None."""
+    r = req.as_struct(self_len)
+    rc = load().ape_attention_prefill(ctypes.byref(shape), ctypes.byref(r), _ptr(q), q.shape[0], _ptr(out), _ptr(lse_out),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc)
+
+
+def attention_decode(shape: ApeShape, reqs: Sequence[Request], q: torch.Tensor, out: torch.Tensor,
+                     lse_out: Optional[torch.Tensor], workspace: torch.Tensor, stream=None,
+                     self_lens: Optional[Sequence[int]] = None):
+    """``ape_attention_decode``: q/out [batch, Hq, d]; lse_out fp32 [batch, Hq] or None."""
+    n = len(reqs)
+    arr = (ApeRequest * n)(*[r.as_struct(None if self_lens is None else self_lens[i]) for i, r in enumerate(reqs)])
+    rc = load().ape_attention_decode(ctypes.byref(shape), arr, n, _ptr(q), _ptr(out), _ptr(lse_out),
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc)
+
+
+def decode_call(shape: ApeShape, reqs: Sequence[Request], q, out, lse_out, workspace, stream=None):
+    """Pre-marshalled decode call for tight loops: returns ``(fn, structs)`` where ``structs`` is
+    the ctypes array of ape_request whose ``self_len`` fields the caller bumps between steps."""
+    lib = load()
+    n = len(reqs)
+    arr = (ApeRequest * n)(*[r.as_struct() for r in reqs])
+    sh = ctypes.byref(shape)
+    args = (_ptr(q), _ptr(out), _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+
+    def fn():
+        rc = lib.ape_attention_decode(sh, arr, n, *args)
+        if rc != APE_OK:
+            _check(rc)
+    return fn, arr

@@ -1,0 +1,256 @@
+// Host side of the C ABI declared in include/ape.h: argument validation, split planning,
+// workspace carving and kernel launches.  Nothing here allocates, copies or synchronises.
+#include "ape_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace ape {
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
+
+struct ShapeInfo {
+    int hq, hkv, d, dtype, group;
+    bool force_generic;
+    bool mfma;                  // matrix-core kernels cover this shape
+};
+
+int check_shape(const ape_shape* s, ShapeInfo* o) {
+    if (!s) return fail(APE_ERR_INVALID_ARG, "shape is NULL");
+    o->hq = s->n_q_heads; o->hkv = s->n_kv_heads; o->d = s->head_dim;
+    o->force_generic = (s->dtype & APE_DTYPE_FLAG_GENERIC) != 0;
+    o->dtype = s->dtype & ~APE_DTYPE_FLAG_GENERIC;
+    if (o->hq <= 0 || o->hkv <= 0 || o->d <= 0)
+        return fail(APE_ERR_INVALID_ARG, "head counts and head_dim must be positive (got %d, %d, %d)", o->hq, o->hkv, o->d);
+    if (o->hq % o->hkv) return fail(APE_ERR_INVALID_ARG, "n_q_heads %d is not a multiple of n_kv_heads %d", o->hq, o->hkv);
+    if (o->dtype != APE_F32 && o->dtype != APE_BF16) return fail(APE_ERR_UNSUPPORTED, "dtype %d is not APE_F32 or APE_BF16", o->dtype);
+    if (o->d > 256 || o->d % 8) return fail(APE_ERR_UNSUPPORTED, "head_dim %d: must be a multiple of 8 and <= 256", o->d);
+    o->group = o->hq / o->hkv;
+    o->mfma = !o->force_generic && o->dtype == APE_BF16 && o->d == 128 &&
+              (o->group == 1 || o->group == 2 || o->group == 4 || o->group == 8);
+    return APE_OK;
+}
+
+int check_request(const ape_request* r, int q_len, int idx) {
+    if (r->prefix_len < 0) return fail(APE_ERR_INVALID_ARG, "request %d: prefix_len %d < 0", idx, r->prefix_len);
+    if (r->prefix_len > 0 && (!r->k_prefix || !r->v_prefix)) return fail(APE_ERR_INVALID_ARG, "request %d: prefix KV is NULL", idx);
+    if (r->n_chunks < 0 || r->total_ctx_len < 0) return fail(APE_ERR_INVALID_ARG, "request %d: negative chunk count or context length", idx);
+    if (r->n_chunks == 0 && r->total_ctx_len != 0) return fail(APE_ERR_INVALID_ARG, "request %d: total_ctx_len %d with no chunks", idx, r->total_ctx_len);
+    if (r->n_chunks > 0 && (!r->k_chunks || !r->v_chunks || !r->cu_chunk_lens))
+        return fail(APE_ERR_INVALID_ARG, "request %d: chunk table is NULL", idx);
+    if (r->self_len < q_len || q_len < 1) return fail(APE_ERR_INVALID_ARG, "request %d: self_len %d < q_len %d (the query rows' own KV belongs to k_self)", idx, r->self_len, q_len);
+    if (!r->k_self || !r->v_self) return fail(APE_ERR_INVALID_ARG, "request %d: self KV is NULL", idx);
+    if (!(std::isfinite(r->temperature) && r->temperature > 0.f)) return fail(APE_ERR_INVALID_ARG, "request %d: temperature must be finite and > 0", idx);
+    if (!(std::isfinite(r->scale) && r->scale > 0.f)) return fail(APE_ERR_INVALID_ARG, "request %d: scale must be finite and > 0", idx);
+    return APE_OK;
+}
+
+KvView to_view(const ape_request* r) {
+    KvView v;
+    v.k_prefix = r->k_prefix; v.v_prefix = r->v_prefix;
+    v.k_chunks = r->k_chunks; v.v_chunks = r->v_chunks; v.cu = r->cu_chunk_lens;
+    v.k_self = r->k_self; v.v_self = r->v_self;
+    v.prefix_len = r->prefix_len; v.n_chunks = r->n_chunks;
+    v.total_ctx = r->n_chunks > 0 ? r->total_ctx_len : 0;
+    v.self_len = r->self_len;
+    v.temperature = r->temperature; v.scale = r->scale;
+    return v;
+}
+
+// Number of context splits: enough workgroups to fill 256 CUs a few times over, never more than
+// kMaxSplits, never splits shorter than `min_len` tokens.  Depends on sizes only.
+QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_workgroups) {
+    QueryPlan p;
+    if (max_ctx <= 0) { p.n_ctx_splits = 0; p.ctx_split_len = 64; p.n_splits_total = 1; return p; }
+    int want = ceil_div(target_workgroups, base_workgroups > 0 ? base_workgroups : 1);
+    int cap = ceil_div(max_ctx, min_len);
+    int n = want < 1 ? 1 : want;
+    if (n > cap) n = cap;
+    if (n > kMaxSplits) n = kMaxSplits;
+    long len = (max_ctx + n - 1) / n;
+    len = (len + 63) / 64 * 64;                        // tiles never straddle a split
+    n = ceil_div(max_ctx, len);
+    p.n_ctx_splits = n; p.ctx_split_len = (int)len; p.n_splits_total = n + 1;
+    return p;
+}
+
+size_t partial_bytes(long units, int n_splits_total, int d) {
+    return align_up((size_t)units * n_splits_total * d * sizeof(float), kWsAlign) +
+           align_up((size_t)units * n_splits_total * sizeof(float), kWsAlign);
+}
+
+}  // namespace
+}  // namespace ape
+
+using namespace ape;
+
+extern "C" {
+
+const char* ape_status_string(int status) {
+    switch (status) {
+        case APE_OK: return "ok";
+        case APE_ERR_INVALID_ARG: return "invalid argument";
+        case APE_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case APE_ERR_WORKSPACE: return "workspace missing or too small";
+        case APE_ERR_DEVICE: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+const char* ape_last_error(void) { return g_err; }
+const char* ape_version(void) { return "0.1.0"; }
+
+size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_t q_len) {
+    ShapeInfo si;
+    if (check_shape(shape, &si) != APE_OK) return 0;
+    if (op == APE_OP_ENCODE) return 0;
+    if (op == APE_OP_DECODE) q_len = 1;
+    else if (op == APE_OP_PREFILL) batch = 1;
+    else return 0;
+    if (batch < 1 || q_len < 1) return 0;
+    // worst case over every context length: kMaxSplits context splits + 1
+    return partial_bytes((long)batch * q_len * si.hq, kMaxSplits + 1, si.d);
+}
+
+int ape_encode_chunks(const ape_shape* shape,
+                      const void* q_prefix, const void* k_prefix, const void* v_prefix, int32_t prefix_len,
+                      const void* q_chunks, const void* k_chunks, const void* v_chunks,
+                      const int32_t* cu_host, const int32_t* cu_dev, int32_t n_chunks,
+                      void* o_prefix, void* o_chunks, float* lse_prefix, float* lse_chunks,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (prefix_len < 0 || n_chunks < 0) return fail(APE_ERR_INVALID_ARG, "prefix_len and n_chunks must be >= 0");
+    if (prefix_len > 0 && (!k_prefix || !v_prefix)) return fail(APE_ERR_INVALID_ARG, "prefix KV is NULL");
+    if ((q_prefix == nullptr) != (o_prefix == nullptr)) return fail(APE_ERR_INVALID_ARG, "q_prefix and o_prefix must both be given or both be NULL");
+    if (lse_prefix && !q_prefix) return fail(APE_ERR_INVALID_ARG, "lse_prefix given without q_prefix");
+    long total = 0;
+    int max_len = 0;
+    if (n_chunks > 0) {
+        if (!cu_host || !cu_dev) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens (host and device) are required");
+        if (cu_host[0] != 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens[0] must be 0");
+        for (int i = 0; i < n_chunks; ++i) {
+            const long li = (long)cu_host[i + 1] - cu_host[i];
+            if (li < 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens is not non-decreasing at %d", i);
+            if (li > max_len) max_len = (int)li;
+        }
+        total = cu_host[n_chunks];
+        if (total > 0 && (!q_chunks || !k_chunks || !v_chunks || !o_chunks)) return fail(APE_ERR_INVALID_ARG, "chunk Q/K/V/O is NULL");
+    }
+    hipStream_t st = (hipStream_t)stream;
+
+    // the prefix rows are one more "context" with no prefix in front of it
+    if (q_prefix && prefix_len > 0) {
+        // cu for a single chunk [0, prefix_len): reuse of a device table is not possible without a
+        // copy, so the prefix rows go through the kernels' single-chunk mode (cu == NULL).
+        EncodeArgs e{};
+        e.q = q_prefix; e.k = k_prefix; e.v = v_prefix; e.k_prefix = nullptr; e.v_prefix = nullptr;
+        e.cu = nullptr; e.out = o_prefix; e.lse = lse_prefix;
+        e.n_chunks = 1; e.prefix_len = 0; e.total_rows = prefix_len; e.max_chunk_len = prefix_len;
+        e.n_q_heads = si.hq; e.n_kv_heads = si.hkv; e.head_dim = si.d;
+        hipError_t he = si.mfma ? launch_flash_encode(e, st) : launch_generic_encode(e, si.dtype, st);
+        if (he != hipSuccess) return fail(APE_ERR_DEVICE, "encode (prefix rows): %s", hipGetErrorString(he));
+    }
+    if (total > 0) {
+        EncodeArgs e{};
+        e.q = q_chunks; e.k = k_chunks; e.v = v_chunks; e.k_prefix = k_prefix; e.v_prefix = v_prefix;
+        e.cu = cu_dev; e.out = o_chunks; e.lse = lse_chunks;
+        e.n_chunks = n_chunks; e.prefix_len = prefix_len; e.total_rows = (int)total; e.max_chunk_len = max_len;
+        e.n_q_heads = si.hq; e.n_kv_heads = si.hkv; e.head_dim = si.d;
+        hipError_t he = si.mfma ? launch_flash_encode(e, st) : launch_generic_encode(e, si.dtype, st);
+        if (he != hipSuccess) return fail(APE_ERR_DEVICE, "encode: %s", hipGetErrorString(he));
+    }
+    return APE_OK;
+}
+
+static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, int q_len, bool decode,
+                     const void* q, void* out, float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    long max_ctx = 0;
+    for (int b = 0; b < batch; ++b) {
+        int rc = check_request(&reqs[b], q_len, b);
+        if (rc) return rc;
+        const long m = reqs[b].n_chunks > 0 ? reqs[b].total_ctx_len : 0;
+        if (m > max_ctx) max_ctx = m;
+    }
+    const long units = (long)batch * q_len * si.hq;
+    QueryPlan plan;
+    if (decode) {
+        // one workgroup per (request, KV head, split) on the matrix-core path
+        const int base = si.mfma ? batch * si.hkv : (int)units;
+        plan = plan_query(base, max_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
+    } else {
+        const int rows = q_len * si.group;
+        const int base = si.mfma ? si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
+        plan = plan_query(base, max_ctx, si.mfma ? 256 : 256, si.mfma ? 512 : 1024);
+    }
+    const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
+    if (!workspace || workspace_bytes < need)
+        return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_workspace_bytes gives the bound)", workspace_bytes, need);
+    if ((uintptr_t)workspace % kWsAlign) return fail(APE_ERR_WORKSPACE, "workspace must be %d-byte aligned", kWsAlign);
+    float* part_o = (float*)workspace;
+    float* part_lse = (float*)((char*)workspace + align_up((size_t)units * plan.n_splits_total * si.d * sizeof(float), kWsAlign));
+
+    for (int b0 = 0; b0 < batch; b0 += kMaxReqPerLaunch) {
+        const int nb = batch - b0 < kMaxReqPerLaunch ? batch - b0 : kMaxReqPerLaunch;
+        QueryArgs a{};
+        MergeArgs m{};
+        for (int i = 0; i < nb; ++i) { a.req[i] = to_view(&reqs[b0 + i]); m.scale[i] = reqs[b0 + i].scale; }
+        a.q = (const char*)q + (size_t)b0 * q_len * si.hq * si.d * (si.dtype == APE_F32 ? 4 : 2);
+        a.part_o = part_o; a.part_lse = part_lse;
+        a.n_req = nb; a.q_len = q_len; a.n_q_heads = si.hq; a.n_kv_heads = si.hkv; a.head_dim = si.d;
+        a.n_ctx_splits = plan.n_ctx_splits; a.ctx_split_len = plan.ctx_split_len;
+        a.units_total = (int)units; a.req_base = b0;
+        hipError_t he;
+        if (si.mfma) he = decode ? launch_decode_mfma(a, st) : launch_flash_prefill(a, st);
+        else he = launch_generic_query(a, si.dtype, st);
+        if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
+
+        m.part_o = part_o; m.part_lse = part_lse; m.out = out; m.lse_out = lse_out;
+        m.n_req = nb; m.q_len = q_len; m.n_q_heads = si.hq; m.head_dim = si.d;
+        m.n_ctx_splits = plan.n_ctx_splits; m.n_splits_total = plan.n_splits_total;
+        m.units_total = (int)units; m.req_base = b0; m.lse_head_major = decode ? 0 : 1; m.dtype = si.dtype;
+        he = launch_merge(m, st);
+        if (he != hipSuccess) return fail(APE_ERR_DEVICE, "merge kernel: %s", hipGetErrorString(he));
+    }
+    return APE_OK;
+}
+
+int ape_attention_prefill(const ape_shape* shape, const ape_request* req,
+                          const void* q, int32_t q_len, void* out, float* lse_out,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (!req || !q || !out) return fail(APE_ERR_INVALID_ARG, "req, q and out must not be NULL");
+    if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
+    return run_query(si, req, 1, q_len, false, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int ape_attention_decode(const ape_shape* shape, const ape_request* reqs, int32_t batch,
+                         const void* q, void* out, float* lse_out,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (!reqs || !q || !out) return fail(APE_ERR_INVALID_ARG, "reqs, q and out must not be NULL");
+    if (batch < 1) return fail(APE_ERR_INVALID_ARG, "batch %d < 1", batch);
+    return run_query(si, reqs, batch, 1, true, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

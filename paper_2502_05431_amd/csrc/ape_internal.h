@@ -1,0 +1,128 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+// Not part of the public ABI (that is include/ape.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ape.h"
+
+namespace ape {
+
+// Device-visible copy of one ape_request (pointers are device pointers).
+struct KvView {
+    const void* k_prefix;
+    const void* v_prefix;
+    const void* const* k_chunks;
+    const void* const* v_chunks;
+    const int32_t* cu;          // [n_chunks + 1]
+    const void* k_self;
+    const void* v_self;
+    int32_t prefix_len;
+    int32_t n_chunks;
+    int32_t total_ctx;
+    int32_t self_len;
+    float temperature;
+    float scale;
+};
+
+constexpr int kMaxReqPerLaunch = 32;     // requests whose descriptors travel in one kernel-argument block
+constexpr int kMaxSplits = 64;           // upper bound of context splits per (request, head)
+constexpr int kWsAlign = 256;
+
+// Kernel-argument block of the query-time kernels (prefill and decode).
+struct QueryArgs {
+    KvView req[kMaxReqPerLaunch];
+    const void* q;              // [batch*q_len, Hq, d]
+    float* part_o;              // [n_splits_total][units][d], unit = (request*q_len + row)*Hq + head
+    float* part_lse;            // [n_splits_total][units]
+    int32_t n_req;
+    int32_t q_len;              // rows per request
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t n_ctx_splits;       // splits of the context group; split index n_ctx_splits is prefix + self
+    int32_t ctx_split_len;      // context tokens per split (multiple of 64)
+    int32_t units_total;        // n_req * q_len * Hq (stride of the split dimension)
+    int32_t req_base;           // index of req[0] in the whole batch
+};
+
+struct MergeArgs {
+    const float* part_o;
+    const float* part_lse;
+    void* out;                  // [units][d], dtype
+    float* lse_out;             // NULL or fp32
+    float scale[kMaxReqPerLaunch];
+    int32_t n_req;
+    int32_t q_len;
+    int32_t n_q_heads;
+    int32_t head_dim;
+    int32_t n_ctx_splits;
+    int32_t n_splits_total;
+    int32_t units_total;
+    int32_t req_base;
+    int32_t lse_head_major;     // 1: lse_out[h*q_len + r] (prefill); 0: lse_out[unit] (decode)
+    int32_t dtype;
+};
+
+struct EncodeArgs {
+    const void* q;              // packed [M, Hq, d]
+    const void* k;              // packed [M, Hkv, d]
+    const void* v;
+    const void* k_prefix;
+    const void* v_prefix;
+    const int32_t* cu;          // device [n_chunks + 1]
+    void* out;                  // packed [M, Hq, d]
+    float* lse;                 // NULL or [Hq, M]
+    int32_t n_chunks;
+    int32_t prefix_len;
+    int32_t total_rows;         // M
+    int32_t max_chunk_len;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+};
+
+#if defined(__HIPCC__)
+// Field access into the kernel-argument segment.  A by-value argument struct that is indexed
+// with a run-time index would be copied to scratch as a whole; reading it through the
+// segment pointer keeps the accesses scalar loads.  Valid only for kernels whose FIRST
+// argument is the struct in question (it then starts at offset 0 of the segment).
+template <typename Args>
+__device__ __forceinline__ __attribute__((address_space(4))) const Args* kernarg() {
+    return (__attribute__((address_space(4))) const Args*)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
+template <typename Args>
+__device__ __forceinline__ KvView load_view(int rq) {
+    auto ap = kernarg<Args>();
+    KvView v;
+    v.k_prefix = ap->req[rq].k_prefix; v.v_prefix = ap->req[rq].v_prefix;
+    v.k_chunks = ap->req[rq].k_chunks; v.v_chunks = ap->req[rq].v_chunks; v.cu = ap->req[rq].cu;
+    v.k_self = ap->req[rq].k_self; v.v_self = ap->req[rq].v_self;
+    v.prefix_len = ap->req[rq].prefix_len; v.n_chunks = ap->req[rq].n_chunks;
+    v.total_ctx = ap->req[rq].total_ctx; v.self_len = ap->req[rq].self_len;
+    v.temperature = ap->req[rq].temperature; v.scale = ap->req[rq].scale;
+    return v;
+}
+#endif
+
+// Split plan shared by ape_workspace_bytes and the launches.
+struct QueryPlan {
+    int n_ctx_splits;
+    int ctx_split_len;
+    int n_splits_total;
+};
+
+// ---- launchers (each returns hipGetLastError() of its launch) ------------------------------
+hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s);
+hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s);     // bf16, d = 128
+hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s);     // bf16, d = 128
+hipError_t launch_decode_mfma(const QueryArgs& a, hipStream_t s);       // bf16, d = 128, q_len = 1
+
+// rows of (token, group-head) pairs one flash workgroup covers for a given amount of rows
+int flash_block_rows(int rows_per_kv_head);
+
+}  // namespace ape

@@ -1,0 +1,131 @@
+"""Shared plumbing of the GPU parity tests: runs the HIP library through its C ABI
+(via the thin binding) and the fp64 oracle on the same seeded arrays."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import ape_oracle
+from paper_2502_05431_amd import binding as B
+from paper_2502_05431_amd import workloads as W
+
+# Tolerances fixed by the benchmark definition: fp32 max-abs <= 1e-5; bf16 storage with fp32
+# accumulation: relative L2 <= 5e-3 and max-abs <= 2e-2.
+F32_MAX_ABS = 1e-5
+BF16_REL_L2 = 5e-3
+BF16_MAX_ABS = 2e-2
+
+
+def check_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = ""):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape, what)
+    assert np.isfinite(got).all(), "non-finite output: " + what
+    err = np.abs(got - ref).max() if got.size else 0.0
+    if dtype == "f32":
+        assert err <= F32_MAX_ABS, "%s: max-abs %.3e > %.1e" % (what, err, F32_MAX_ABS)
+    else:
+        rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300)
+        assert rel <= BF16_REL_L2, "%s: rel-L2 %.3e > %.1e (max-abs %.3e)" % (what, rel, BF16_REL_L2, err)
+        assert err <= BF16_MAX_ABS, "%s: max-abs %.3e > %.1e" % (what, err, BF16_MAX_ABS)
+
+
+def lse_tol(dtype: str) -> float:
+    # LogSumExp is an fp32 output on both paths; bf16 inputs are exact in the oracle too, the only
+    # bf16 rounding inside the kernels (P before the PV product) does not touch it.
+    return 2e-5 if dtype == "f32" else 2e-4
+
+
+class HostArrays:
+    """fp32 host copies (exact) of one request's tensors, made once."""
+
+    def __init__(self, r: W.RequestData):
+        n = W.to_numpy_f32
+        self.q_prefix, self.k_prefix, self.v_prefix = n(r.q_prefix), n(r.k_prefix), n(r.v_prefix)
+        self.q_ctx, self.k_ctx, self.v_ctx = n(r.q_ctx), n(r.k_ctx), n(r.v_ctx)
+        self.q_self, self.k_self, self.v_self = n(r.q_self), n(r.k_self), n(r.v_self)
+        self.chunk_lens = list(r.chunk_lens)
+
+
+def make_binding_request(r: W.RequestData, self_len: int, separate_buffers: bool = False,
+                         order=None) -> B.Request:
+    ks, vs = r.chunk_views()
+    if separate_buffers:
+        ks = [k.clone() for k in ks]
+        vs = [v.clone() for v in vs]
+    if order is not None:
+        ks = [ks[i] for i in order]
+        vs = [vs[i] for i in order]
+    lp = r.k_prefix.shape[0]
+    return B.Request(k_prefix=r.k_prefix if lp else None, v_prefix=r.v_prefix if lp else None,
+                     k_chunks=ks, v_chunks=vs, k_self=r.k_self, v_self=r.v_self, self_len=self_len,
+                     temperature=r.temperature, scale=r.scale)
+
+
+def poisoned_workspace(nbytes: int, device) -> torch.Tensor:
+    """Workspace filled with NaN: a kernel that reads a partial nobody wrote shows up at once."""
+    n = max(1, (nbytes + 3) // 4)
+    return torch.full((n,), float("nan"), dtype=torch.float32, device=device)
+
+
+def run_prefill(spec: W.WorkloadSpec, r: W.RequestData, q_len: int, self_len: int, generic=False, req=None,
+                want_lse=True):
+    dev = r.k_self.device
+    shape = B.make_shape(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.torch_dtype, generic=generic)
+    req = req or make_binding_request(r, self_len)
+    q = r.q_self[self_len - q_len:self_len].contiguous()
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((spec.n_q_heads, q_len), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
+    ws = poisoned_workspace(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, q_len), dev)
+    B.attention_prefill(shape, req, q, out, lse, ws, self_len=self_len)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def run_decode(spec: W.WorkloadSpec, rs, self_lens, generic=False, reqs=None, want_lse=True):
+    dev = rs[0].k_self.device
+    shape = B.make_shape(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.torch_dtype, generic=generic)
+    reqs = reqs or [make_binding_request(r, sl) for r, sl in zip(rs, self_lens)]
+    q = torch.stack([r.q_self[sl - 1] for r, sl in zip(rs, self_lens)]).contiguous()
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((len(rs), spec.n_q_heads), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
+    ws = poisoned_workspace(B.workspace_bytes(B.APE_OP_DECODE, shape, len(rs), 1), dev)
+    B.attention_decode(shape, reqs, q, out, lse, ws, self_lens=list(self_lens))
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def run_encode(spec: W.WorkloadSpec, r: W.RequestData, generic=False, with_prefix_rows=True, want_lse=True):
+    dev = r.k_ctx.device
+    shape = B.make_shape(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.torch_dtype, generic=generic)
+    cu = [0]
+    for li in r.chunk_lens:
+        cu.append(cu[-1] + li)
+    cu_dev = torch.tensor(cu, dtype=torch.int32, device=dev)
+    lp = r.k_prefix.shape[0]
+    o_ctx = torch.full_like(r.q_ctx, float("nan"))
+    lse_ctx = torch.full((spec.n_q_heads, cu[-1]), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
+    do_prefix = with_prefix_rows and lp > 0
+    o_p = torch.full_like(r.q_prefix, float("nan")) if do_prefix else None
+    lse_p = torch.full((spec.n_q_heads, lp), float("nan"), dtype=torch.float32, device=dev) if (do_prefix and want_lse) else None
+    B.encode_chunks(shape, r.q_prefix if do_prefix else None, r.k_prefix if lp else None, r.v_prefix if lp else None,
+                    r.q_ctx, r.k_ctx, r.v_ctx, cu, cu_dev, o_p, o_ctx, lse_p, lse_ctx)
+    torch.cuda.synchronize()
+    return o_ctx, lse_ctx, o_p, lse_p
+
+
+def oracle_prefill(h: HostArrays, q_len, self_len, T, S, pairs=None, form="weights"):
+    return ape_oracle.attention(h.q_self[self_len - q_len:self_len], h.k_prefix, h.v_prefix, h.k_ctx, h.v_ctx,
+                                h.chunk_lens, h.k_self[:self_len], h.v_self[:self_len], T, S, pairs=pairs, form=form)
+
+
+def oracle_encode(h: HostArrays, pairs=None):
+    return ape_oracle.encode(h.q_ctx, h.k_prefix, h.v_prefix, h.k_ctx, h.v_ctx, h.chunk_lens, pairs=pairs)
+
+
+def oracle_encode_prefix(h: HostArrays):
+    return ape_oracle.encode(h.q_prefix, None, None, h.k_prefix, h.v_prefix, [h.k_prefix.shape[0]])
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)

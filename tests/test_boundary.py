@@ -1,0 +1,126 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+public header declares, sizes workspaces, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_05431_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "ape.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ape_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    names = header_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert re.match(rb"\d+\.\d+\.\d+", lib.ape_version())
+
+
+def test_status_strings():
+    lib = B.load()
+    for code in (0, -1, -2, -3, -4):
+        assert lib.ape_status_string(code)
+    assert lib.ape_status_string(-99) == b"unknown status"
+
+
+def test_workspace_bytes():
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    assert B.workspace_bytes(B.APE_OP_ENCODE, sh, 1, 1) == 0
+    d = B.workspace_bytes(B.APE_OP_DECODE, sh, 32, 1)
+    p = B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256)
+    assert d > 0 and p > d
+    assert d % 256 == 0 and p % 256 == 0
+    # decode ignores q_len, prefill ignores batch
+    assert B.workspace_bytes(B.APE_OP_DECODE, sh, 32, 77) == d
+    assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 9, 256) == p
+    bad = B.make_shape(32, 7, 128, B.APE_BF16)
+    assert B.workspace_bytes(B.APE_OP_DECODE, bad, 1, 1) == 0
+    assert B.workspace_bytes(99, sh, 1, 1) == 0
+
+
+FAKE = 0x1000  # never dereferenced: every call below fails validation before any launch
+
+
+def _req(**kw):
+    r = B.ApeRequest()
+    r.k_prefix = FAKE; r.v_prefix = FAKE; r.prefix_len = 4; r.n_chunks = 2
+    r.k_chunks = FAKE; r.v_chunks = FAKE; r.cu_chunk_lens = FAKE; r.total_ctx_len = 64
+    r.self_len = 8; r.k_self = FAKE; r.v_self = FAKE; r.temperature = 0.9; r.scale = 0.9
+    for k, v in kw.items():
+        setattr(r, k, v)
+    return r
+
+
+def _prefill(shape, req, q_len=8, q=FAKE, out=FAKE, ws=None, ws_bytes=0):
+    return B.load().ape_attention_prefill(ctypes.byref(shape), ctypes.byref(req), q, q_len, out, None, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(temperature=0.0), B.APE_ERR_INVALID_ARG),
+    (dict(temperature=float("nan")), B.APE_ERR_INVALID_ARG),
+    (dict(temperature=float("inf")), B.APE_ERR_INVALID_ARG),
+    (dict(scale=-0.5), B.APE_ERR_INVALID_ARG),
+    (dict(scale=float("nan")), B.APE_ERR_INVALID_ARG),
+    (dict(self_len=7), B.APE_ERR_INVALID_ARG),            # fewer self tokens than query rows
+    (dict(prefix_len=-1), B.APE_ERR_INVALID_ARG),
+    (dict(k_prefix=None), B.APE_ERR_INVALID_ARG),
+    (dict(k_chunks=None), B.APE_ERR_INVALID_ARG),
+    (dict(cu_chunk_lens=None), B.APE_ERR_INVALID_ARG),
+    (dict(n_chunks=0), B.APE_ERR_INVALID_ARG),            # context length without chunks
+    (dict(k_self=None), B.APE_ERR_INVALID_ARG),
+    (dict(), B.APE_ERR_WORKSPACE),                        # valid request, no workspace
+])
+def test_prefill_argument_errors(kw, code):
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    assert _prefill(sh, _req(**kw)) == code
+    assert B.load().ape_last_error()
+
+
+def test_shape_errors():
+    r = _req()
+    assert _prefill(B.make_shape(32, 7, 128, B.APE_BF16), r) == B.APE_ERR_INVALID_ARG
+    assert _prefill(B.make_shape(0, 8, 128, B.APE_BF16), r) == B.APE_ERR_INVALID_ARG
+    assert _prefill(B.make_shape(32, 8, 100, B.APE_BF16), r) == B.APE_ERR_UNSUPPORTED
+    assert _prefill(B.make_shape(32, 8, 512, B.APE_BF16), r) == B.APE_ERR_UNSUPPORTED
+    assert _prefill(B.make_shape(32, 8, 128, 7), r) == B.APE_ERR_UNSUPPORTED
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    assert _prefill(sh, r, q_len=0) == B.APE_ERR_INVALID_ARG
+    assert _prefill(sh, r, q=None) == B.APE_ERR_INVALID_ARG
+    assert _prefill(sh, r, ws=FAKE + 4, ws_bytes=1 << 40) == B.APE_ERR_WORKSPACE     # misaligned
+    assert B.load().ape_attention_prefill(None, ctypes.byref(r), FAKE, 8, FAKE, None, None, 0, None) == B.APE_ERR_INVALID_ARG
+
+
+def test_decode_and_encode_argument_errors():
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    arr = (B.ApeRequest * 2)(_req(self_len=1), _req(self_len=0))
+    assert lib.ape_attention_decode(ctypes.byref(sh), arr, 2, FAKE, FAKE, None, None, 0, None) == B.APE_ERR_INVALID_ARG
+    assert b"request 1" in lib.ape_last_error()
+    assert lib.ape_attention_decode(ctypes.byref(sh), arr, 0, FAKE, FAKE, None, None, 0, None) == B.APE_ERR_INVALID_ARG
+    cu = (ctypes.c_int32 * 3)(0, 5, 3)
+    enc = lambda cu_host, cu_dev, **kw: lib.ape_encode_chunks(
+        ctypes.byref(sh), kw.get("q_prefix"), FAKE, FAKE, kw.get("prefix_len", 4), FAKE, FAKE, FAKE,
+        cu_host, cu_dev, 2, kw.get("o_prefix"), FAKE, None, None, None, 0, None)
+    assert enc(ctypes.cast(cu, ctypes.c_void_p), FAKE) == B.APE_ERR_INVALID_ARG        # not non-decreasing
+    assert enc(None, FAKE) == B.APE_ERR_INVALID_ARG
+    cu2 = (ctypes.c_int32 * 3)(0, 5, 9)
+    assert enc(ctypes.cast(cu2, ctypes.c_void_p), None) == B.APE_ERR_INVALID_ARG       # no device copy
+    assert enc(ctypes.cast(cu2, ctypes.c_void_p), FAKE, q_prefix=FAKE) == B.APE_ERR_INVALID_ARG   # q_prefix without o_prefix
+    assert enc(ctypes.cast(cu2, ctypes.c_void_p), FAKE, prefix_len=-2) == B.APE_ERR_INVALID_ARG
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        B.load()

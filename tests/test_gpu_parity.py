@@ -1,0 +1,211 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by
+element, on the same seeded inputs.  Sizes here are the ones the oracle finishes in seconds;
+full-size sampled parity lives in test_gpu_fullsize.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_05431_amd import binding as B
+from paper_2502_05431_amd import workloads as W
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _check_query(spec, r, h, q_len, self_len, generic=False, req=None, what=""):
+    out, lse = H.run_prefill(spec, r, q_len, self_len, generic=generic, req=req)
+    ref, ref_lse, _ = H.oracle_prefill(h, q_len, self_len, r.temperature, r.scale)
+    H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, spec.dtype, what + " prefill out")
+    got_lse = H.f64(lse).T.reshape(-1)                  # [Hq, q_len] -> (row, head) order
+    assert np.abs(got_lse - ref_lse).max() <= H.lse_tol(spec.dtype), what + " prefill lse"
+
+
+def _check_decode(spec, r, h, self_len, generic=False, what=""):
+    out, lse = H.run_decode(spec, [r], [self_len], generic=generic)
+    ref, ref_lse, _ = H.oracle_prefill(h, 1, self_len, r.temperature, r.scale)
+    H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, spec.dtype, what + " decode out")
+    assert np.abs(H.f64(lse).reshape(-1) - ref_lse).max() <= H.lse_tol(spec.dtype), what + " decode lse"
+
+
+def _check_encode(spec, r, h, generic=False, what=""):
+    o_ctx, lse_ctx, o_p, lse_p = H.run_encode(spec, r, generic=generic)
+    ref, ref_lse = H.oracle_encode(h)
+    H.check_close(H.f64(o_ctx).reshape(-1, spec.head_dim), ref, spec.dtype, what + " encode out")
+    assert np.abs(H.f64(lse_ctx).T.reshape(-1) - ref_lse).max() <= H.lse_tol(spec.dtype), what + " encode lse"
+    if o_p is not None:
+        refp, refp_lse = H.oracle_encode_prefix(h)
+        H.check_close(H.f64(o_p).reshape(-1, spec.head_dim), refp, spec.dtype, what + " encode prefix rows")
+        assert np.abs(H.f64(lse_p).T.reshape(-1) - refp_lse).max() <= H.lse_tol(spec.dtype)
+
+
+# ------------------------------------------------------------------ workload 1 (fp32)
+@pytest.mark.parametrize("T,S", [(1.0, 1.0), (0.8, 1.0), (1.0, 0.9), (0.8, 0.9)])
+def test_cfg1_fp32_all_rows(T, S):
+    spec = W.CONFIGS[1].replace(temperature=T, scale=S)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, what="cfg1")
+    _check_query(spec, r, h, spec.q_len, spec.q_len, what="cfg1")
+    for step in range(spec.decode_steps):
+        _check_decode(spec, r, h, spec.q_len + step + 1, what="cfg1 step %d" % step)
+
+
+def test_cfg1_fp32_matches_pooled_not_per_context_scale():
+    """The library implements the pooled scaling factor of the main-text equation; the
+    per-context reading of Appendix C.2 differs by far more than the fp32 tolerance."""
+    spec = W.CONFIGS[1]
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    out, _ = H.run_prefill(spec, r, spec.q_len, spec.q_len)
+    pooled, _, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, form="hier")
+    per_ctx, _, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, form="hier_per_context")
+    got = H.f64(out).reshape(-1, spec.head_dim)
+    assert np.abs(got - pooled).max() <= H.F32_MAX_ABS
+    assert np.abs(got - per_ctx).max() > 100 * H.F32_MAX_ABS
+
+
+def test_fp32_ragged_and_degenerate():
+    base = W.CONFIGS[1]
+    for kw in (dict(chunk_lens=(1, 70, 3, 64, 129)), dict(chunk_lens=()), dict(prefix_len=0),
+               dict(prefix_len=0, chunk_lens=()), dict(chunk_lens=(5,), q_len=1, decode_steps=2),
+               dict(head_dim=40, n_q_heads=6, n_kv_heads=2), dict(head_dim=256, n_q_heads=2, n_kv_heads=2, chunk_lens=(9, 9))):
+        spec = base.replace(**kw)
+        r = W.make_request(spec, DEV)
+        h = H.HostArrays(r)
+        what = "fp32 %s" % (kw,)
+        if spec.chunk_lens:
+            _check_encode(spec, r, h, what=what)
+        _check_query(spec, r, h, spec.q_len, spec.q_len, what=what)
+        _check_decode(spec, r, h, spec.self_len_max, what=what)
+
+
+# ------------------------------------------------------------------ bf16, generic kernels
+def test_bf16_generic_small():
+    spec = W.CONFIGS[1].replace(dtype="bf16", chunk_lens=(33, 64, 7), q_len=20)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, what="bf16 d64")
+    _check_query(spec, r, h, spec.q_len, spec.q_len, what="bf16 d64")
+    _check_decode(spec, r, h, spec.self_len_max, what="bf16 d64")
+
+
+# ------------------------------------------------------------------ bf16, matrix-core kernels
+SMALL_MFMA = [
+    dict(chunk_lens=(64, 64), q_len=64, prefix_len=32),                       # exact tiles
+    dict(chunk_lens=(100, 1, 65, 300, 31), q_len=50, prefix_len=7, k_scale=1.0),   # ragged everything, peaky scores
+    dict(chunk_lens=(130,), q_len=1, prefix_len=0, decode_steps=3),           # no prefix, single row
+    dict(chunk_lens=(), q_len=70, prefix_len=40),                             # no context
+    dict(chunk_lens=(257, 255), q_len=96, prefix_len=32, n_q_heads=8, n_kv_heads=8),    # G = 1
+    dict(chunk_lens=(257, 255), q_len=33, prefix_len=32, n_q_heads=16, n_kv_heads=8),   # G = 2
+    dict(chunk_lens=(200, 90), q_len=40, prefix_len=5, n_q_heads=16, n_kv_heads=2),     # G = 8
+    dict(chunk_lens=(512,) * 3, q_len=130, prefix_len=32, decode_steps=70, k_scale=1.0),   # several q tiles, long self
+]
+
+
+@pytest.mark.parametrize("kw", SMALL_MFMA, ids=[str(i) for i in range(len(SMALL_MFMA))])
+def test_bf16_mfma_small_shapes(kw):
+    kw = dict(kw)
+    spec = W.CONFIGS[2].replace(decode_steps=kw.pop("decode_steps", 5), **kw)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    what = "mfma %s" % (kw,)
+    if spec.chunk_lens:
+        _check_encode(spec, r, h, what=what)
+    _check_query(spec, r, h, spec.q_len, spec.q_len, what=what)
+    # query rows in the middle of a longer self KV (chunked prefill of the query)
+    if spec.q_len > 8:
+        _check_query(spec, r, h, spec.q_len - 7, spec.q_len, what=what + " offset")
+    for sl in {spec.q_len + 1, spec.self_len_max}:
+        _check_decode(spec, r, h, sl, what=what)
+
+
+def test_cfg2_rag_bf16_all_rows():
+    spec = W.CONFIGS[2]
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, what="cfg2")
+    _check_query(spec, r, h, spec.q_len, spec.q_len, what="cfg2")
+    for step in (0, 1, 100, 255):
+        _check_decode(spec, r, h, spec.q_len + step + 1, what="cfg2 step %d" % step)
+
+
+def test_cfg2_generic_path_agrees():
+    """The portable kernels on the same bf16 workload (cross-check of the two GPU paths through
+    the oracle, each to the bf16 tolerance)."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(512,) * 4, q_len=32)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, generic=True, what="cfg2 generic")
+    _check_query(spec, r, h, spec.q_len, spec.q_len, generic=True, what="cfg2 generic")
+    _check_decode(spec, r, h, spec.q_len + 3, generic=True, what="cfg2 generic")
+
+
+def test_values_all_ones_rows_sum_to_one():
+    """Rows of Eq.5 sum to 1: with all-ones values the output is all-ones (holds at any size)."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(512,) * 8, q_len=64)
+    r = W.make_request(spec, DEV)
+    for name in ("v_prefix", "v_ctx", "v_self"):
+        getattr(r, name).fill_(1.0)
+    out, _ = H.run_prefill(spec, r, spec.q_len, spec.q_len)
+    assert (H.f64(out) - 1.0).__abs__().max() <= 2 ** -8          # one bf16 ulp at 1.0
+    out, _ = H.run_decode(spec, [r], [spec.q_len + 1])
+    assert (H.f64(out) - 1.0).__abs__().max() <= 2 ** -8
+    o_ctx, _, o_p, _ = H.run_encode(spec, r)
+    assert (H.f64(o_ctx) - 1.0).__abs__().max() <= 2 ** -8
+    assert (H.f64(o_p) - 1.0).__abs__().max() <= 2 ** -8
+
+
+def test_chunk_table_order_and_separate_buffers():
+    """Contexts live in separately allocated buffers reached through the table; permuting the
+    table leaves the result unchanged within tolerance (Eq.5 is a sum over contexts)."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(300, 512, 64, 700, 129), q_len=48)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    ref, _, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale)
+    for order in (None, [3, 0, 4, 2, 1]):
+        req = H.make_binding_request(r, spec.q_len, separate_buffers=True, order=order)
+        out, _ = H.run_prefill(spec, r, spec.q_len, spec.q_len, req=req)
+        H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, "bf16", "order %s" % (order,))
+        reqd = H.make_binding_request(r, spec.q_len + 2, separate_buffers=True, order=order)
+        outd, _ = H.run_decode(spec, [r], [spec.q_len + 2], reqs=[reqd])
+        refd, _, _ = H.oracle_prefill(h, 1, spec.q_len + 2, r.temperature, r.scale)
+        H.check_close(H.f64(outd).reshape(-1, spec.head_dim), refd, "bf16", "decode order %s" % (order,))
+
+
+def test_batched_decode_mixed_requests():
+    """Requests of different context sizes, T and S in one decode call (more than one launch's
+    worth of descriptors)."""
+    base = W.CONFIGS[5].replace(batch=35, decode_steps=9)
+    rs, hs, lens = [], [], []
+    for b in range(base.batch):
+        n_chunks = 1 + b % 4
+        spec = base.replace(chunk_lens=tuple(64 + 37 * ((b + i) % 5) for i in range(n_chunks)), prefix_len=(b % 3) * 16)
+        r = W.make_request(spec, DEV, request=b)
+        rs.append(r); hs.append(H.HostArrays(r)); lens.append(1 + b % 9)
+    out, lse = H.run_decode(base, rs, lens)
+    for b, (r, h) in enumerate(zip(rs, hs)):
+        ref, ref_lse, _ = H.oracle_prefill(h, 1, lens[b], r.temperature, r.scale)
+        H.check_close(H.f64(out[b]), ref, "bf16", "request %d" % b)
+        assert np.abs(H.f64(lse[b]) - ref_lse).max() <= H.lse_tol("bf16")
+
+
+def test_errors_leave_outputs_untouched():
+    spec = W.CONFIGS[2].replace(chunk_lens=(64,), q_len=8)
+    r = W.make_request(spec, DEV)
+    shape = B.make_shape(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.torch_dtype)
+    req = H.make_binding_request(r, spec.q_len)
+    q = r.q_self[:spec.q_len].contiguous()
+    out = torch.full_like(q, 7.0)
+    small = torch.zeros(64, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.ApeError) as e:
+        B.attention_prefill(shape, req, q, out, None, small)
+    assert e.value.status == B.APE_ERR_WORKSPACE
+    req.temperature = 0.0
+    ws = H.poisoned_workspace(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, spec.q_len), DEV)
+    with pytest.raises(B.ApeError) as e:
+        B.attention_prefill(shape, req, q, out, None, ws)
+    assert e.value.status == B.APE_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert (out == 7.0).all()
