@@ -1,0 +1,217 @@
+"""Benchmark of the APE attention hot path on one MI355X.
+
+A "step" is one pass of the whole path over the 128K-context workload (benchmark config 3,
+the configuration the headline metric is quoted on): ``ape_encode_chunks`` over 64 chunks x 2048
+tokens with the shared 32-token prefix, ``ape_attention_prefill`` of a 256-token query over the
+131K cached KV, then ``--decode-steps`` single-token ``ape_attention_decode`` steps over the same
+cache.  All inputs are synthetic, seeded and resident in HBM before the timed region.
+
+Printed: ONE JSON line.  ``value`` = algorithmic FLOPs of the whole step / step time.  Per-phase
+figures (prefill TFLOP/s = the headline, decode GB/s, and the batched-decode workload of config
+5 timed in a region of its own) are in ``phases``.  ``roofline`` describes the kernel that
+dominates the step's time; ``cpu_baseline`` is the fp64 oracle timed on the host cores on a
+bounded sample of the same workload.
+
+FLOP convention: 4*head_dim per unmasked (query, key) pair per query head.  Byte convention for
+decode: every cached K and V element once + Q and O.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
+# same counters' reading for a copy kernel of known size; see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": None, "flash_prefill_kernel": None, "decode_kernel": None}
+
+
+def pair_counts(spec):
+    """Unmasked (query, key) pairs per query head for the phases of one step."""
+    lp, m, lq = spec.prefix_len, spec.total_ctx_len, spec.q_len
+    enc = sum(li * (li + 1) // 2 + li * lp for li in spec.chunk_lens)
+    pre = lq * (lp + m) + lq * (lq + 1) // 2
+    return enc, pre
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--decode-steps", type=int, default=8, help="decode steps per step over the 128K cache")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cfg5", action="store_true", help="skip the batched-decode (config 5) region")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
+              "in this path)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2502_05431_amd import binding as B
+    from paper_2502_05431_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B.load()
+
+    spec = W.CONFIGS[3].replace(decode_steps=args.decode_steps)
+    r = W.make_request(spec, dev)
+    hq, hkv, d = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
+    shape = B.make_shape(hq, hkv, d, spec.torch_dtype)
+    cu = [0]
+    for li in r.chunk_lens:
+        cu.append(cu[-1] + li)
+    cu_dev = torch.tensor(cu, dtype=torch.int32, device=dev)
+    ks, vs = r.chunk_views()
+    req = B.Request(r.k_prefix, r.v_prefix, ks, vs, r.k_self, r.v_self, spec.q_len, r.temperature, r.scale)
+    o_ctx = torch.empty_like(r.q_ctx)
+    q = r.q_self[:spec.q_len].contiguous()
+    out = torch.empty_like(q)
+    ws = torch.empty(max(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, spec.q_len),
+                         B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1)) // 4, dtype=torch.float32, device=dev)
+    qd = [r.q_self[spec.q_len + i:spec.q_len + i + 1].contiguous() for i in range(args.decode_steps)]
+    outd = torch.empty_like(qd[0]) if qd else None
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        B.encode_chunks(shape, None, r.k_prefix, r.v_prefix, r.q_ctx, r.k_ctx, r.v_ctx, cu, cu_dev, None, o_ctx)
+        if ev: ev[1].record()
+        B.attention_prefill(shape, req, q, out, None, ws)
+        if ev: ev[2].record()
+        for i in range(args.decode_steps):
+            B.attention_decode(shape, [req], qd[i], outd, None, ws, self_lens=[spec.q_len + i + 1])
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    ph = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in events])      # ms
+    ms_enc, ms_pre, ms_dec = ph.mean(axis=0)
+
+    enc_pairs, pre_pairs = pair_counts(spec)
+    fl_enc, fl_pre = 4.0 * d * hq * enc_pairs, 4.0 * d * hq * pre_pairs
+    kv_row_bytes = 2 * hkv * d * 2
+    dec_tokens = [spec.prefix_len + spec.total_ctx_len + spec.q_len + i + 1 for i in range(args.decode_steps)]
+    fl_dec = sum(4.0 * d * hq * t for t in dec_tokens)
+    by_dec = sum(kv_row_bytes * t + 2 * hq * d * 2 for t in dec_tokens)
+    value = (fl_enc + fl_pre + fl_dec) / (ms_step * 1e-3) / 1e12
+
+    phases = {
+        "encode": {"ms": float(ms_enc), "tflops": fl_enc / (ms_enc * 1e-3) / 1e12, "frac_mfma_peak": fl_enc / (ms_enc * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "prefill": {"ms": float(ms_pre), "tflops": fl_pre / (ms_pre * 1e-3) / 1e12, "frac_mfma_peak": fl_pre / (ms_pre * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                    "note": "flash kernel + merge kernel"},
+    }
+    if args.decode_steps:
+        phases["decode_128k_batch1"] = {"ms_per_token": float(ms_dec) / args.decode_steps,
+                                        "gbs": by_dec / (ms_dec * 1e-3) / 1e9, "frac_hbm_peak": by_dec / (ms_dec * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                        "note": "538 MB of KV per token, batch 1"}
+
+    # the kernel that dominates the step
+    if ms_enc >= ms_pre and ms_enc >= ms_dec:
+        roof = {"kernel": "flash_encode_kernel", "bound": "mfma", "achieved": fl_enc / (ms_enc * 1e-3) / 1e12,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    elif ms_pre >= ms_dec:
+        roof = {"kernel": "flash_prefill_kernel", "bound": "mfma", "achieved": fl_pre / (ms_pre * 1e-3) / 1e12,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roof = {"kernel": "decode_kernel", "bound": "hbm", "achieved": by_dec / (ms_dec * 1e-3) / 1e9,
+                "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(roof["kernel"])
+    roof["launch_ms"] = float({"flash_encode_kernel": ms_enc, "flash_prefill_kernel": ms_pre, "decode_kernel": ms_dec / max(1, args.decode_steps)}[roof["kernel"]])
+
+    # ---- batched decode (config 5): the clean HBM measurement, timed in its own region
+    if not args.no_cfg5:
+        spec5 = W.CONFIGS[5]
+        rs = [W.make_request(spec5, dev, request=b) for b in range(spec5.batch)]
+        reqs = []
+        for rr in rs:
+            k5, v5 = rr.chunk_views()
+            reqs.append(B.Request(rr.k_prefix, rr.v_prefix, k5, v5, rr.k_self, rr.v_self, 1, rr.temperature, rr.scale))
+        q5 = torch.stack([rr.q_self for rr in rs], dim=1).contiguous()          # [steps, batch, Hq, d]
+        o5 = torch.empty_like(q5[0])
+        ws5 = torch.empty(B.workspace_bytes(B.APE_OP_DECODE, shape, spec5.batch, 1) // 4, dtype=torch.float32, device=dev)
+
+        def decode_pass():
+            for s in range(spec5.decode_steps):
+                B.attention_decode(shape, reqs, q5[s], o5, None, ws5, self_lens=[s + 1] * spec5.batch)
+        decode_pass()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        e0.record()
+        for _ in range(reps):
+            decode_pass()
+        e1.record()
+        torch.cuda.synchronize()
+        ms5 = e0.elapsed_time(e1) / reps
+        tok5 = [spec5.batch * (spec5.prefix_len + spec5.total_ctx_len + s + 1) for s in range(spec5.decode_steps)]
+        by5 = sum(kv_row_bytes * t + spec5.batch * 2 * hq * d * 2 for t in tok5)
+        phases["decode_cfg5_batch32"] = {"ms_per_step": ms5 / spec5.decode_steps, "gbs": by5 / (ms5 * 1e-3) / 1e9,
+                                         "frac_hbm_peak": by5 / (ms5 * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                         "note": "32 requests x 16.4K KV tokens, 128 steps, 2.15 GB per step"}
+        del rs, reqs, q5, o5, ws5
+
+    # ---- the oracle beside it, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ape_oracle
+        n = W.to_numpy_f32
+        kc, vc, kp, vp = n(r.k_ctx), n(r.v_ctx), n(r.k_prefix), n(r.v_prefix)
+        ksf, vsf, qs = n(r.k_self[:spec.q_len]), n(r.v_self[:spec.q_len]), n(q)
+        rng = np.random.default_rng(0)
+
+        def sample(n_pairs):
+            pairs = [(int(rng.integers(spec.q_len)), int(rng.integers(hq))) for _ in range(n_pairs)]
+            t = time.perf_counter()
+            ape_oracle.attention(qs, kp, vp, kc, vc, r.chunk_lens, ksf, vsf, r.temperature, r.scale, pairs=pairs)
+            dt = time.perf_counter() - t
+            fl = sum(4.0 * d * (spec.prefix_len + spec.total_ctx_len + row + 1) for row, _ in pairs)
+            return dt, fl
+        threads = ape_oracle.num_threads()
+        dt, fl = sample(2 * threads)                                    # calibration
+        n_pairs = int(max(2 * threads, min(8192, args.cpu_seconds / max(dt, 1e-3) * 2 * threads)))
+        dt, fl = sample(n_pairs)
+        cpu = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+               "sample": "%d random (row, head) pairs of the config-3 query prefill, each over its full 131K KV, fp64, %.1f s" % (n_pairs, dt)}
+
+    line = {
+        "metric": "APE attn TFLOP/s (query prefill over 128K cached KV) + decode HBM GB/s",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 3: 128K context (64 chunks x 2048 + prefix 32), Llama-3-8B heads (32q/8kv, d=128), "
+                               "encode + 256-row query prefill + %d decode steps, T=0.8 S=0.85, batch 1" % args.decode_steps,
+                   "seed": r.seed, "generator": r.generator},
+        "headline_prefill_tflops": phases["prefill"]["tflops"],
+        "headline_decode_gbs": phases.get("decode_cfg5_batch32", {}).get("gbs"),
+        "phases": phases, "roofline": roof, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,106 @@
+"""GPU parity at the full benchmark sizes (configs 3, 4, 5), in the launch configuration bench.py
+times.  The oracle computes sampled outputs one by one -- each sampled (row, head) pair exactly,
+over its full KV -- always including first/last rows and heads and rows at tile and chunk
+boundaries; size-independent properties cover the rest."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_05431_amd import workloads as W
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _pairs(rng, n_rows, n_heads, n, must_rows=()):
+    rows = {0, n_rows - 1, *[r for r in must_rows if 0 <= r < n_rows]}
+    pairs = [(r, h) for r in sorted(rows) for h in (0, n_heads - 1)]
+    while len(pairs) < n:
+        pairs.append((int(rng.integers(n_rows)), int(rng.integers(n_heads))))
+    return pairs
+
+
+def _gather(t: torch.Tensor, pairs, head_major=False):
+    if head_major:                                         # [Hq, rows]
+        return np.array([float(t[h, r]) for r, h in pairs])
+    return np.stack([t[r, h].float().cpu().numpy().astype(np.float64) for r, h in pairs])
+
+
+def test_cfg3_128k_encode_and_prefill_sampled():
+    spec = W.CONFIGS[3]
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    rng = np.random.default_rng(3)
+
+    # query prefill: 256 rows over the 131K cached KV
+    out, lse = H.run_prefill(spec, r, spec.q_len, spec.q_len)
+    pairs = _pairs(rng, spec.q_len, spec.n_q_heads, 384, must_rows=(63, 64, 127, 128, 191, 192))
+    ref, ref_lse, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, pairs=pairs)
+    H.check_close(_gather(out, pairs), ref, "bf16", "cfg3 prefill")
+    assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(out.float()).all()
+
+    # encode: 64 chunks x 2048 rows; sample rows at chunk starts/ends and tile edges
+    o_ctx, lse_ctx, o_p, _ = H.run_encode(spec, r)
+    m = spec.total_ctx_len
+    must = [0, 1, 63, 64, 2047, 2048, 2049, 4095, 4096, m - 2048, m - 2047, m - 1, 2048 * 17 + 1023, 2048 * 40 + 64]
+    pairs = _pairs(rng, m, spec.n_q_heads, 512, must_rows=must)
+    ref, ref_lse = H.oracle_encode(h, pairs=pairs)
+    H.check_close(_gather(o_ctx, pairs), ref, "bf16", "cfg3 encode")
+    assert np.abs(_gather(lse_ctx, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(o_ctx.float()).all()
+    refp, _ = H.oracle_encode_prefix(h)
+    H.check_close(H.f64(o_p).reshape(-1, spec.head_dim), refp, "bf16", "cfg3 prefix rows")
+
+
+def test_cfg3_rows_sum_to_one_at_full_size():
+    spec = W.CONFIGS[3]
+    r = W.make_request(spec, DEV)
+    for name in ("v_prefix", "v_ctx", "v_self"):
+        getattr(r, name).fill_(1.0)
+    out, _ = H.run_prefill(spec, r, spec.q_len, spec.q_len)
+    assert (out.float() - 1.0).abs().max().item() <= 2 ** -8
+    o_ctx, _, _, _ = H.run_encode(spec, r, with_prefix_rows=False, want_lse=False)
+    assert (o_ctx.float() - 1.0).abs().max().item() <= 2 ** -8
+
+
+def test_cfg4_manyshot_prefill_and_decode_sampled():
+    spec = W.CONFIGS[4]
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    rng = np.random.default_rng(4)
+    out, lse = H.run_prefill(spec, r, spec.q_len, spec.q_len)
+    pairs = _pairs(rng, spec.q_len, spec.n_q_heads, 256, must_rows=(31, 32, 63, 64))
+    ref, ref_lse, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, pairs=pairs)
+    H.check_close(_gather(out, pairs), ref, "bf16", "cfg4 prefill")
+    assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    for step in (0, 63):
+        sl = spec.q_len + step + 1
+        outd, lsed = H.run_decode(spec, [r], [sl])
+        refd, refd_lse, _ = H.oracle_prefill(h, 1, sl, r.temperature, r.scale)
+        H.check_close(H.f64(outd).reshape(-1, spec.head_dim), refd, "bf16", "cfg4 decode step %d" % step)
+        assert np.abs(H.f64(lsed).reshape(-1) - refd_lse).max() <= H.lse_tol("bf16")
+    # encode of 512 short chunks
+    o_ctx, _, _, _ = H.run_encode(spec, r, with_prefix_rows=False, want_lse=False)
+    m = spec.total_ctx_len
+    pairs = _pairs(rng, m, spec.n_q_heads, 256, must_rows=(255, 256, 257, m - 256, 256 * 300 + 63, 256 * 300 + 64))
+    ref, _ = H.oracle_encode(h, pairs=pairs)
+    H.check_close(_gather(o_ctx, pairs), ref, "bf16", "cfg4 encode")
+
+
+def test_cfg5_batched_decode_all_outputs():
+    """32 requests x 16.4K KV tokens, per-request T and S: every (request, head) output at the
+    first, a middle and the last decode step."""
+    spec = W.CONFIGS[5]
+    rs = [W.make_request(spec, DEV, request=b) for b in range(spec.batch)]
+    assert len({round(r.temperature, 4) for r in rs}) > 8 and len({round(r.scale, 4) for r in rs}) > 8
+    for step in (0, 64, 127):
+        sl = step + 1
+        out, lse = H.run_decode(spec, rs, [sl] * spec.batch)
+        for b in (range(spec.batch) if step == 127 else (0, 13, 31)):
+            h = H.HostArrays(rs[b])
+            ref, ref_lse, _ = H.oracle_prefill(h, 1, sl, rs[b].temperature, rs[b].scale)
+            H.check_close(H.f64(out[b]), ref, "bf16", "cfg5 request %d step %d" % (b, step))
+            assert np.abs(H.f64(lse[b]) - ref_lse).max() <= H.lse_tol("bf16")
