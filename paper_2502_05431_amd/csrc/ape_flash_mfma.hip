@@ -7,148 +7,166 @@
 // the pooled context LogSumExp (Appendix C.3/C.4).
 //
 // Tiling (wave64, MFMA 32x32x16 bf16):
-//   - a workgroup = 4 wavefronts; a wavefront owns RB blocks of 32 query rows, where a "row" is
-//     a (query token, head of the GQA group) pair, so the G query heads that share a KV head
-//     also share every K/V tile staged in LDS;
-//   - keys/values are streamed in tiles of 64 tokens through a double-buffered LDS stage
-//     (16-byte coalesced global loads -> registers -> XOR-swizzled LDS rows of 256 bytes);
+//   - a workgroup = 4 wavefronts, one per SIMD; a wavefront owns RB blocks of 32 query rows,
+//     where a "row" is a (query token, head of the GQA group) pair, so the G query heads that
+//     share a KV head also share every K/V block staged in LDS;
+//   - keys/values stream in blocks of 32 tokens through a ring of LDS slots filled by direct
+//     global->LDS loads (16 bytes per lane, no staging registers), several blocks ahead of the
+//     compute; rows are 256 bytes and XOR-swizzled so that every LDS read is conflict-free;
 //   - scores are computed TRANSPOSED, S^T = K Q^T: the accumulator layout then puts one query
 //     row in one lane (and its partner lane +32), so the softmax row reductions are in-lane,
 //     and the bf16 probabilities are already laid out as the B operand of O^T += V^T P^T;
-//   - V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16.
+//   - V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16;
+//   - the loop is software-pipelined: while the vector ALUs run the softmax of block j, the
+//     matrix cores run O += P V of block j-1 and K Q^T of block j+1.
 #include "ape_internal.h"
 
 #include <math.h>
+
+#include <type_traits>
 
 namespace ape {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
 
 constexpr int D = 128;                       // head_dim
-constexpr int BN = 64;                       // KV tokens per LDS tile
-constexpr int TB = BN / 32;                  // 32-token blocks per tile
+constexpr int BLK = 32;                      // KV tokens per block
 constexpr int NT = 256;                      // threads per workgroup
 constexpr int NW = NT / 64;                  // wavefronts
 constexpr int ROWB = D * 2;                  // bytes of one head's K or V row
-constexpr int TILEB = BN * ROWB;             // 16 KB
-constexpr int STAGEB = 2 * TILEB;            // K tile + V tile
-constexpr int LDSB = 2 * STAGEB;             // double buffer: 64 KB
-constexpr int LD_PER_THREAD = BN * 16 / NT;  // 16-byte pieces per thread per tile (4)
+constexpr int KVB = BLK * ROWB;              // 8 KB: one block of K (or V) rows
+constexpr int SLOTB = 2 * KVB;               // K rows then V rows
+constexpr int RING = 6;                      // LDS slots: blocks j, j+1 in use, 4 more in flight
+constexpr int LDSB = RING * SLOTB;           // 96 KB
+constexpr int LOADS_PER_BLOCK = 4;           // direct-to-LDS load instructions per wavefront per block
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr float kLazy = 8.f;                 // the reference maximum moves only when exceeded by 2^kLazy
 
-typedef __attribute__((address_space(3))) char lds_char;
-
-// One KV tile: n_valid (1..BN) consecutive tokens of one segment.
-struct Tile {
-    const char* k;        // row 0 of the tile for this KV head
+// One KV block: n_valid (1..32) consecutive tokens of one segment.
+struct Block {
+    const char* k;        // row 0 of the block for this KV head
     const char* v;
     int n_valid;
     int j0;               // index of row 0 inside the causal segment, or -1 (no causal mask)
 };
 
-// Walks the pooled contexts [t0, t1) through the chunk table; tiles stop at chunk ends.
-struct CtxWalk {
-    const KvView* kv;
-    long t, t1, c0, c1;
-    int c;
-    long stride_b, head_b;
-    __device__ void init(const KvView* kv_, long t0_, long t1_, long stride_b_, long head_b_) {
-        kv = kv_; t = t0_; t1 = t1_; stride_b = stride_b_; head_b = head_b_;
+// Block source of one workgroup.  Two modes share one type (and therefore one instantiation of
+// the pipeline): a range [t, t1) of the pooled contexts walked through the chunk table (blocks
+// stop at chunk ends, no mask), or a plain segment (the prefix, no mask) followed by a causal
+// segment (self KV / own chunk).
+struct Walk {
+    // context mode (cu != NULL)
+    const int32_t* cu;
+    const void* const* k_chunks;
+    const void* const* v_chunks;
+    int n_chunks, c;
+    long t, t1, c0, c1, head_b;
+    // sequence mode
+    const char *kp, *vp, *kc, *vc;
+    int np, nc, j, phase;
+    long stride_b;
+
+    __device__ void init_ctx(const KvView& kv, long t0_, long t1_, long stride_b_, long head_b_) {
+        cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
+        t = t0_; t1 = t1_; stride_b = stride_b_; head_b = head_b_;
         c = 0; c0 = 0; c1 = 0;
-        if (t < t1) {
-            int lo = 0, hi = kv->n_chunks - 1;
+        kp = vp = kc = vc = nullptr; np = nc = j = 0; phase = 2;
+        if (t < t1 && cu != nullptr) {
+            int lo = 0, hi = n_chunks - 1;
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (kv->cu[mid] <= t) lo = mid; else hi = mid - 1;
+                if (cu[mid] <= t) lo = mid; else hi = mid - 1;
             }
-            c = lo; c0 = kv->cu[c]; c1 = kv->cu[c + 1];
+            c = lo; c0 = cu[c]; c1 = cu[c + 1];
+        } else {
+            t1 = t;
         }
     }
-    __device__ bool next(Tile& tile) {
-        if (t >= t1) return false;
-        while (t >= c1) {                                          // next non-empty chunk
-            if (c + 1 >= kv->n_chunks) { t = t1; return false; }   // table shorter than total_ctx: stop, stay in bounds
-            ++c; c0 = c1; c1 = kv->cu[c + 1];
-        }
-        const long e = c1 < t1 ? c1 : t1;
-        const int n = (int)(e - t < BN ? e - t : BN);
-        tile.k = (const char*)kv->k_chunks[c] + (t - c0) * stride_b + head_b;
-        tile.v = (const char*)kv->v_chunks[c] + (t - c0) * stride_b + head_b;
-        tile.n_valid = n; tile.j0 = -1;
-        t += n;
-        return true;
-    }
-};
-
-// Walks a plain segment (the prefix, no mask) and then a causal segment (self KV / own chunk).
-struct SeqWalk {
-    const char* kp; const char* vp; int np;      // prefix rows
-    const char* kc; const char* vc; int nc;      // causal rows visible to this workgroup
-    int j; int phase;
-    long stride_b;
-    __device__ void init(const char* kp_, const char* vp_, int np_, const char* kc_, const char* vc_, int nc_, long stride_b_) {
+    __device__ void init_seq(const char* kp_, const char* vp_, int np_, const char* kc_, const char* vc_, int nc_, long stride_b_) {
+        cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = c = 0; t = t1 = c0 = c1 = head_b = 0;
         kp = kp_; vp = vp_; np = np_; kc = kc_; vc = vc_; nc = nc_; stride_b = stride_b_;
         j = 0; phase = np > 0 ? 0 : 1;
     }
-    __device__ bool next(Tile& tile) {
+    __device__ bool next(Block& b) {
+        if (cu != nullptr) {
+            if (t >= t1) return false;
+            while (t >= c1) {                                          // next non-empty chunk
+                if (c + 1 >= n_chunks) { t = t1; return false; }       // table shorter than total_ctx: stop, stay in bounds
+                ++c; c0 = c1; c1 = cu[c + 1];
+            }
+            const long e = c1 < t1 ? c1 : t1;
+            const int n = (int)(e - t < BLK ? e - t : BLK);
+            b.k = (const char*)k_chunks[c] + (t - c0) * stride_b + head_b;
+            b.v = (const char*)v_chunks[c] + (t - c0) * stride_b + head_b;
+            b.n_valid = n; b.j0 = -1;
+            t += n;
+            return true;
+        }
         if (phase == 0) {
-            const int n = np - j < BN ? np - j : BN;
-            tile.k = kp + (long)j * stride_b; tile.v = vp + (long)j * stride_b; tile.n_valid = n; tile.j0 = -1;
+            const int n = np - j < BLK ? np - j : BLK;
+            b.k = kp + (long)j * stride_b; b.v = vp + (long)j * stride_b; b.n_valid = n; b.j0 = -1;
             j += n;
             if (j >= np) { phase = 1; j = 0; }
             return true;
         }
-        if (j >= nc) return false;
-        const int n = nc - j < BN ? nc - j : BN;
-        tile.k = kc + (long)j * stride_b; tile.v = vc + (long)j * stride_b; tile.n_valid = n; tile.j0 = j;
+        if (phase != 1 || j >= nc) return false;
+        const int n = nc - j < BLK ? nc - j : BLK;
+        b.k = kc + (long)j * stride_b; b.v = vc + (long)j * stride_b; b.n_valid = n; b.j0 = j;
         j += n;
         return true;
     }
 };
 
-struct Staged { u32x4 k[LD_PER_THREAD]; u32x4 v[LD_PER_THREAD]; };
-
-// 16-byte pieces: piece id = i*NT + tid -> (row = id / 16, chunk = id % 16); rows past n_valid are zero.
-__device__ __forceinline__ void load_tile(const Tile& t, long stride_b, Staged& s) {
-    const int tid = threadIdx.x;
+// LDS layout of a block: K row r at r*256, 16-byte chunk index XOR (r & 15) (conflict-free 16-byte
+// reads down a column of rows); V row r at 8192 + r*256, chunk index XOR 4*(r & 3) (the four rows
+// of one transposing read land in distinct 64-byte windows).
+//
+// Direct global->LDS loads write lane i's 16 bytes at (wave-uniform LDS base) + 16*i, so one
+// instruction fills four consecutive 256-byte rows; the swizzle is applied on the global side:
+// lane i = (row r = i/16, physical chunk c = i%16) fetches logical chunk c ^ f(r).
+// Wavefront w fills rows 8w .. 8w+7 of K and of V: four instructions per block.
+// Rows past n_valid re-read the last valid row: finite data whose probabilities are zero.
+__device__ __forceinline__ void issue_block_loads(const Block& b, long stride_b, char* slot) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, rl = lane >> 4;
 #pragma unroll
-    for (int i = 0; i < LD_PER_THREAD; ++i) {
-        const int id = i * NT + tid;
-        const int row = id >> 4, ch = id & 15;
-        if (row < t.n_valid) {
-            s.k[i] = *(const u32x4*)(t.k + (long)row * stride_b + ch * 16);
-            s.v[i] = *(const u32x4*)(t.v + (long)row * stride_b + ch * 16);
-        } else {
-            s.k[i] = (u32x4){0, 0, 0, 0};
-            s.v[i] = (u32x4){0, 0, 0, 0};
-        }
+    for (int i = 0; i < 2; ++i) {
+        const int r = 8 * wave + 4 * i + rl;
+        const int rr = r < b.n_valid ? r : b.n_valid - 1;
+        const char* ksrc = b.k + (long)rr * stride_b + ((c ^ (r & 15)) << 4);
+        const char* vsrc = b.v + (long)rr * stride_b + ((c ^ ((r & 3) << 2)) << 4);
+        char* dst = slot + (8 * wave + 4 * i) * ROWB;
+        __builtin_amdgcn_global_load_lds((glb_void*)ksrc, (lds_void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)vsrc, (lds_void*)(dst + KVB), 16, 0, 0);
     }
 }
 
-// K rows: 16-byte chunk index XOR (row & 15): conflict-free 16-byte reads down a column of rows.
-// V rows: chunk index XOR 4*(row & 3): the four rows of one transposing read land in distinct
-// 64-byte windows.
-__device__ __forceinline__ int k_off(int row, int ch) { return row * ROWB + ((ch ^ (row & 15)) << 4); }
-__device__ __forceinline__ int v_off(int row, int ch) { return row * ROWB + ((ch ^ ((row & 3) << 2)) << 4); }
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14]).
+// The direct-to-LDS loads complete in issue order; `blocks_younger` blocks may stay in flight.
+__device__ __forceinline__ void wait_vmcnt(int blocks_younger) {
+    if (blocks_younger >= 3) __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * LOADS_PER_BLOCK));
+    else if (blocks_younger == 2) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * LOADS_PER_BLOCK));
+    else if (blocks_younger == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | LOADS_PER_BLOCK);
+    else __builtin_amdgcn_s_waitcnt(0x0f70);
+}
 
-__device__ __forceinline__ void store_tile(const Staged& s, char* stage) {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int i = 0; i < LD_PER_THREAD; ++i) {
-        const int id = i * NT + tid;
-        const int row = id >> 4, ch = id & 15;
-        *(u32x4*)(stage + k_off(row, ch)) = s.k[i];
-        *(u32x4*)(stage + TILEB + v_off(row, ch)) = s.v[i];
-    }
+// Workgroup barrier that the compiler may not move memory operations across, without the
+// vmcnt(0) drain a fence would add (the loads in flight target other ring slots).
+__device__ __forceinline__ void ring_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
@@ -156,140 +174,325 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
     return __builtin_bit_cast(bf16x4, r);
 }
 
-// Per-wavefront running softmax state of RB blocks of 32 query rows.
+// max over the two half-wavefronts (query row = lane & 31 lives in lanes l and l ^ 32)
+__device__ __forceinline__ float max_halves(float x) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Per-wavefront state of RB blocks of 32 query rows.
 template <int RB>
 struct WaveState {
-    float m[RB];                 // running max, log2 units (score * scale * log2 e)
+    float m[RB];                 // reference maximum, log2 units (score * scale * log2 e)
     float l[RB];                 // this lane's share of the running sum
     f32x16 o[RB][4];             // O^T accumulators: [row block][32-dim block]
 };
 
-// One KV tile for one wavefront, 32 tokens at a time: S^T = K Q^T, online softmax, O^T += V^T P^T.
-//   qf       Q fragments [RB][8 k-slabs]
-//   sc2      score scale * log2(e)
-//   lim[rb]  causal limit of this lane's row (largest visible index of the causal segment)
-// The running reference maximum m only moves when a row's new maximum exceeds it by more than
-// kLazy (log2 units): probabilities then stay below 2^kLazy and the accumulators are rescaled
-// only on those rare steps.
-constexpr float kLazy = 8.f;
+// per-lane LDS byte offsets inside a slot (constant over the loop)
+struct LaneOffsets {
+    int k;                       // K fragment for k-slab ks: k ^ (32*ks)
+    int v[4];                    // V^T fragment for dim block db; + 4096*sl + 2048*half
+};
 
-template <int RB>
-__device__ __forceinline__ void compute_tile(const char* stage, const bf16x8 (&qf)[RB][8], WaveState<RB>& st,
-                                             float sc2, const Tile& t, const int (&lim)[RB], bool need_mask) {
+__device__ __forceinline__ LaneOffsets lane_offsets() {
     const int lane = threadIdx.x & 63;
-    const int l32 = lane & 31, hi = lane >> 5;
-    const int g16 = lane >> 4, s16 = lane & 15;
-    const char* vst = stage + TILEB;
+    const int l32 = lane & 31, hi = lane >> 5, g16 = lane >> 4, s16 = lane & 15;
+    LaneOffsets o;
+    // A operand of K Q^T: token row l32, dims 16*ks + 8*hi .. +7 = chunk 2*ks + hi
+    o.k = l32 * ROWB + ((hi ^ (l32 & 15)) << 4);
+    // A operand of V^T P^T via the transposing read: this lane supplies the address of token row
+    // 16*sl + 4*(g16 >> 1) + (s16 >> 2) (+8 for the second half), dims 32*db + 16*(g16 & 1) + 4*(s16 & 3) .. +3
+    const int row0 = 4 * (g16 >> 1) + (s16 >> 2);
+    const int chlow = 2 * (g16 & 1) + ((s16 & 3) >> 1);
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-        if (tb * 32 >= t.n_valid) break;                      // nothing but padding in this block
-        f32x16 s[RB];
+    for (int db = 0; db < 4; ++db)
+        o.v[db] = KVB + row0 * ROWB + (((4 * db + chlow) ^ ((row0 & 3) << 2)) << 4) + (s16 & 1) * 8;
+    return o;
+}
+
+// S^T = K Q^T for one block (both row blocks share each K fragment).
+template <int RB>
+__device__ __forceinline__ void scores(const char* slot, const LaneOffsets& lo, const bf16x8 (&qf)[RB][8], f32x16 (&s)[RB]) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+            s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], s[rb], 0, 0, 0);
+    }
+}
 
-        // ---- S^T = K Q^T
-        const int row = tb * 32 + l32;
+// O^T += V^T P^T for one block.  k-slot e of lane half `hi` in slab sl is token
+// 16*sl + (e < 4 ? 4*hi + e : 8 + 4*hi + e - 4): two transposing reads per fragment.
+template <int RB>
+__device__ __forceinline__ void accumulate(const char* slot, const LaneOffsets& lo, const bf16x8 (&p)[RB][2], WaveState<RB>& st) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 a = *(const bf16x8*)(stage + k_off(row, 2 * ks + hi));
+    for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const bf16x4 lo4 = lds_read_tr(slot + lo.v[db] + 4096 * sl);
+            const bf16x4 hi4 = lds_read_tr(slot + lo.v[db] + 4096 * sl + 2048);
+            const bf16x8 a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
-                s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], s[rb], 0, 0, 0);
+                st.o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[rb][sl], st.o[rb][db], 0, 0, 0);
         }
+}
 
-        // ---- masks (tile tail, causal diagonal); accumulator register r holds token
-        //      tb*32 + 8*(r/4) + 4*hi + (r%4) of the tile for query row l32
-        if (need_mask) {
+// Masks of a block (tail, causal diagonal); accumulator register r holds token
+// 8*(r/4) + 4*hi + (r%4) of the block for query row lane & 31.
+template <int RB>
+__device__ __forceinline__ void apply_mask(f32x16 (&s)[RB], const Block& b, const int (&lim)[RB]) {
+    const int hi = (threadIdx.x & 63) >> 5;
+    // keep the vector writes below clear of the matrix-core writes to the same registers
+    asm volatile("s_nop 15");
+    asm volatile("s_nop 15");
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int tok = tb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+    for (int rb = 0; rb < RB; ++rb) {
+        // tokens of the block this row sees: [0, nvis)
+        const int nvis = b.j0 >= 0 ? min(b.n_valid, lim[rb] - b.j0 + 1) : b.n_valid;
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    const bool dead = tok >= t.n_valid || (t.j0 >= 0 && t.j0 + tok > lim[rb]);
-                    if (dead) s[rb][r] = -INFINITY;
-                }
-            }
-        }
-
-        // ---- online softmax per query row (row = lane & 31, shared with lane ^ 32)
-        bf16x8 p[RB][2];
-        float alpha[RB];
-        bool rescale = false;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            float mx = s[rb][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[rb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * sc2;
-            const float m_old = st.m[rb];
-            const float m_new = mx > m_old + kLazy ? mx : m_old;    // -inf + 8 = -inf: first visible key always moves it
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;   // row with nothing visible yet
-            alpha[rb] = __builtin_amdgcn_exp2f(m_old - m_use);
-            rescale |= m_new != m_old;
-            float psum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -m_use));
-                psum += pv;
-                p[rb][r >> 3][r & 7] = (__bf16)pv;
-            }
-            st.l[rb] = st.l[rb] * alpha[rb] + psum;
-            st.m[rb] = m_new;
-        }
-        if (__builtin_amdgcn_ballot_w64(rescale) != 0) {
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) st.o[rb][db][r] *= alpha[rb];
-        }
-
-        // ---- O^T += V^T P^T.  k-slot e of lane half `hi` in slab sl is token
-        //      tb*32 + 16*sl + (e < 4 ? 4*hi + e : 8 + 4*hi + e - 4): two transposing reads.
-#pragma unroll
-        for (int sl = 0; sl < 2; ++sl) {
-            const int row0 = tb * 32 + 16 * sl + 4 * (g16 >> 1) + (s16 >> 2);
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const int ch = 4 * db + 2 * (g16 & 1) + ((s16 & 3) >> 1);
-                const int sub = (s16 & 1) * 8;
-                const bf16x4 lo4 = lds_read_tr(vst + v_off(row0, ch) + sub);
-                const bf16x4 hi4 = lds_read_tr(vst + v_off(row0 + 8, ch) + sub);
-                const bf16x8 a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-                    st.o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[rb][sl], st.o[rb][db], 0, 0, 0);
-            }
+        for (int r = 0; r < 16; ++r) {
+            const int tok = 8 * (r >> 2) + 4 * hi + (r & 3);
+            s[rb][r] = tok < nvis ? s[rb][r] : -INFINITY;      // a select, not a branch
         }
     }
 }
 
-// Streams every tile of `walk` through the double-buffered LDS stage.
-//   vis_hi  largest causal index any row of THIS wavefront sees (tiles beyond it are skipped)
-//   vis_lo  smallest causal limit among this wavefront's rows (tiles up to it need no causal mask)
-template <int RB, typename Walk>
-__device__ __forceinline__ void run_tiles(Walk& walk, long stride_b, char* lds, const bf16x8 (&qf)[RB][8],
-                                          WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo, int vis_hi) {
-    Tile cur, nxt;
-    bool have = walk.next(cur);
-    Staged sg;
-    if (have) load_tile(cur, stride_b, sg);
-    int it = 0;
-    while (have) {
-        char* stage = lds + (it & 1) * STAGEB;
-        store_tile(sg, stage);
-        __syncthreads();
-        const bool have_next = walk.next(nxt);
-        if (have_next) load_tile(nxt, stride_b, sg);
-        const bool causal = cur.j0 >= 0;
-        if (!(causal && cur.j0 > vis_hi)) {
-            const bool need_mask = cur.n_valid < BN || (causal && cur.j0 + BN - 1 > vis_lo);
-            compute_tile<RB>(stage, qf, st, sc2, cur, lim, need_mask);
+// ---- online softmax of one block, in two phases so that it can be sliced between MFMAs ----
+// Phase A (needs the whole block of scores): new reference maximum of each query row.
+//   m_use  reference the probabilities of this block are taken against
+//   alpha  factor that brings older sums/accumulators to the new reference (1 when it did not move)
+template <int RB>
+struct RowRef {
+    float m_use[RB];
+    float alpha[RB];
+    float psum[RB];
+    bool moved;
+};
+
+__device__ __forceinline__ float max8(const f32x16& s, int base) {
+    return fmaxf(fmaxf(fmaxf(s[base], s[base + 1]), fmaxf(s[base + 2], s[base + 3])),
+                 fmaxf(fmaxf(s[base + 4], s[base + 5]), fmaxf(s[base + 6], s[base + 7])));
+}
+
+template <int RB>
+__device__ __forceinline__ void phase_a_finish(float mx_lane, int rb, float sc2, WaveState<RB>& st, RowRef<RB>& ref) {
+    const float mx = max_halves(mx_lane) * sc2;
+    const float m_old = st.m[rb];
+    const float m_new = mx > m_old + kLazy ? mx : m_old;        // -inf + 8 = -inf: the first visible key always moves it
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;       // row with nothing visible yet
+    ref.m_use[rb] = m_use;
+    ref.alpha[rb] = __builtin_amdgcn_exp2f(m_old - m_use);
+    ref.psum[rb] = 0.f;
+    ref.moved |= m_new != m_old;
+    st.m[rb] = m_new;
+}
+
+template <int RB>
+__device__ __forceinline__ void phase_a_row(const f32x16 (&s)[RB], int rb, float sc2, WaveState<RB>& st, RowRef<RB>& ref) {
+    phase_a_finish<RB>(fmaxf(max8(s[rb], 0), max8(s[rb], 8)), rb, sc2, st, ref);
+}
+
+// Phase B, one slice: two scores -> two bf16 probabilities (register pair k of row block rb).
+// The row sum is taken over the ROUNDED probabilities, the ones the PV product uses.
+template <int RB>
+__device__ __forceinline__ void phase_b_pair(const f32x16 (&s)[RB], int rb, int k, float sc2, RowRef<RB>& ref, bf16x8 (&p)[RB][2]) {
+    const int r = 2 * k;
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -ref.m_use[rb]));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[rb][r + 1], sc2, -ref.m_use[rb]));
+    bf16x2 pk;
+    pk[0] = (__bf16)p0; pk[1] = (__bf16)p1;
+    const bf16x2 ones = {(__bf16)1.f, (__bf16)1.f};
+    ref.psum[rb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ref.psum[rb], false);
+    p[rb][r >> 3][r & 7] = pk[0];
+    p[rb][r >> 3][(r & 7) + 1] = pk[1];
+}
+
+template <int RB>
+__device__ __forceinline__ void rescale(WaveState<RB>& st, const float (&alpha)[RB]) {
+    // keep the vector read-modify-write clear of the matrix-core writes to the accumulators
+    asm volatile("s_nop 15");
+    asm volatile("s_nop 15");
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[rb][db][r] *= alpha[rb];
+}
+
+__device__ __forceinline__ bf16x8 read_k_frag(const char* slot, const LaneOffsets& lo, int ks) {
+    return *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
+}
+// V^T fragment f = sl*4 + db
+__device__ __forceinline__ bf16x8 read_v_frag(const char* slot, const LaneOffsets& lo, int f) {
+    const bf16x4 lo4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2));
+    const bf16x4 hi4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2) + 2048);
+    return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Keeps a value (and with it the slice of vector work that produced it) at this point of the
+// program: the scheduling barriers below order machine instructions, this orders the IR.
+__device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
+
+// One step of the software pipeline, for block j, entered with
+//   s_cur    scores of block j, phase A already done (ref_cur); holds block j+1's on return
+// It runs  K Q^T of block j+1 -> s_nxt  (matrix cores)  |  phase B of block j -> p   (vector ALUs)
+// then     O += P V of block j          (matrix cores)  |  phase A of block j+1 -> ref_nxt
+// as ONE interleaved instruction stream: an MFMA, a slice of vector work, pinned by a scheduling
+// barrier -- a wavefront has its SIMD to itself, so nothing else would fill the matrix cores
+// while it runs the softmax.  Without a next block (have_nxt false) slot_nxt is any landed slot:
+// the scores are computed and dropped.
+template <int RB>
+__device__ __forceinline__ void pipeline_step(const char* slot_cur, const char* slot_nxt, const LaneOffsets& lo,
+                                              const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
+                                              f32x16 (&s_cur)[RB], f32x16 (&s_nxt)[RB],
+                                              RowRef<RB>& ref_cur, RowRef<RB>& ref_nxt,
+                                              bool have_nxt, const Block& nb, bool nxt_masked, const int (&lim)[RB]) {
+    // O holds blocks < j at the previous reference: bring it to block j's (rare)
+    if (__builtin_amdgcn_ballot_w64(ref_cur.moved) != 0) rescale<RB>(st, ref_cur.alpha);
+
+    // ---- first half: 8*RB MFMAs of K Q^T, 8*RB slices of phase B
+    bf16x8 p[RB][2];
+    bf16x8 kf[8];
+    kf[0] = read_k_frag(slot_nxt, lo, 0);
+    kf[1] = read_k_frag(slot_nxt, lo, 1);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_nxt[rb][r] = 0.f;
+    // two slices ahead of the first MFMA cover the latency of the first fragment reads
+    phase_b_pair<RB>(s_cur, 0, 0, sc2, ref_cur, p);
+    phase_b_pair<RB>(s_cur, 0, 1, sc2, ref_cur, p);
+    pin(ref_cur.psum[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 vf[8];
+#pragma unroll
+    for (int n = 0; n < 8 * RB; ++n) {
+        const int ks = n / RB, rb = n % RB;
+        if (rb == 0 && ks + 2 < 8) kf[ks + 2] = read_k_frag(slot_nxt, lo, ks + 2);
+        if (rb == 0 && ks == 6) vf[0] = read_v_frag(slot_cur, lo, 0);
+        if (rb == 0 && ks == 7) vf[1] = read_v_frag(slot_cur, lo, 1);
+        s_nxt[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_nxt[rb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        const int slice = n + 2;                                     // (row block, register pair) of phase B
+        if (slice < 8 * RB) {
+            phase_b_pair<RB>(s_cur, slice / 8, slice % 8, sc2, ref_cur, p);
+            pin(ref_cur.psum[slice / 8]);
         }
-        cur = nxt; have = have_next; ++it;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) st.l[rb] = st.l[rb] * ref_cur.alpha[rb] + ref_cur.psum[rb];
+
+    // ---- second half: 8*RB MFMAs of O += P V; in their shadow the scores of block j+1 move from
+    //      the MFMA accumulators into the vector registers of s_cur (block j's scores are dead
+    //      now) and go through phase A
+    float m_keep[RB], mx[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) m_keep[rb] = st.m[rb];
+    ref_nxt.moved = false;
+    vf[2] = read_v_frag(slot_cur, lo, 2);
+    if (nxt_masked) {
+        // rare (block tails, the causal diagonal): no interleaving; the PV products go first
+#pragma unroll
+        for (int n = 0; n < 8 * RB; ++n) {
+            const int f = n / RB, rb = n % RB;
+            if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
+            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) s_cur[rb] = s_nxt[rb];
+        apply_mask<RB>(s_cur, nb, lim);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) phase_a_row<RB>(s_cur, rb, sc2, st, ref_nxt);
+    } else {
+#pragma unroll
+        for (int n = 0; n < 8 * RB; ++n) {
+            const int f = n / RB, rb = n % RB;                       // fragment f = sl*4 + db
+            if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
+            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            // vector slices: 4 x (move 8 scores of a row block + their maximum), then the row references
+            if (n < 4 * RB) {
+                const int r2 = n / 4, part = n % 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s_cur[r2][4 * part + e] = s_nxt[r2][4 * part + e];
+                const float m4 = fmaxf(fmaxf(s_cur[r2][4 * part], s_cur[r2][4 * part + 1]),
+                                       fmaxf(s_cur[r2][4 * part + 2], s_cur[r2][4 * part + 3]));
+                mx[r2] = part == 0 ? m4 : fmaxf(mx[r2], m4);
+                pin(mx[r2]);
+            } else if (n < 5 * RB) {
+                phase_a_finish<RB>(mx[n - 4 * RB], n - 4 * RB, sc2, st, ref_nxt);
+                pin(ref_nxt.alpha[n - 4 * RB]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (!have_nxt) {                                                 // nothing was there: keep the references
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) st.m[rb] = m_keep[rb];
+        ref_nxt.moved = false;
+    }
+}
+
+// Streams every block of the walk.  Two copies of the walker run: `lw` feeds the loads (RING-1
+// blocks ahead), `cw` describes the blocks being computed.  Every wavefront of the workgroup
+// executes the same barriers and the same instruction stream; causal blocks a wavefront's rows
+// do not see are simply masked.
+//   vis_lo smallest causal limit among this wavefront's rows (blocks up to it need no causal mask)
+template <int RB>
+__device__ __forceinline__ void run_blocks(Walk lw, Walk cw, long stride_b, char* lds, const bf16x8 (&qf)[RB][8],
+                                           WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo) {
+    const LaneOffsets lo = lane_offsets();
+    Block lb;
+    int issued = 0;                                   // blocks whose loads have been issued
+    bool more = true;
+    while (issued < RING - 1 && more) {
+        more = lw.next(lb);
+        if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB); ++issued; }
+    }
+    if (issued == 0) return;
+
+    f32x16 s_cur[RB], s_nxt[RB];                      // scores of blocks j and j+1
+    RowRef<RB> ref_cur, ref_nxt;
+    Block cb, nb;
+    bool have_cur = cw.next(cb);                      // block 0 (exists: issued > 0)
+    auto masked = [&](const Block& b) { return b.n_valid < BLK || (b.j0 >= 0 && b.j0 + BLK - 1 > vis_lo); };
+
+    // block 0: scores and phase A
+    wait_vmcnt(issued - 1);
+    ring_barrier();
+    scores<RB>(lds, lo, qf, s_cur);
+    if (masked(cb)) apply_mask<RB>(s_cur, cb, lim);
+    ref_cur.moved = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) phase_a_row<RB>(s_cur, rb, sc2, st, ref_cur);
+
+    for (int j = 0; have_cur; ++j) {
+        // block j+1 must have landed; every wavefront is then also done with block j-1's slot,
+        // which the next loads overwrite
+        const bool have_nxt = cw.next(nb);
+        if (have_nxt) {
+            wait_vmcnt(issued - (j + 2));
+            ring_barrier();
+            if (more) {
+                more = lw.next(lb);
+                if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB); ++issued; }
+            }
+        }
+        const char* slot_cur = lds + (j % RING) * SLOTB;
+        const char* slot_nxt = have_nxt ? lds + ((j + 1) % RING) * SLOTB : slot_cur;
+        pipeline_step<RB>(slot_cur, slot_nxt, lo, qf, st, sc2, s_cur, s_nxt, ref_cur, ref_nxt,
+                          have_nxt, nb, have_nxt && masked(nb), lim);
+        ref_cur = ref_nxt;                            // (s_cur already holds block j+1's scores)
+        cb = nb; have_cur = have_nxt;
     }
 }
 
@@ -356,28 +559,30 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
     WaveState<RB> st;
     init_state<RB>(st);
     const float inv_sqrt_d = 0.08838834764831845f;      // 1/sqrt(128)
+    Walk walk;
+    float sc2 = inv_sqrt_d * LOG2E;
+    int vis_lo = 0, vis_hi = 0;
     if (split < a.n_ctx_splits) {
         const long t0 = (long)split * a.ctx_split_len;
         const long t1 = min((long)kv.total_ctx, t0 + a.ctx_split_len);
-        CtxWalk walk;
-        walk.init(&kv, t0, t1, stride_b, head_b);
-        run_tiles<RB>(walk, stride_b, lds, qf, st, inv_sqrt_d / kv.temperature * LOG2E, lim, 0, 0);
+        walk.init_ctx(kv, t0, t1, stride_b, head_b);
+        sc2 = inv_sqrt_d / kv.temperature * LOG2E;
     } else {
         // rows of this workgroup see the causal segment up to the last valid row's limit
         const int wg_tok_hi = min((qtile * BM + BM - 1) / G, q_len - 1);
-        SeqWalk walk;
-        walk.init((const char*)kv.k_prefix + head_b, (const char*)kv.v_prefix + head_b, kv.prefix_len,
-                  (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
-        run_tiles<RB>(walk, stride_b, lds, qf, st, inv_sqrt_d * LOG2E, lim, tok_lo + causal_off, tok_hi + causal_off);
+        walk.init_seq((const char*)kv.k_prefix + head_b, (const char*)kv.v_prefix + head_b, kv.prefix_len,
+                      (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
+        vis_lo = tok_lo + causal_off; vis_hi = tok_hi + causal_off;
     }
+    run_blocks<RB>(walk, walk, stride_b, lds, qf, st, sc2, lim, vis_lo);
 
     // ---- block result (Appendix C.1): normalised values + natural-log LogSumExp
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
         const int tok = R / G, g = R % G;
-        if (tok >= q_len) continue;
         const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
+        if (tok >= q_len) continue;
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
         const long unit = (long)tok * hq + hk * G + g;
         const long slot = (long)split * a.units_total + unit;
@@ -437,18 +642,18 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
 
     WaveState<RB> st;
     init_state<RB>(st);
-    SeqWalk walk;
-    walk.init((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
+    Walk walk;
+    walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
               (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
               wg_tok_hi + 1, stride_b);
-    run_tiles<RB>(walk, stride_b, lds, qf, st, 0.08838834764831845f * LOG2E, lim, tok_lo, tok_hi);
+    run_blocks<RB>(walk, walk, stride_b, lds, qf, st, 0.08838834764831845f * LOG2E, lim, tok_lo);
 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
         const int tok = R / G, g = R % G;
-        if (tok >= len) continue;
         const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
+        if (tok >= len) continue;
         const float inv = 1.f / lt;                        // a row always sees itself
         const int h = hk * G + g;
         char* o = (char*)a.out + ((long)(c0 + tok) * hq + h) * ROWB;

@@ -31,9 +31,14 @@ def check_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = ""):
 
 
 def lse_tol(dtype: str) -> float:
-    # LogSumExp is an fp32 output on both paths; bf16 inputs are exact in the oracle too, the only
-    # bf16 rounding inside the kernels (P before the PV product) does not touch it.
-    return 2e-5 if dtype == "f32" else 2e-4
+    """Tolerance of the LogSumExp outputs (the benchmark definition states none; derived here).
+    fp32 path: fp32 scores, expf, fp32 sums of <= a few hundred terms: 2e-5.
+    bf16 path: the matrix-core kernels sum the probabilities AFTER rounding them to bf16, so that
+    the normaliser carries the same rounding as the P.V numerator.  bf16 keeps 8 significant bits,
+    so each rounded term is off by a relative 2^-8 at most, hence so is the sum of these positive
+    terms and |dLSE| <= 2^-8 ~ 3.9e-3 in the worst case (a row dominated by one key); errors of
+    random sign average out (~4e-4 observed over 131K keys)."""
+    return 2e-5 if dtype == "f32" else 4e-3
 
 
 class HostArrays:
