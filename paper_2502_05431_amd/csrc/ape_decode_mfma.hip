@@ -138,11 +138,11 @@ __device__ __forceinline__ void accumulate_pv(const uint32_t (&v)[32], bf16x8 p,
 // walked through the chunk table.  next() yields tiles of <= 32 tokens that never straddle a
 // segment or chunk end.
 struct Stream {
-    const int32_t* cu;                // non-NULL: context range [t, te) through the chunk table
+    const int32_t* cu;                 // non-NULL: context range [t, te) through the chunk table (scalar loads)
     const void* const* k_chunks;
     const void* const* v_chunks;
     int n_chunks;
-    long t, te, c0, c1;
+    int t, te, c0, c1;
     int c;
     const char *k0, *v0, *k1, *v1;    // plain segments
     int n0, n1;
@@ -151,15 +151,15 @@ struct Stream {
 
     __device__ void init_ctx(const KvView& kv, long t_, long te_, long stride_b_, long head_b_) {
         cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
-        t = t_; te = te_; stride_b = stride_b_; head_b = head_b_; c = 0; c0 = 0; c1 = 0;
+        t = (int)t_; te = (int)te_; stride_b = stride_b_; head_b = head_b_; c = 0; c0 = 0; c1 = 0;
         seg = 2; j = 0; n0 = n1 = 0; k0 = v0 = k1 = v1 = nullptr;
         if (t < te) {
             int lo = 0, hi = n_chunks - 1;
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (cu[mid] <= t) lo = mid; else hi = mid - 1;
+                if (scalar_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
             }
-            c = lo; c0 = cu[c]; c1 = cu[c + 1];
+            c = lo; c0 = scalar_load_i32(cu + c); c1 = scalar_load_i32(cu + c + 1);
         } else {
             te = t;
         }
@@ -175,12 +175,12 @@ struct Stream {
             if (t >= te) return false;
             while (t >= c1) {
                 if (c + 1 >= n_chunks) { t = te; return false; }   // table shorter than total_ctx: stay in bounds
-                ++c; c0 = c1; c1 = cu[c + 1];
+                ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
             }
-            const long e = c1 < te ? c1 : te;
-            nv = (int)(e - t < BT ? e - t : BT);
-            kb = (const char*)k_chunks[c] + (t - c0) * stride_b + head_b;
-            vb = (const char*)v_chunks[c] + (t - c0) * stride_b + head_b;
+            const int e = c1 < te ? c1 : te;
+            nv = e - t < BT ? e - t : BT;
+            kb = (const char*)scalar_load_ptr(k_chunks + c) + (long)(t - c0) * stride_b + head_b;
+            vb = (const char*)scalar_load_ptr(v_chunks + c) + (long)(t - c0) * stride_b + head_b;
             t += nv;
             return true;
         }
@@ -223,7 +223,11 @@ __global__ __launch_bounds__(NT, 2) void decode_kernel(const QueryArgs a) {
     __shared__ float sm_m[NW][16];
     __shared__ float sm_l[NW][16];
     __shared__ float sm_o[NW][G][D];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wavefront index is made provably uniform: everything the block walker derives from it
+    // (token ranges, chunk indices, table addresses) then lives in scalar registers and its
+    // branches are scalar branches -- a scalar table load must never sit in divergent control
+    // flow, where it would run with EXEC = 0 and a stale address
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, kg = lane >> 4;
     const int split = blockIdx.x, hk = blockIdx.y, rq = blockIdx.z;
     // the request descriptor is read straight from the kernel-argument segment (scalar loads);

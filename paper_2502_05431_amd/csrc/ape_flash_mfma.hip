@@ -66,12 +66,13 @@ struct Block {
 // stop at chunk ends, no mask), or a plain segment (the prefix, no mask) followed by a causal
 // segment (self KV / own chunk).
 struct Walk {
-    // context mode (cu != NULL)
+    // context mode (cu != NULL); the tables are read with scalar loads
     const int32_t* cu;
     const void* const* k_chunks;
     const void* const* v_chunks;
     int n_chunks, c;
-    long t, t1, c0, c1, head_b;
+    int t, t1, c0, c1;
+    long head_b;
     // sequence mode
     const char *kp, *vp, *kc, *vc;
     int np, nc, j, phase;
@@ -79,22 +80,22 @@ struct Walk {
 
     __device__ void init_ctx(const KvView& kv, long t0_, long t1_, long stride_b_, long head_b_) {
         cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
-        t = t0_; t1 = t1_; stride_b = stride_b_; head_b = head_b_;
+        t = (int)t0_; t1 = (int)t1_; stride_b = stride_b_; head_b = head_b_;
         c = 0; c0 = 0; c1 = 0;
         kp = vp = kc = vc = nullptr; np = nc = j = 0; phase = 2;
         if (t < t1 && cu != nullptr) {
             int lo = 0, hi = n_chunks - 1;
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (cu[mid] <= t) lo = mid; else hi = mid - 1;
+                if (scalar_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
             }
-            c = lo; c0 = cu[c]; c1 = cu[c + 1];
+            c = lo; c0 = scalar_load_i32(cu + c); c1 = scalar_load_i32(cu + c + 1);
         } else {
             t1 = t;
         }
     }
     __device__ void init_seq(const char* kp_, const char* vp_, int np_, const char* kc_, const char* vc_, int nc_, long stride_b_) {
-        cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = c = 0; t = t1 = c0 = c1 = head_b = 0;
+        cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = c = 0; t = t1 = c0 = c1 = 0; head_b = 0;
         kp = kp_; vp = vp_; np = np_; kc = kc_; vc = vc_; nc = nc_; stride_b = stride_b_;
         j = 0; phase = np > 0 ? 0 : 1;
     }
@@ -103,12 +104,12 @@ struct Walk {
             if (t >= t1) return false;
             while (t >= c1) {                                          // next non-empty chunk
                 if (c + 1 >= n_chunks) { t = t1; return false; }       // table shorter than total_ctx: stop, stay in bounds
-                ++c; c0 = c1; c1 = cu[c + 1];
+                ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
             }
-            const long e = c1 < t1 ? c1 : t1;
-            const int n = (int)(e - t < BLK ? e - t : BLK);
-            b.k = (const char*)k_chunks[c] + (t - c0) * stride_b + head_b;
-            b.v = (const char*)v_chunks[c] + (t - c0) * stride_b + head_b;
+            const int e = c1 < t1 ? c1 : t1;
+            const int n = e - t < BLK ? e - t : BLK;
+            b.k = (const char*)scalar_load_ptr(k_chunks + c) + (long)(t - c0) * stride_b + head_b;
+            b.v = (const char*)scalar_load_ptr(v_chunks + c) + (long)(t - c0) * stride_b + head_b;
             b.n_valid = n; b.j0 = -1;
             t += n;
             return true;

@@ -93,6 +93,31 @@ __device__ __forceinline__ __attribute__((address_space(4))) const Args* kernarg
     return (__attribute__((address_space(4))) const Args*)__builtin_amdgcn_kernarg_segment_ptr();
 }
 
+// The chunk tables (pointer arrays, cu_chunk_lens) are read-only for the whole launch and are
+// indexed with wavefront-uniform indices.  They are read with explicit SCALAR loads: the results
+// stay in scalar registers (uniform control flow around the block walkers) and, being counted by
+// lgkmcnt, the reads do not drain the vector-memory queue that holds the K/V loads in flight
+// (a vector load of a table entry would be followed by s_waitcnt vmcnt(0)).
+// The address must be wavefront-uniform; the compiler moves it to scalar registers.
+__device__ __forceinline__ uint64_t uniform_address(const void* p) {
+    const uint64_t a = (uint64_t)p;
+    // the builtin returns a signed int: go through uint32_t, or the low half would be sign-extended
+    // into the high half
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+    return ((uint64_t)hi << 32) | (uint64_t)lo;
+}
+__device__ __forceinline__ int32_t scalar_load_i32(const int32_t* p) {
+    int32_t v;
+    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_address(p)) : "memory");
+    return v;
+}
+__device__ __forceinline__ const void* scalar_load_ptr(const void* const* p) {
+    uint64_t v;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_address(p)) : "memory");
+    return (const void*)v;
+}
+
 template <typename Args>
 __device__ __forceinline__ KvView load_view(int rq) {
     auto ap = kernarg<Args>();
