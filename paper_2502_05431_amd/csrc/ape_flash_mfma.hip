@@ -51,7 +51,7 @@ constexpr int LDSB = RING * SLOTB;           // 96 KB
 constexpr int LOADS_PER_BLOCK = 4;           // direct-to-LDS load instructions per wavefront per block
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
-constexpr float kLazy = 8.f;                 // the reference maximum moves only when exceeded by 2^kLazy
+constexpr float kLazy = 40.f;                // the reference maximum moves only when exceeded by 2^kLazy
 
 // One KV block: n_valid (1..32) consecutive tokens of one segment.
 struct Block {
@@ -66,10 +66,11 @@ struct Block {
 // stop at chunk ends, no mask), or a plain segment (the prefix, no mask) followed by a causal
 // segment (self KV / own chunk).
 struct Walk {
-    // context mode (cu != NULL); the tables are read with scalar loads
+    // context mode (cu != NULL); the tables are read with scalar loads, once per chunk
     const int32_t* cu;
     const void* const* k_chunks;
     const void* const* v_chunks;
+    const char *kbase, *vbase;       // rows of the current chunk for this KV head
     int n_chunks, c;
     int t, t1, c0, c1;
     long head_b;
@@ -78,10 +79,14 @@ struct Walk {
     int np, nc, j, phase;
     long stride_b;
 
+    __device__ void load_chunk() {
+        kbase = (const char*)scalar_load_ptr(k_chunks + c) + head_b;
+        vbase = (const char*)scalar_load_ptr(v_chunks + c) + head_b;
+    }
     __device__ void init_ctx(const KvView& kv, long t0_, long t1_, long stride_b_, long head_b_) {
         cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
         t = (int)t0_; t1 = (int)t1_; stride_b = stride_b_; head_b = head_b_;
-        c = 0; c0 = 0; c1 = 0;
+        c = 0; c0 = 0; c1 = 0; kbase = vbase = nullptr;
         kp = vp = kc = vc = nullptr; np = nc = j = 0; phase = 2;
         if (t < t1 && cu != nullptr) {
             int lo = 0, hi = n_chunks - 1;
@@ -90,26 +95,30 @@ struct Walk {
                 if (scalar_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
             }
             c = lo; c0 = scalar_load_i32(cu + c); c1 = scalar_load_i32(cu + c + 1);
+            load_chunk();
         } else {
             t1 = t;
         }
     }
     __device__ void init_seq(const char* kp_, const char* vp_, int np_, const char* kc_, const char* vc_, int nc_, long stride_b_) {
-        cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = c = 0; t = t1 = c0 = c1 = 0; head_b = 0;
+        cu = nullptr; k_chunks = v_chunks = nullptr; kbase = vbase = nullptr; n_chunks = c = 0; t = t1 = c0 = c1 = 0; head_b = 0;
         kp = kp_; vp = vp_; np = np_; kc = kc_; vc = vc_; nc = nc_; stride_b = stride_b_;
         j = 0; phase = np > 0 ? 0 : 1;
     }
     __device__ bool next(Block& b) {
         if (cu != nullptr) {
             if (t >= t1) return false;
-            while (t >= c1) {                                          // next non-empty chunk
-                if (c + 1 >= n_chunks) { t = t1; return false; }       // table shorter than total_ctx: stop, stay in bounds
-                ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
+            if (t >= c1) {
+                do {                                                   // next non-empty chunk
+                    if (c + 1 >= n_chunks) { t = t1; return false; }   // table shorter than total_ctx: stop, stay in bounds
+                    ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
+                } while (t >= c1);
+                load_chunk();
             }
             const int e = c1 < t1 ? c1 : t1;
             const int n = e - t < BLK ? e - t : BLK;
-            b.k = (const char*)scalar_load_ptr(k_chunks + c) + (long)(t - c0) * stride_b + head_b;
-            b.v = (const char*)scalar_load_ptr(v_chunks + c) + (long)(t - c0) * stride_b + head_b;
+            b.k = kbase + (long)(t - c0) * stride_b;
+            b.v = vbase + (long)(t - c0) * stride_b;
             b.n_valid = n; b.j0 = -1;
             t += n;
             return true;
@@ -138,18 +147,33 @@ struct Walk {
 // lane i = (row r = i/16, physical chunk c = i%16) fetches logical chunk c ^ f(r).
 // Wavefront w fills rows 8w .. 8w+7 of K and of V: four instructions per block.
 // Rows past n_valid re-read the last valid row: finite data whose probabilities are zero.
-__device__ __forceinline__ void issue_block_loads(const Block& b, long stride_b, char* slot) {
+struct LoadOffsets { uint32_t k[2], v[2]; };          // byte offsets of this lane's pieces from a block's row 0
+
+__device__ __forceinline__ LoadOffsets load_offsets(long stride_b, int n_valid) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, rl = lane >> 4;
+    LoadOffsets o;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = 8 * wave + 4 * i + rl;
-        const int rr = r < b.n_valid ? r : b.n_valid - 1;
-        const char* ksrc = b.k + (long)rr * stride_b + ((c ^ (r & 15)) << 4);
-        const char* vsrc = b.v + (long)rr * stride_b + ((c ^ ((r & 3) << 2)) << 4);
+        const int rr = r < n_valid ? r : n_valid - 1;
+        o.k[i] = (uint32_t)rr * (uint32_t)stride_b + ((c ^ (r & 15)) << 4);
+        o.v[i] = (uint32_t)rr * (uint32_t)stride_b + ((c ^ ((r & 3) << 2)) << 4);
+    }
+    return o;
+}
+
+// `full` holds the offsets of a full block (computed once); a partial block recomputes them with
+// its rows clamped.  The block's base pointers are wavefront-uniform, the offsets 32-bit per lane.
+__device__ __forceinline__ void issue_block_loads(const Block& b, long stride_b, char* slot, const LoadOffsets& full) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    LoadOffsets o = full;
+    if (b.n_valid < BLK) o = load_offsets(stride_b, b.n_valid);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
         char* dst = slot + (8 * wave + 4 * i) * ROWB;
-        __builtin_amdgcn_global_load_lds((glb_void*)ksrc, (lds_void*)dst, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void*)vsrc, (lds_void*)(dst + KVB), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(b.k + o.k[i]), (lds_void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(b.v + o.v[i]), (lds_void*)(dst + KVB), 16, 0, 0);
     }
 }
 
@@ -290,7 +314,7 @@ __device__ __forceinline__ void phase_a_finish(float mx_lane, int rb, float sc2,
     ref.m_use[rb] = m_use;
     ref.alpha[rb] = __builtin_amdgcn_exp2f(m_old - m_use);
     ref.psum[rb] = 0.f;
-    ref.moved |= m_new != m_old;
+    ref.moved |= m_new != m_old && m_old != -INFINITY;           // nothing to rescale before the first visible key
     st.m[rb] = m_new;
 }
 
@@ -314,17 +338,25 @@ __device__ __forceinline__ void phase_b_pair(const f32x16 (&s)[RB], int rb, int 
     p[rb][r >> 3][(r & 7) + 1] = pk[1];
 }
 
+// O *= alpha (per query row), done on the accumulation registers themselves: the accumulators
+// stay in the AGPR half of the register file for the whole loop (nothing in the loop needs them
+// as vector-ALU operands), so the compiler has no reason to shuttle them on the hot path.
 template <int RB>
 __device__ __forceinline__ void rescale(WaveState<RB>& st, const float (&alpha)[RB]) {
-    // keep the vector read-modify-write clear of the matrix-core writes to the accumulators
-    asm volatile("s_nop 15");
-    asm volatile("s_nop 15");
+    // keep clear of the matrix-core writes to the accumulators
+    asm volatile("s_nop 15\n\ts_nop 15");
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) st.o[rb][db][r] *= alpha[rb];
+            for (int r = 0; r < 16; ++r) {
+                float x = st.o[rb][db][r], t;
+                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1"
+                             : "+a"(x), "=&v"(t) : "v"(alpha[rb]));
+                st.o[rb][db][r] = x;
+            }
+    asm volatile("s_nop 7");
 }
 
 __device__ __forceinline__ bf16x8 read_k_frag(const char* slot, const LaneOffsets& lo, int ks) {
@@ -355,8 +387,10 @@ __device__ __forceinline__ void pipeline_step(const char* slot_cur, const char* 
                                               f32x16 (&s_cur)[RB], f32x16 (&s_nxt)[RB],
                                               RowRef<RB>& ref_cur, RowRef<RB>& ref_nxt,
                                               bool have_nxt, const Block& nb, bool nxt_masked, const int (&lim)[RB]) {
-    // O holds blocks < j at the previous reference: bring it to block j's (rare)
-    if (__builtin_amdgcn_ballot_w64(ref_cur.moved) != 0) rescale<RB>(st, ref_cur.alpha);
+    // O holds blocks < j at the previous reference: bring it to block j's.  Rare: probabilities
+    // and sums are fp32/bf16 with 8 exponent bits, so a reference 2^kLazy below the running
+    // maximum loses no precision, and the reference only moves on a larger jump than that.
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(ref_cur.moved) != 0, 0)) rescale<RB>(st, ref_cur.alpha);
 
     // ---- first half: 8*RB MFMAs of K Q^T, 8*RB slices of phase B
     bf16x8 p[RB][2];
@@ -399,42 +433,35 @@ __device__ __forceinline__ void pipeline_step(const char* slot_cur, const char* 
     for (int rb = 0; rb < RB; ++rb) m_keep[rb] = st.m[rb];
     ref_nxt.moved = false;
     vf[2] = read_v_frag(slot_cur, lo, 2);
-    if (nxt_masked) {
-        // rare (block tails, the causal diagonal): no interleaving; the PV products go first
 #pragma unroll
-        for (int n = 0; n < 8 * RB; ++n) {
-            const int f = n / RB, rb = n % RB;
-            if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
-            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
+    for (int n = 0; n < 8 * RB; ++n) {
+        const int f = n / RB, rb = n % RB;                           // fragment f = sl*4 + db
+        if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
+        st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // vector slices: 4 x (move 8 scores of a row block + their maximum), then the row references
+        if (n < 4 * RB) {
+            const int r2 = n / 4, part = n % 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s_cur[r2][4 * part + e] = s_nxt[r2][4 * part + e];
+            const float m4 = fmaxf(fmaxf(s_cur[r2][4 * part], s_cur[r2][4 * part + 1]),
+                                   fmaxf(s_cur[r2][4 * part + 2], s_cur[r2][4 * part + 3]));
+            mx[r2] = part == 0 ? m4 : fmaxf(mx[r2], m4);
+            pin(mx[r2]);
+        } else if (n < 5 * RB) {
+            phase_a_finish<RB>(mx[n - 4 * RB], n - 4 * RB, sc2, st, ref_nxt);
+            pin(ref_nxt.alpha[n - 4 * RB]);
         }
         __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__builtin_expect(nxt_masked, 0)) {
+        // rare (block tails, the causal diagonal): redo phase A on the masked scores
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) s_cur[rb] = s_nxt[rb];
+        for (int rb = 0; rb < RB; ++rb) st.m[rb] = m_keep[rb];
+        ref_nxt.moved = false;
         apply_mask<RB>(s_cur, nb, lim);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) phase_a_row<RB>(s_cur, rb, sc2, st, ref_nxt);
-    } else {
-#pragma unroll
-        for (int n = 0; n < 8 * RB; ++n) {
-            const int f = n / RB, rb = n % RB;                       // fragment f = sl*4 + db
-            if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
-            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            // vector slices: 4 x (move 8 scores of a row block + their maximum), then the row references
-            if (n < 4 * RB) {
-                const int r2 = n / 4, part = n % 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) s_cur[r2][4 * part + e] = s_nxt[r2][4 * part + e];
-                const float m4 = fmaxf(fmaxf(s_cur[r2][4 * part], s_cur[r2][4 * part + 1]),
-                                       fmaxf(s_cur[r2][4 * part + 2], s_cur[r2][4 * part + 3]));
-                mx[r2] = part == 0 ? m4 : fmaxf(mx[r2], m4);
-                pin(mx[r2]);
-            } else if (n < 5 * RB) {
-                phase_a_finish<RB>(mx[n - 4 * RB], n - 4 * RB, sc2, st, ref_nxt);
-                pin(ref_nxt.alpha[n - 4 * RB]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
     }
     if (!have_nxt) {                                                 // nothing was there: keep the references
 #pragma unroll
@@ -452,12 +479,13 @@ template <int RB>
 __device__ __forceinline__ void run_blocks(Walk lw, Walk cw, long stride_b, char* lds, const bf16x8 (&qf)[RB][8],
                                            WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo) {
     const LaneOffsets lo = lane_offsets();
+    const LoadOffsets full = load_offsets(stride_b, BLK);
     Block lb;
     int issued = 0;                                   // blocks whose loads have been issued
     bool more = true;
     while (issued < RING - 1 && more) {
         more = lw.next(lb);
-        if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB); ++issued; }
+        if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full); ++issued; }
     }
     if (issued == 0) return;
 
@@ -485,7 +513,7 @@ __device__ __forceinline__ void run_blocks(Walk lw, Walk cw, long stride_b, char
             ring_barrier();
             if (more) {
                 more = lw.next(lb);
-                if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB); ++issued; }
+                if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full); ++issued; }
             }
         }
         const char* slot_cur = lds + (j % RING) * SLOTB;
