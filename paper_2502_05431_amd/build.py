@@ -20,6 +20,15 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# Per-file flags.  The flash kernels keep every MFMA accumulator in the vector registers (the
+# scores feed vector instructions at once; copying them out of the accumulation registers would
+# cost one instruction per score) and never produce NaNs on valid inputs (-inf only), which lets
+# the maxima compile to bare v_max3.
+EXTRA_FLAGS = {
+    "ape_flash_mfma.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -30,7 +39,8 @@ def build(verbose: bool = True, extra=()) -> str:
     for src in sources():
         obj = os.path.join(PKG, "_build", os.path.basename(src) + ".o")
         os.makedirs(os.path.dirname(obj), exist_ok=True)
-        cmd = ["hipcc", *[f for f in HIPCC_FLAGS if f != "-shared"], *extra, "-c", src, "-o", obj]
+        cmd = ["hipcc", *[f for f in HIPCC_FLAGS if f != "-shared"], *EXTRA_FLAGS.get(os.path.basename(src), []),
+               *extra, "-c", src, "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False

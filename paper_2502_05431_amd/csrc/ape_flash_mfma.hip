@@ -46,7 +46,10 @@ constexpr int NW = NT / 64;                  // wavefronts
 constexpr int ROWB = D * 2;                  // bytes of one head's K or V row
 constexpr int KVB = BLK * ROWB;              // 8 KB: one block of K (or V) rows
 constexpr int SLOTB = 2 * KVB;               // K rows then V rows
-constexpr int RING = 6;                      // LDS slots: blocks j, j+1 in use, 4 more in flight
+#ifndef APE_X_RING
+#define APE_X_RING 6
+#endif
+constexpr int RING = APE_X_RING;                      // LDS slots: blocks j, j+1 in use, 4 more in flight
 constexpr int LDSB = RING * SLOTB;           // 96 KB
 constexpr int LOADS_PER_BLOCK = 4;           // direct-to-LDS load instructions per wavefront per block
 constexpr float LOG2E = 1.4426950408889634f;
@@ -194,9 +197,17 @@ __device__ __forceinline__ void ring_barrier() {
     asm volatile("" ::: "memory");
 }
 
+// The transposing LDS read.  The pointer is passed through a restrict-qualified parameter on
+// purpose: once inlined, the read carries alias-scope information, like the plain K reads carry
+// type information.  The compiler's wait-count pass drains ALL outstanding global->LDS loads
+// before an LDS read it knows nothing about -- which would serialise the ring -- and leaves
+// reads with alias information to the explicit wait_vmcnt()/barrier protocol below.
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+__device__ __forceinline__ s16x4 lds_read_tr_raw(lds_s16x4* __restrict__ p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(p);
+}
 __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
-    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
-    return __builtin_bit_cast(bf16x4, r);
+    return __builtin_bit_cast(bf16x4, lds_read_tr_raw((lds_s16x4*)p));
 }
 
 // max over the two half-wavefronts (query row = lane & 31 lives in lanes l and l ^ 32)
@@ -288,82 +299,64 @@ __device__ __forceinline__ void apply_mask(f32x16 (&s)[RB], const Block& b, cons
     }
 }
 
-// ---- online softmax of one block, in two phases so that it can be sliced between MFMAs ----
-// Phase A (needs the whole block of scores): new reference maximum of each query row.
-//   m_use  reference the probabilities of this block are taken against
-//   alpha  factor that brings older sums/accumulators to the new reference (1 when it did not move)
-template <int RB>
-struct RowRef {
-    float m_use[RB];
-    float alpha[RB];
-    float psum[RB];
-    bool moved;
-};
-
-__device__ __forceinline__ float max8(const f32x16& s, int base) {
-    return fmaxf(fmaxf(fmaxf(s[base], s[base + 1]), fmaxf(s[base + 2], s[base + 3])),
-                 fmaxf(fmaxf(s[base + 4], s[base + 5]), fmaxf(s[base + 6], s[base + 7])));
+// ---- online softmax with a lazily maintained reference --------------------------------------
+// Probabilities are taken against a per-row reference m (log2 units): p = 2^(s*sc2 - m).  fp32 and
+// bf16 both carry 8 exponent bits, so m need not be the running maximum: any m within 2^kLazy of
+// it loses no precision.  The fast path therefore never computes a maximum; it only checks,
+// from the row sums it needs anyway, that no probability left the safe range -- or that a row
+// whose reference is still unset (-inf) has just seen its first keys -- and in that rare case
+// runs set_reference(), which takes the true row maxima, rescales O and l, and redoes the block.
+__device__ __forceinline__ float max16(const f32x16& s) {
+    return fmaxf(fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7]))),
+                 fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
 }
 
+// Two scores -> two bf16 probabilities (register pair k of row block rb).  The row sum is taken
+// over the ROUNDED probabilities, the ones the PV product uses.
 template <int RB>
-__device__ __forceinline__ void phase_a_finish(float mx_lane, int rb, float sc2, WaveState<RB>& st, RowRef<RB>& ref) {
-    const float mx = max_halves(mx_lane) * sc2;
-    const float m_old = st.m[rb];
-    const float m_new = mx > m_old + kLazy ? mx : m_old;        // -inf + 8 = -inf: the first visible key always moves it
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;       // row with nothing visible yet
-    ref.m_use[rb] = m_use;
-    ref.alpha[rb] = __builtin_amdgcn_exp2f(m_old - m_use);
-    ref.psum[rb] = 0.f;
-    ref.moved |= m_new != m_old && m_old != -INFINITY;           // nothing to rescale before the first visible key
-    st.m[rb] = m_new;
-}
-
-template <int RB>
-__device__ __forceinline__ void phase_a_row(const f32x16 (&s)[RB], int rb, float sc2, WaveState<RB>& st, RowRef<RB>& ref) {
-    phase_a_finish<RB>(fmaxf(max8(s[rb], 0), max8(s[rb], 8)), rb, sc2, st, ref);
-}
-
-// Phase B, one slice: two scores -> two bf16 probabilities (register pair k of row block rb).
-// The row sum is taken over the ROUNDED probabilities, the ones the PV product uses.
-template <int RB>
-__device__ __forceinline__ void phase_b_pair(const f32x16 (&s)[RB], int rb, int k, float sc2, RowRef<RB>& ref, bf16x8 (&p)[RB][2]) {
+__device__ __forceinline__ void softmax_pair(const f32x16 (&s)[RB], int rb, int k, float sc2, float m_use,
+                                             float (&psum)[RB], bf16x8 (&p)[RB][2]) {
     const int r = 2 * k;
-    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -ref.m_use[rb]));
-    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[rb][r + 1], sc2, -ref.m_use[rb]));
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -m_use));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[rb][r + 1], sc2, -m_use));
     bf16x2 pk;
     pk[0] = (__bf16)p0; pk[1] = (__bf16)p1;
     const bf16x2 ones = {(__bf16)1.f, (__bf16)1.f};
-    ref.psum[rb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ref.psum[rb], false);
+#ifdef APE_X_NOSOFTMAX
+    if (k) return;
+#endif
+    psum[rb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum[rb], false);
     p[rb][r >> 3][r & 7] = pk[0];
     p[rb][r >> 3][(r & 7) + 1] = pk[1];
 }
 
-// O *= alpha (per query row), done on the accumulation registers themselves: the accumulators
-// stay in the AGPR half of the register file for the whole loop (nothing in the loop needs them
-// as vector-ALU operands), so the compiler has no reason to shuttle them on the hot path.
+__device__ __forceinline__ float ref_use(float m) { return m == -INFINITY ? 0.f : m; }
+
+// O *= alpha (per query row).  The file is built with VGPR-form MFMAs (accumulators in the
+// vector registers), so this is a plain multiply; it is kept clear of the matrix-core writes.
 template <int RB>
 __device__ __forceinline__ void rescale(WaveState<RB>& st, const float (&alpha)[RB]) {
-    // keep clear of the matrix-core writes to the accumulators
     asm volatile("s_nop 15\n\ts_nop 15");
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float x = st.o[rb][db][r], t;
-                asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1"
-                             : "+a"(x), "=&v"(t) : "v"(alpha[rb]));
-                st.o[rb][db][r] = x;
-            }
+            for (int r = 0; r < 16; ++r) st.o[rb][db][r] *= alpha[rb];
     asm volatile("s_nop 7");
 }
 
 __device__ __forceinline__ bf16x8 read_k_frag(const char* slot, const LaneOffsets& lo, int ks) {
+#ifdef APE_X_NOKREAD
+    { u32x4 w = {(unsigned)lo.k, (unsigned)ks, (unsigned)(size_t)slot, 1u}; return __builtin_bit_cast(bf16x8, w); }
+#endif
     return *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
 }
 // V^T fragment f = sl*4 + db
 __device__ __forceinline__ bf16x8 read_v_frag(const char* slot, const LaneOffsets& lo, int f) {
+#ifdef APE_X_NOVREAD
+    { u32x4 w = {(unsigned)lo.v[f & 3], (unsigned)f, (unsigned)(size_t)slot, 1u}; return __builtin_bit_cast(bf16x8, w); }
+#endif
     const bf16x4 lo4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2));
     const bf16x4 hi4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2) + 2048);
     return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -373,156 +366,212 @@ __device__ __forceinline__ bf16x8 read_v_frag(const char* slot, const LaneOffset
 // program: the scheduling barriers below order machine instructions, this orders the IR.
 __device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
 
-// One step of the software pipeline, for block j, entered with
-//   s_cur    scores of block j, phase A already done (ref_cur); holds block j+1's on return
-// It runs  K Q^T of block j+1 -> s_nxt  (matrix cores)  |  phase B of block j -> p   (vector ALUs)
-// then     O += P V of block j          (matrix cores)  |  phase A of block j+1 -> ref_nxt
-// as ONE interleaved instruction stream: an MFMA, a slice of vector work, pinned by a scheduling
-// barrier -- a wavefront has its SIMD to itself, so nothing else would fill the matrix cores
-// while it runs the softmax.  Without a next block (have_nxt false) slot_nxt is any landed slot:
-// the scores are computed and dropped.
+// Rare path of the lazy reference: take the true row maxima of the (masked) scores of the
+// current block, move the references that are unset or too low, bring O and l to them, and
+// recompute the block's probabilities.
+template <int RB>
+__device__ __forceinline__ void set_reference(const f32x16 (&s_cur)[RB], float sc2, WaveState<RB>& st,
+                                              float (&psum)[RB], bf16x8 (&p)[RB][2]) {
+    float alpha[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const float mx = max_halves(max16(s_cur[rb])) * sc2;
+        const float m_old = st.m[rb];
+        const float m_new = (m_old == -INFINITY || mx > m_old + kLazy) ? mx : m_old;
+        alpha[rb] = m_old == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_old - m_new);     // O = l = 0 while unset
+        st.m[rb] = m_new;
+        st.l[rb] *= alpha[rb];
+    }
+    rescale<RB>(st, alpha);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        psum[rb] = 0.f;
+        const float m_use = ref_use(st.m[rb]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) softmax_pair<RB>(s_cur, rb, k, sc2, m_use, psum, p);
+    }
+}
+
+// One step of the software pipeline, for block j, entered with its (masked) scores in s_cur.
+// It runs  K Q^T of block j+1 -> s_nxt  (matrix cores)  |  softmax of block j -> p     (vector ALUs)
+// then     O += P V of block j          (matrix cores)  |  s_cur <- s_nxt
+// as an interleaved instruction stream: an MFMA, then a slice of vector work, pinned by
+// scheduling barriers.  Without a next block (have_nxt false) slot_nxt is any landed slot: the
+// scores are computed and dropped.
 template <int RB>
 __device__ __forceinline__ void pipeline_step(const char* slot_cur, const char* slot_nxt, const LaneOffsets& lo,
                                               const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
-                                              f32x16 (&s_cur)[RB], f32x16 (&s_nxt)[RB],
-                                              RowRef<RB>& ref_cur, RowRef<RB>& ref_nxt,
-                                              bool have_nxt, const Block& nb, bool nxt_masked, const int (&lim)[RB]) {
-    // O holds blocks < j at the previous reference: bring it to block j's.  Rare: probabilities
-    // and sums are fp32/bf16 with 8 exponent bits, so a reference 2^kLazy below the running
-    // maximum loses no precision, and the reference only moves on a larger jump than that.
-    if (__builtin_expect(__builtin_amdgcn_ballot_w64(ref_cur.moved) != 0, 0)) rescale<RB>(st, ref_cur.alpha);
-
-    // ---- first half: 8*RB MFMAs of K Q^T, 8*RB slices of phase B
+                                              f32x16 (&s_cur)[RB], const Block& nb, bool nxt_masked, const int (&lim)[RB]) {
+    // ---- first half: 8*RB MFMAs of K Q^T, 8*RB slices of the softmax
+    f32x16 s_nxt[RB];
     bf16x8 p[RB][2];
+    float psum[RB], m_use[RB];
     bf16x8 kf[8];
     kf[0] = read_k_frag(slot_nxt, lo, 0);
     kf[1] = read_k_frag(slot_nxt, lo, 1);
+    kf[2] = read_k_frag(slot_nxt, lo, 2);
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+    for (int rb = 0; rb < RB; ++rb) {
+        psum[rb] = 0.f;
+        m_use[rb] = ref_use(st.m[rb]);
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_nxt[rb][r] = 0.f;
+    }
     // two slices ahead of the first MFMA cover the latency of the first fragment reads
-    phase_b_pair<RB>(s_cur, 0, 0, sc2, ref_cur, p);
-    phase_b_pair<RB>(s_cur, 0, 1, sc2, ref_cur, p);
-    pin(ref_cur.psum[0]);
+    softmax_pair<RB>(s_cur, 0, 0, sc2, m_use[0], psum, p);
+    softmax_pair<RB>(s_cur, 0, 1, sc2, m_use[0], psum, p);
+    pin(psum[0]);
     __builtin_amdgcn_sched_barrier(0);
     bf16x8 vf[8];
 #pragma unroll
     for (int n = 0; n < 8 * RB; ++n) {
         const int ks = n / RB, rb = n % RB;
-        if (rb == 0 && ks + 2 < 8) kf[ks + 2] = read_k_frag(slot_nxt, lo, ks + 2);
-        if (rb == 0 && ks == 6) vf[0] = read_v_frag(slot_cur, lo, 0);
-        if (rb == 0 && ks == 7) vf[1] = read_v_frag(slot_cur, lo, 1);
+        if (rb == 0 && ks + 3 < 8) kf[ks + 3] = read_k_frag(slot_nxt, lo, ks + 3);
+        if (rb == 0 && ks == 5) vf[0] = read_v_frag(slot_cur, lo, 0);
+        if (rb == 0 && ks == 6) vf[1] = read_v_frag(slot_cur, lo, 1);
+        if (rb == 0 && ks == 7) vf[2] = read_v_frag(slot_cur, lo, 2);
+#ifdef APE_X_NOMFMA
+        s_nxt[rb][ks] += __builtin_bit_cast(f32x4, kf[ks])[0] * __builtin_bit_cast(f32x4, qf[rb][ks])[1];
+#else
         s_nxt[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_nxt[rb], 0, 0, 0);
+#endif
         __builtin_amdgcn_sched_barrier(0);
-        const int slice = n + 2;                                     // (row block, register pair) of phase B
+        const int slice = n + 2;                                     // (row block, register pair)
         if (slice < 8 * RB) {
-            phase_b_pair<RB>(s_cur, slice / 8, slice % 8, sc2, ref_cur, p);
-            pin(ref_cur.psum[slice / 8]);
+            softmax_pair<RB>(s_cur, slice / 8, slice % 8, sc2, m_use[slice / 8], psum, p);
+            pin(psum[slice / 8]);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    // ---- did every probability stay in range, and is every row that saw a key referenced?
+    bool bad = false;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) st.l[rb] = st.l[rb] * ref_cur.alpha[rb] + ref_cur.psum[rb];
+    for (int rb = 0; rb < RB; ++rb)
+        bad |= !(psum[rb] <= 0x1p40f) || (st.m[rb] == -INFINITY && psum[rb] > 0.f);
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) set_reference<RB>(s_cur, sc2, st, psum, p);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb];
 
-    // ---- second half: 8*RB MFMAs of O += P V; in their shadow the scores of block j+1 move from
-    //      the MFMA accumulators into the vector registers of s_cur (block j's scores are dead
-    //      now) and go through phase A
-    float m_keep[RB], mx[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) m_keep[rb] = st.m[rb];
-    ref_nxt.moved = false;
-    vf[2] = read_v_frag(slot_cur, lo, 2);
+    // ---- second half: 8*RB MFMAs of O += P V; in their shadow the scores of block j+1 become s_cur
 #pragma unroll
     for (int n = 0; n < 8 * RB; ++n) {
         const int f = n / RB, rb = n % RB;                           // fragment f = sl*4 + db
         if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
+#ifdef APE_X_NOMFMA
+        st.o[rb][f & 3][f] += __builtin_bit_cast(f32x4, vf[f])[0] * __builtin_bit_cast(f32x4, p[rb][f >> 2])[1];
+#else
         st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
+#endif
         __builtin_amdgcn_sched_barrier(0);
-        // vector slices: 4 x (move 8 scores of a row block + their maximum), then the row references
         if (n < 4 * RB) {
             const int r2 = n / 4, part = n % 4;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) s_cur[r2][4 * part + e] = s_nxt[r2][4 * part + e];
-            const float m4 = fmaxf(fmaxf(s_cur[r2][4 * part], s_cur[r2][4 * part + 1]),
-                                   fmaxf(s_cur[r2][4 * part + 2], s_cur[r2][4 * part + 3]));
-            mx[r2] = part == 0 ? m4 : fmaxf(mx[r2], m4);
-            pin(mx[r2]);
-        } else if (n < 5 * RB) {
-            phase_a_finish<RB>(mx[n - 4 * RB], n - 4 * RB, sc2, st, ref_nxt);
-            pin(ref_nxt.alpha[n - 4 * RB]);
+            for (int e = 0; e < 4; ++e) {
+                float t = s_nxt[r2][4 * part + e];
+                pin(t);
+                s_cur[r2][4 * part + e] = t;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-    if (__builtin_expect(nxt_masked, 0)) {
-        // rare (block tails, the causal diagonal): redo phase A on the masked scores
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) st.m[rb] = m_keep[rb];
-        ref_nxt.moved = false;
-        apply_mask<RB>(s_cur, nb, lim);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) phase_a_row<RB>(s_cur, rb, sc2, st, ref_nxt);
-    }
-    if (!have_nxt) {                                                 // nothing was there: keep the references
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) st.m[rb] = m_keep[rb];
-        ref_nxt.moved = false;
-    }
+    if (__builtin_expect(nxt_masked, 0)) apply_mask<RB>(s_cur, nb, lim);   // block tails, the causal diagonal
 }
 
-// Streams every block of the walk.  Two copies of the walker run: `lw` feeds the loads (RING-1
-// blocks ahead), `cw` describes the blocks being computed.  Every wavefront of the workgroup
+// Streams every block of the walk `lw`.  Every wavefront of the workgroup
 // executes the same barriers and the same instruction stream; causal blocks a wavefront's rows
 // do not see are simply masked.
 //   vis_lo smallest causal limit among this wavefront's rows (blocks up to it need no causal mask)
+#ifdef APE_TIMING
+#define APE_T(i) do { const unsigned long long t__ = __builtin_amdgcn_s_memtime(); tacc[i] += t__ - tlast; tlast = __builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define APE_T(i) do { } while (0)
+#endif
+
 template <int RB>
-__device__ __forceinline__ void run_blocks(Walk lw, Walk cw, long stride_b, char* lds, const bf16x8 (&qf)[RB][8],
-                                           WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo) {
+__device__ __forceinline__ void run_blocks(Walk lw, long stride_b, char* lds, const bf16x8 (&qf)[RB][8],
+                                           WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo, unsigned long long* tdbg = nullptr) {
+#ifdef APE_TIMING
+    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
+    unsigned long long tlast = __builtin_amdgcn_s_memtime();
+#endif
     const LaneOffsets lo = lane_offsets();
     const LoadOffsets full = load_offsets(stride_b, BLK);
-    Block lb;
-    int issued = 0;                                   // blocks whose loads have been issued
-    bool more = true;
-    while (issued < RING - 1 && more) {
-        more = lw.next(lb);
-        if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full); ++issued; }
+    // Loads run RING-1 blocks ahead of the compute.  What the compute needs to know of a block
+    // in flight (valid rows, causal index of row 0) waits in a small FIFO: entry i describes
+    // block j+1+i at the top of step j; n_valid == 0 marks "no such block".
+    constexpr int FIFO = RING - 2;
+    int f_nv[FIFO], f_j0[FIFO];
+    Block lb, cb;
+    bool more = lw.next(cb);
+    if (!more) return;
+    issue_block_loads(cb, stride_b, lds, full);
+    int issued = 1;                                   // blocks whose loads have been issued
+#pragma unroll
+    for (int i = 0; i < FIFO; ++i) {
+        f_nv[i] = 0; f_j0[i] = -1;
+        if (more) {
+            more = lw.next(lb);
+            if (more) {
+                issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full);
+                ++issued;
+                f_nv[i] = lb.n_valid; f_j0[i] = lb.j0;
+            }
+        }
     }
-    if (issued == 0) return;
 
-    f32x16 s_cur[RB], s_nxt[RB];                      // scores of blocks j and j+1
-    RowRef<RB> ref_cur, ref_nxt;
-    Block cb, nb;
-    bool have_cur = cw.next(cb);                      // block 0 (exists: issued > 0)
-    auto masked = [&](const Block& b) { return b.n_valid < BLK || (b.j0 >= 0 && b.j0 + BLK - 1 > vis_lo); };
+    f32x16 s_cur[RB];                                 // (masked) scores of block j
+    auto masked = [&](int n_valid, int j0) { return n_valid < BLK || (j0 >= 0 && j0 + BLK - 1 > vis_lo); };
 
-    // block 0: scores and phase A
+    // block 0: scores (its reference is set by the first step's check)
     wait_vmcnt(issued - 1);
     ring_barrier();
     scores<RB>(lds, lo, qf, s_cur);
-    if (masked(cb)) apply_mask<RB>(s_cur, cb, lim);
-    ref_cur.moved = false;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) phase_a_row<RB>(s_cur, rb, sc2, st, ref_cur);
+    if (masked(cb.n_valid, cb.j0)) apply_mask<RB>(s_cur, cb, lim);
 
+    APE_T(0);
+    bool have_cur = true;
     for (int j = 0; have_cur; ++j) {
-        // block j+1 must have landed; every wavefront is then also done with block j-1's slot,
-        // which the next loads overwrite
-        const bool have_nxt = cw.next(nb);
+        // block j+1: pop its description
+        Block nb;
+        nb.k = nb.v = nullptr; nb.n_valid = f_nv[0]; nb.j0 = f_j0[0];
+        const bool have_nxt = nb.n_valid > 0;
+#pragma unroll
+        for (int i = 0; i + 1 < FIFO; ++i) { f_nv[i] = f_nv[i + 1]; f_j0[i] = f_j0[i + 1]; }
+        f_nv[FIFO - 1] = 0; f_j0[FIFO - 1] = -1;
+        APE_T(1);
         if (have_nxt) {
+            // block j+1 must have landed; every wavefront is then also done with block j-1's
+            // slot, which the next loads overwrite
+#ifndef APE_X_NOLOAD
             wait_vmcnt(issued - (j + 2));
+#endif
+            APE_T(2);
+#ifndef APE_X_NOBARRIER
             ring_barrier();
+#endif
+            APE_T(3);
             if (more) {
                 more = lw.next(lb);
-                if (more) { issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full); ++issued; }
+                if (more) {
+#ifndef APE_X_NOLOAD
+                    issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full);
+#endif
+                    ++issued;
+                    f_nv[FIFO - 1] = lb.n_valid; f_j0[FIFO - 1] = lb.j0;
+                }
             }
         }
         const char* slot_cur = lds + (j % RING) * SLOTB;
         const char* slot_nxt = have_nxt ? lds + ((j + 1) % RING) * SLOTB : slot_cur;
-        pipeline_step<RB>(slot_cur, slot_nxt, lo, qf, st, sc2, s_cur, s_nxt, ref_cur, ref_nxt,
-                          have_nxt, nb, have_nxt && masked(nb), lim);
-        ref_cur = ref_nxt;                            // (s_cur already holds block j+1's scores)
-        cb = nb; have_cur = have_nxt;
+        APE_T(4);
+        pipeline_step<RB>(slot_cur, slot_nxt, lo, qf, st, sc2, s_cur, nb, have_nxt && masked(nb.n_valid, nb.j0), lim);
+        have_cur = have_nxt;
+        APE_T(5);
     }
+#ifdef APE_TIMING
+    if (tdbg && threadIdx.x == 0 && blockIdx.x == 0)
+        for (int i = 0; i < 6; ++i) tdbg[i] = tacc[i];
+#endif
 }
 
 template <int RB>
@@ -603,7 +652,11 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
                       (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
         vis_lo = tok_lo + causal_off; vis_hi = tok_hi + causal_off;
     }
-    run_blocks<RB>(walk, walk, stride_b, lds, qf, st, sc2, lim, vis_lo);
+#ifdef APE_TIMING
+    run_blocks<RB>(walk, stride_b, lds, qf, st, sc2, lim, vis_lo, (unsigned long long*)(a.part_lse + (long)60 * a.units_total));
+#else
+    run_blocks<RB>(walk, stride_b, lds, qf, st, sc2, lim, vis_lo);
+#endif
 
     // ---- block result (Appendix C.1): normalised values + natural-log LogSumExp
 #pragma unroll
@@ -675,7 +728,7 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
     walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
               (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
               wg_tok_hi + 1, stride_b);
-    run_blocks<RB>(walk, walk, stride_b, lds, qf, st, 0.08838834764831845f * LOG2E, lim, tok_lo);
+    run_blocks<RB>(walk, stride_b, lds, qf, st, 0.08838834764831845f * LOG2E, lim, tok_lo);
 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -737,7 +790,11 @@ hipError_t launch_encode_g(int group, const EncodeArgs& a, unsigned grid, int n_
 
 }  // namespace
 
+#ifdef APE_X_RB1
+int flash_block_rows(int rows_per_kv_head) { return 128; }
+#else
 int flash_block_rows(int rows_per_kv_head) { return rows_per_kv_head > 128 ? 256 : 128; }
+#endif
 
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
