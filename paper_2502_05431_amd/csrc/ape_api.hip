@@ -197,7 +197,7 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
     } else {
         const int rows = q_len * si.group;
         const int base = si.mfma ? si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
-        plan = plan_query(base, max_ctx, si.mfma ? 256 : 256, si.mfma ? 512 : 1024);
+        plan = plan_query(base, max_ctx, si.mfma ? 256 : 256, si.mfma ? 256 : 1024);
     }
     const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
     if (!workspace || workspace_bytes < need)

@@ -17,8 +17,13 @@
 //     row in one lane (and its partner lane +32), so the softmax row reductions are in-lane,
 //     and the bf16 probabilities are already laid out as the B operand of O^T += V^T P^T;
 //   - V^T fragments come from LDS through the transposing read ds_read_b64_tr_b16;
-//   - the loop is software-pipelined: while the vector ALUs run the softmax of block j, the
-//     matrix cores run O += P V of block j-1 and K Q^T of block j+1.
+//   - the loop is software-pipelined over three blocks: one body runs O += P V of block j-1,
+//     then K Q^T of block j+1 with the softmax of block j in the shadow of its MFMAs;
+//   - the softmax keeps a lazily updated reference instead of a running maximum, so its fast
+//     path is two exponentials, two adds and a conversion per pair of scores;
+//   - stretches of full, unmasked blocks of one segment run a branch-free body; segment ends,
+//     partial blocks and the causal diagonal take a generic body with the same arithmetic.
+// The file is compiled with the MFMA accumulators in the vector registers (VGPR form).
 #include "ape_internal.h"
 
 #include <math.h>
@@ -46,98 +51,98 @@ constexpr int NW = NT / 64;                  // wavefronts
 constexpr int ROWB = D * 2;                  // bytes of one head's K or V row
 constexpr int KVB = BLK * ROWB;              // 8 KB: one block of K (or V) rows
 constexpr int SLOTB = 2 * KVB;               // K rows then V rows
-#ifndef APE_X_RING
-#define APE_X_RING 6
-#endif
-constexpr int RING = APE_X_RING;                      // LDS slots: blocks j, j+1 in use, 4 more in flight
-constexpr int LDSB = RING * SLOTB;           // 96 KB
 constexpr int LOADS_PER_BLOCK = 4;           // direct-to-LDS load instructions per wavefront per block
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
-constexpr float kLazy = 40.f;                // the reference maximum moves only when exceeded by 2^kLazy
+constexpr float kLazy = 40.f;                // a reference moves only when exceeded by 2^kLazy
+constexpr float kUnset = -1.0e30f;           // reference of a row that has not seen a key yet
+constexpr float kPsumMax = 0x1p40f;          // a lane's block sum above this: some probability left the safe range
 
-// One KV block: n_valid (1..32) consecutive tokens of one segment.
-struct Block {
-    const char* k;        // row 0 of the block for this KV head
-    const char* v;
-    int n_valid;
-    int j0;               // index of row 0 inside the causal segment, or -1 (no causal mask)
-};
+// LDS slots of the ring (blocks j and j+1 in use, the others in flight), by row blocks per
+// wavefront: the wide tile runs one workgroup per CU and looks further ahead; the narrow tile
+// leaves room for two workgroups per CU, whose wavefronts fill each other's issue gaps.
+template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 
-// Block source of one workgroup.  Two modes share one type (and therefore one instantiation of
-// the pipeline): a range [t, t1) of the pooled contexts walked through the chunk table (blocks
-// stop at chunk ends, no mask), or a plain segment (the prefix, no mask) followed by a causal
-// segment (self KV / own chunk).
-struct Walk {
-    // context mode (cu != NULL); the tables are read with scalar loads, once per chunk
+// A block = n_valid (1..32) consecutive tokens of one segment, described to the compute side by
+// one integer: n_valid | (j0 + 1) << 6, j0 = index of row 0 inside its causal segment or -1 (no
+// causal mask).  0 = no block.
+__device__ __forceinline__ int desc_n(int d) { return d & 63; }
+__device__ __forceinline__ int desc_j0(int d) { return (d >> 6) - 1; }
+
+// The K/V rows of one workgroup as a stream of blocks: a list of segments (runs of rows at a fixed
+// stride), each cut into blocks of 32 rows.  Two segment sources share the type (and therefore
+// one instantiation of the pipeline): a range [t, t1) of the pooled contexts, cut at chunk ends
+// through the chunk table (no mask), or a plain segment (the prefix) followed by a causal one
+// (self KV / own chunk).  Everything here is wavefront-uniform and lives in scalar registers;
+// the per-block path is a handful of scalar instructions, the tables are read (with scalar
+// loads) only when a segment ends.
+struct Stream {
+    const char *k, *v;               // row 0 of the next block (this KV head)
+    int rem;                         // rows left in the current segment; 0 = stream exhausted
+    int run;                         // full blocks handed out back to back from the current segment
+    int j0, jstep;                   // causal index of that row (-1: none) and its step per block
+    long stride_b, head_b;
+    // context source (cu != NULL)
     const int32_t* cu;
     const void* const* k_chunks;
     const void* const* v_chunks;
-    const char *kbase, *vbase;       // rows of the current chunk for this KV head
-    int n_chunks, c;
-    int t, t1, c0, c1;
-    long head_b;
-    // sequence mode
-    const char *kp, *vp, *kc, *vc;
-    int np, nc, j, phase;
-    long stride_b;
+    int n_chunks, c, c0, c1, t, t1;  // chunk c = [c0, c1) holds pooled index t, the next undelivered row
+    // sequence source: the causal segment still to come (nc == 0: none)
+    const char *kc, *vc;
+    int nc;
 
-    __device__ void load_chunk() {
-        kbase = (const char*)scalar_load_ptr(k_chunks + c) + head_b;
-        vbase = (const char*)scalar_load_ptr(v_chunks + c) + head_b;
+    // Opens the segment that starts at pooled index t (t < t1).
+    __device__ __forceinline__ void open_ctx() {
+        while (t >= c1) {                                          // skip empty chunks
+            if (c + 1 >= n_chunks) return;                         // table shorter than total_ctx: stop, stay in bounds
+            ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
+        }
+        const long off = (long)(t - c0) * stride_b + head_b;
+        k = (const char*)scalar_load_ptr(k_chunks + c) + off;
+        v = (const char*)scalar_load_ptr(v_chunks + c) + off;
+        const int e = c1 < t1 ? c1 : t1;
+        rem = e - t; t = e;
     }
-    __device__ void init_ctx(const KvView& kv, long t0_, long t1_, long stride_b_, long head_b_) {
+    __device__ __forceinline__ void init_ctx(const KvView& kv, int t0_, int t1_, long stride_b_, long head_b_) {
         cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
-        t = (int)t0_; t1 = (int)t1_; stride_b = stride_b_; head_b = head_b_;
-        c = 0; c0 = 0; c1 = 0; kbase = vbase = nullptr;
-        kp = vp = kc = vc = nullptr; np = nc = j = 0; phase = 2;
-        if (t < t1 && cu != nullptr) {
+        stride_b = stride_b_; head_b = head_b_;
+        k = v = kc = vc = nullptr; nc = 0; rem = 0; run = 0; j0 = -1; jstep = 0;
+        t = t0_; t1 = t1_; c = 0; c0 = c1 = 0;
+        if (t < t1 && cu != nullptr && n_chunks > 0) {
             int lo = 0, hi = n_chunks - 1;
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
                 if (scalar_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
             }
             c = lo; c0 = scalar_load_i32(cu + c); c1 = scalar_load_i32(cu + c + 1);
-            load_chunk();
-        } else {
-            t1 = t;
+            open_ctx();
         }
     }
-    __device__ void init_seq(const char* kp_, const char* vp_, int np_, const char* kc_, const char* vc_, int nc_, long stride_b_) {
-        cu = nullptr; k_chunks = v_chunks = nullptr; kbase = vbase = nullptr; n_chunks = c = 0; t = t1 = c0 = c1 = 0; head_b = 0;
-        kp = kp_; vp = vp_; np = np_; kc = kc_; vc = vc_; nc = nc_; stride_b = stride_b_;
-        j = 0; phase = np > 0 ? 0 : 1;
+    __device__ __forceinline__ void init_seq(const char* kp, const char* vp, int np, const char* kc_, const char* vc_, int nc_, long stride_b_) {
+        cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = c = c0 = c1 = t = t1 = 0; head_b = 0;
+        stride_b = stride_b_;
+        kc = kc_; vc = vc_; nc = nc_;
+        k = kp; v = vp; rem = np; run = 0; j0 = -1; jstep = 0;
+        if (rem == 0) next_segment();
     }
-    __device__ bool next(Block& b) {
+    __device__ __forceinline__ void next_segment() {
+        run = 0;
         if (cu != nullptr) {
-            if (t >= t1) return false;
-            if (t >= c1) {
-                do {                                                   // next non-empty chunk
-                    if (c + 1 >= n_chunks) { t = t1; return false; }   // table shorter than total_ctx: stop, stay in bounds
-                    ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
-                } while (t >= c1);
-                load_chunk();
-            }
-            const int e = c1 < t1 ? c1 : t1;
-            const int n = e - t < BLK ? e - t : BLK;
-            b.k = kbase + (long)(t - c0) * stride_b;
-            b.v = vbase + (long)(t - c0) * stride_b;
-            b.n_valid = n; b.j0 = -1;
-            t += n;
-            return true;
+            if (t < t1) open_ctx();
+        } else if (nc > 0) {
+            k = kc; v = vc; rem = nc; nc = 0; j0 = 0; jstep = BLK;
         }
-        if (phase == 0) {
-            const int n = np - j < BLK ? np - j : BLK;
-            b.k = kp + (long)j * stride_b; b.v = vp + (long)j * stride_b; b.n_valid = n; b.j0 = -1;
-            j += n;
-            if (j >= np) { phase = 1; j = 0; }
-            return true;
-        }
-        if (phase != 1 || j >= nc) return false;
-        const int n = nc - j < BLK ? nc - j : BLK;
-        b.k = kc + (long)j * stride_b; b.v = vc + (long)j * stride_b; b.n_valid = n; b.j0 = j;
-        j += n;
-        return true;
+    }
+    // Hands out the next block (rem > 0) and steps past it.
+    __device__ __forceinline__ int take(const char*& bk, const char*& bv) {
+        const int n = rem < BLK ? rem : BLK;
+        const int d = n | ((j0 + 1) << 6);
+        bk = k; bv = v;
+        k += BLK * stride_b; v += BLK * stride_b;
+        rem -= n; j0 += jstep;
+        run = n == BLK ? run + 1 : 0;
+        if (__builtin_expect(rem == 0, 0)) next_segment();
+        return d;
     }
 };
 
@@ -166,27 +171,52 @@ __device__ __forceinline__ LoadOffsets load_offsets(long stride_b, int n_valid) 
     return o;
 }
 
-// `full` holds the offsets of a full block (computed once); a partial block recomputes them with
-// its rows clamped.  The block's base pointers are wavefront-uniform, the offsets 32-bit per lane.
-__device__ __forceinline__ void issue_block_loads(const Block& b, long stride_b, char* slot, const LoadOffsets& full) {
+// One direct global->LDS load: every lane fetches 16 bytes at base + voff (base wavefront-uniform,
+// voff per lane) and the wavefront's 1 KB lands at the wavefront-uniform LDS address lds_dst (M0).
+// Written as instructions: the scalar-base addressing form costs no vector address arithmetic,
+// and the compiler then does not track these loads, which is intended -- they are ordered against
+// the LDS reads by the explicit vmcnt waits and barriers of the ring, not by the compiler, which
+// could only wait for all of them.
+__device__ __forceinline__ void dma16(const char* base, uint32_t voff, const char* lds_dst) {
+    const uint32_t m0v = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_dst;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(base), "s"(m0v) : "m0");
+}
+
+// Load i (0..3) of a block: wavefront w fills rows 8w + 4(i/2) .. +3 of K (i even) or V (i odd).
+__device__ __forceinline__ void issue_block_load(int i, const char* bk, const char* bv, char* slot, const LoadOffsets& o) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const char* dst = slot + (8 * wave + 4 * (i >> 1)) * ROWB;
+    if ((i & 1) == 0) dma16(bk, o.k[i >> 1], dst);
+    else dma16(bv, o.v[i >> 1], dst + KVB);
+}
+
+// `full` holds the offsets of a full block (computed once); a partial block recomputes them with
+// its rows clamped.
+__device__ __forceinline__ void issue_block_loads(const char* bk, const char* bv, int n_valid, long stride_b, char* slot,
+                                                  const LoadOffsets& full) {
     LoadOffsets o = full;
-    if (b.n_valid < BLK) o = load_offsets(stride_b, b.n_valid);
+    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets(stride_b, n_valid);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        char* dst = slot + (8 * wave + 4 * i) * ROWB;
-        __builtin_amdgcn_global_load_lds((glb_void*)(b.k + o.k[i]), (lds_void*)dst, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void*)(b.v + o.v[i]), (lds_void*)(dst + KVB), 16, 0, 0);
-    }
+    for (int i = 0; i < LOADS_PER_BLOCK; ++i) issue_block_load(i, bk, bv, slot, o);
+}
+
+// Takes the stream's next block and starts its loads into `slot`.
+__device__ __forceinline__ int issue_next(Stream& ld, char* slot, const LoadOffsets& full) {
+    const char *bk, *bv;
+    const int d = ld.take(bk, bv);
+    issue_block_loads(bk, bv, desc_n(d), ld.stride_b, slot, full);
+    return d;
 }
 
 // s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14]).
-// The direct-to-LDS loads complete in issue order; `blocks_younger` blocks may stay in flight.
-__device__ __forceinline__ void wait_vmcnt(int blocks_younger) {
-    if (blocks_younger >= 3) __builtin_amdgcn_s_waitcnt(0x0f70 | (3 * LOADS_PER_BLOCK));
-    else if (blocks_younger == 2) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * LOADS_PER_BLOCK));
-    else if (blocks_younger == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | LOADS_PER_BLOCK);
-    else __builtin_amdgcn_s_waitcnt(0x0f70);
+// The direct-to-LDS loads complete in issue order, so "all but the youngest n blocks have
+// landed" is vmcnt(n * LOADS_PER_BLOCK).
+template <int BLOCKS_YOUNGER>
+__device__ __forceinline__ void wait_blocks() {
+    constexpr int n = BLOCKS_YOUNGER * LOADS_PER_BLOCK;
+    static_assert(n < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (n & 15) | ((n >> 4) << 14));
 }
 
 // Workgroup barrier that the compiler may not move memory operations across, without the
@@ -197,17 +227,9 @@ __device__ __forceinline__ void ring_barrier() {
     asm volatile("" ::: "memory");
 }
 
-// The transposing LDS read.  The pointer is passed through a restrict-qualified parameter on
-// purpose: once inlined, the read carries alias-scope information, like the plain K reads carry
-// type information.  The compiler's wait-count pass drains ALL outstanding global->LDS loads
-// before an LDS read it knows nothing about -- which would serialise the ring -- and leaves
-// reads with alias information to the explicit wait_vmcnt()/barrier protocol below.
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-__device__ __forceinline__ s16x4 lds_read_tr_raw(lds_s16x4* __restrict__ p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(p);
-}
 __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
-    return __builtin_bit_cast(bf16x4, lds_read_tr_raw((lds_s16x4*)p));
+    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+    return __builtin_bit_cast(bf16x4, r);
 }
 
 // max over the two half-wavefronts (query row = lane & 31 lives in lanes l and l ^ 32)
@@ -282,7 +304,8 @@ __device__ __forceinline__ void accumulate(const char* slot, const LaneOffsets& 
 // Masks of a block (tail, causal diagonal); accumulator register r holds token
 // 8*(r/4) + 4*hi + (r%4) of the block for query row lane & 31.
 template <int RB>
-__device__ __forceinline__ void apply_mask(f32x16 (&s)[RB], const Block& b, const int (&lim)[RB]) {
+__device__ __forceinline__ void apply_mask(f32x16 (&s)[RB], int desc, const int (&lim)[RB]) {
+    const int n_valid = desc_n(desc), j0 = desc_j0(desc);
     const int hi = (threadIdx.x & 63) >> 5;
     // keep the vector writes below clear of the matrix-core writes to the same registers
     asm volatile("s_nop 15");
@@ -290,7 +313,7 @@ __device__ __forceinline__ void apply_mask(f32x16 (&s)[RB], const Block& b, cons
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         // tokens of the block this row sees: [0, nvis)
-        const int nvis = b.j0 >= 0 ? min(b.n_valid, lim[rb] - b.j0 + 1) : b.n_valid;
+        const int nvis = j0 >= 0 ? min(n_valid, lim[rb] - j0 + 1) : n_valid;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int tok = 8 * (r >> 2) + 4 * hi + (r & 3);
@@ -303,34 +326,34 @@ __device__ __forceinline__ void apply_mask(f32x16 (&s)[RB], const Block& b, cons
 // Probabilities are taken against a per-row reference m (log2 units): p = 2^(s*sc2 - m).  fp32 and
 // bf16 both carry 8 exponent bits, so m need not be the running maximum: any m within 2^kLazy of
 // it loses no precision.  The fast path therefore never computes a maximum; it only checks,
-// from the row sums it needs anyway, that no probability left the safe range -- or that a row
-// whose reference is still unset (-inf) has just seen its first keys -- and in that rare case
-// runs set_reference(), which takes the true row maxima, rescales O and l, and redoes the block.
+// from the block sums it needs anyway, that no probability left the safe range.  A row that has
+// not seen a key yet carries the reference kUnset, against which every finite score overflows,
+// so its first keys trip the same check.  Then set_reference() takes the true row maxima,
+// rescales O and l, and redoes the block's probabilities.
 __device__ __forceinline__ float max16(const f32x16& s) {
     return fmaxf(fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7]))),
                  fmaxf(fmaxf(fmaxf(s[8], s[9]), fmaxf(s[10], s[11])), fmaxf(fmaxf(s[12], s[13]), fmaxf(s[14], s[15]))));
 }
 
-// Two scores -> two bf16 probabilities (register pair k of row block rb).  The row sum is taken
-// over the ROUNDED probabilities, the ones the PV product uses.
+// The softmax of a block is cut into slices of two scores (register pair k of row block rb):
+// two exponentials, their fp32 row sum, one packed conversion to bf16.  (The row sum is taken in
+// plain fp32 adds on purpose: the bf16 dot-product instruction would do it in one instruction,
+// but it does not overlap with a running MFMA, which these do.)  The conversion is written as an
+// instruction so that it stays in its slice; it lists the new sums as inputs only to be ordered
+// after them, which also keeps it clear of the exponentials it reads.
+// p[rb][sl] holds the probabilities of k-slab sl as four packed pairs.
 template <int RB>
-__device__ __forceinline__ void softmax_pair(const f32x16 (&s)[RB], int rb, int k, float sc2, float m_use,
-                                             float (&psum)[RB], bf16x8 (&p)[RB][2]) {
+__device__ __forceinline__ void softmax_slice(const f32x16 (&s)[RB], int rb, int k, float sc2, float m,
+                                              float (&psum)[RB][2], u32x4 (&p)[RB][2]) {
     const int r = 2 * k;
-    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -m_use));
-    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[rb][r + 1], sc2, -m_use));
-    bf16x2 pk;
-    pk[0] = (__bf16)p0; pk[1] = (__bf16)p1;
-    const bf16x2 ones = {(__bf16)1.f, (__bf16)1.f};
-#ifdef APE_X_NOSOFTMAX
-    if (k) return;
-#endif
-    psum[rb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum[rb], false);
-    p[rb][r >> 3][r & 7] = pk[0];
-    p[rb][r >> 3][(r & 7) + 1] = pk[1];
+    const float e0 = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -m));
+    const float e1 = __builtin_amdgcn_exp2f(fmaf(s[rb][r + 1], sc2, -m));
+    psum[rb][0] += e0;
+    psum[rb][1] += e1;
+    uint32_t pk;
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(e0), "v"(e1), "v"(psum[rb][0]), "v"(psum[rb][1]));
+    p[rb][r >> 3][(r & 7) >> 1] = pk;
 }
-
-__device__ __forceinline__ float ref_use(float m) { return m == -INFINITY ? 0.f : m; }
 
 // O *= alpha (per query row).  The file is built with VGPR-form MFMAs (accumulators in the
 // vector registers), so this is a plain multiply; it is kept clear of the matrix-core writes.
@@ -347,16 +370,10 @@ __device__ __forceinline__ void rescale(WaveState<RB>& st, const float (&alpha)[
 }
 
 __device__ __forceinline__ bf16x8 read_k_frag(const char* slot, const LaneOffsets& lo, int ks) {
-#ifdef APE_X_NOKREAD
-    { u32x4 w = {(unsigned)lo.k, (unsigned)ks, (unsigned)(size_t)slot, 1u}; return __builtin_bit_cast(bf16x8, w); }
-#endif
     return *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
 }
 // V^T fragment f = sl*4 + db
 __device__ __forceinline__ bf16x8 read_v_frag(const char* slot, const LaneOffsets& lo, int f) {
-#ifdef APE_X_NOVREAD
-    { u32x4 w = {(unsigned)lo.v[f & 3], (unsigned)f, (unsigned)(size_t)slot, 1u}; return __builtin_bit_cast(bf16x8, w); }
-#endif
     const bf16x4 lo4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2));
     const bf16x4 hi4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2) + 2048);
     return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -371,214 +388,297 @@ __device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
 // recompute the block's probabilities.
 template <int RB>
 __device__ __forceinline__ void set_reference(const f32x16 (&s_cur)[RB], float sc2, WaveState<RB>& st,
-                                              float (&psum)[RB], bf16x8 (&p)[RB][2]) {
+                                              float (&psum)[RB][2], u32x4 (&p)[RB][2]) {
     float alpha[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const float mx = max_halves(max16(s_cur[rb])) * sc2;
+        const float mx = max_halves(max16(s_cur[rb])) * sc2;             // -inf: the row sees nothing here
         const float m_old = st.m[rb];
-        const float m_new = (m_old == -INFINITY || mx > m_old + kLazy) ? mx : m_old;
-        alpha[rb] = m_old == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_old - m_new);     // O = l = 0 while unset
+        const float m_new = mx > m_old + kLazy ? mx : m_old;             // (kUnset + kLazy == kUnset)
+        alpha[rb] = __builtin_amdgcn_exp2f(m_old - m_new);               // unset -> set: 0, and O = l = 0 anyway
         st.m[rb] = m_new;
         st.l[rb] *= alpha[rb];
     }
     rescale<RB>(st, alpha);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        psum[rb] = 0.f;
-        const float m_use = ref_use(st.m[rb]);
+        psum[rb][0] = psum[rb][1] = 0.f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) softmax_pair<RB>(s_cur, rb, k, sc2, m_use, psum, p);
+        for (int k = 0; k < 8; ++k) softmax_slice<RB>(s_cur, rb, k, sc2, st.m[rb], psum, p);
+        psum[rb][0] += psum[rb][1];                                      // the caller adds [0] to l
     }
 }
 
-// One step of the software pipeline, for block j, entered with its (masked) scores in s_cur.
-// It runs  K Q^T of block j+1 -> s_nxt  (matrix cores)  |  softmax of block j -> p     (vector ALUs)
-// then     O += P V of block j          (matrix cores)  |  s_cur <- s_nxt
-// as an interleaved instruction stream: an MFMA, then a slice of vector work, pinned by
-// scheduling barriers.  Without a next block (have_nxt false) slot_nxt is any landed slot: the
-// scores are computed and dropped.
-template <int RB>
-__device__ __forceinline__ void pipeline_step(const char* slot_cur, const char* slot_nxt, const LaneOffsets& lo,
+// Scalar bookkeeping of the ring, advanced once per loop body.  A wavefront issues one
+// instruction every few cycles whatever its kind, so this bookkeeping is cut into small pieces
+// that the pipeline places between the MFMAs of the PV product, where issue slots are free.
+// At the top of body j:
+//   - blocks j-1, j, j+1 are resident (PV of j-1, softmax of j, K Q^T of j+1 run in this body),
+//     blocks j+2 .. j+RING-3 are in flight, and the loads of block j+RING-2 start, into the slot
+//     block j-2 has left;
+//   - d_cur / d_nxt describe blocks j and j+1, fifo[q] block j+2+q (0 = no such block), the last
+//     entry being the block whose loads start now (d_new, new_k, new_v);
+//   - o_pv / o_cur / o_nxt / o_new are the ring offsets of blocks j-1, j, j+1 and of the new block.
+template <int RING>
+struct RingPlan {
+    static constexpr int NF = RING - 3;
+    Stream ld;
+    int fifo[NF];
+    int d_cur, d_nxt, d_new;
+    const char *new_k, *new_v;
+    int o_pv, o_cur, o_nxt, o_new;
+    bool deep;                      // NF-1 blocks younger than j+1 are in flight (else: wait for all)
+    bool cur_masked;
+    int vis_lo;
+
+    __device__ __forceinline__ bool masked(int d) const {
+        return desc_n(d) < BLK || (desc_j0(d) >= 0 && desc_j0(d) + BLK - 1 > vis_lo);
+    }
+    // The pieces, in order, of "advance to the next body" (piece indices beyond the last do nothing).
+    __device__ __forceinline__ void piece(int i) {
+        if (i == 0) {                                  // the descriptors move up
+            d_cur = d_nxt;
+            d_nxt = fifo[0];
+#pragma unroll
+            for (int q = 0; q + 1 < NF; ++q) fifo[q] = fifo[q + 1];
+            fifo[NF - 1] = 0;
+            deep = NF >= 2 && fifo[NF >= 2 ? NF - 2 : 0] != 0;
+        } else if (i == 1) {                           // the ring turns
+            o_new = o_pv; o_pv = o_cur; o_cur = o_nxt;
+            o_nxt = o_nxt + SLOTB == RING * SLOTB ? 0 : o_nxt + SLOTB;
+        } else if (i == 2) {                           // the block whose loads start next
+            d_new = 0;
+            if (d_nxt != 0 && ld.rem > 0) { d_new = ld.take(new_k, new_v); fifo[NF - 1] = d_new; }
+        } else if (i == 3) {
+            cur_masked = masked(d_cur);
+        }
+    }
+    // The same advance inside a fast stretch (see run_blocks): every block is a full block of the
+    // loader's current segment, so only the pointers and the ring offsets move.
+    __device__ __forceinline__ void fast_piece(int i) {
+        if (i == 0) {
+            new_k = ld.k; new_v = ld.v;
+        } else if (i == 1) {
+            ld.k += BLK * ld.stride_b; ld.v += BLK * ld.stride_b;
+        } else if (i == 2) {
+            o_new = o_pv; o_pv = o_cur; o_cur = o_nxt;
+            o_nxt = o_nxt + SLOTB == RING * SLOTB ? 0 : o_nxt + SLOTB;
+        }
+    }
+    // Number of bodies of a fast stretch that may start now (0: none).  In a stretch every block
+    // described here (j .. j+RING-2) and every block taken is a full block of the loader's current
+    // segment, handed out back to back, and the blocks whose softmax runs need no mask; so the
+    // bodies need no descriptor, no branch and no table look-up, and finish_fast() can rebuild
+    // the descriptors from the loader's position.
+    __device__ __forceinline__ int fast_bodies() const {
+        if (ld.run < RING - 1) return 0;
+        int n = ld.rem / BLK;
+        if (ld.jstep != 0) { const int clear = (vis_lo - desc_j0(d_cur) + 1) / BLK; n = n < clear ? n : clear; }
+        return n > 0 ? n : 0;
+    }
+    __device__ __forceinline__ void finish_fast(int n) {
+        ld.rem -= n * BLK;
+        ld.j0 += n * ld.jstep;
+        ld.run += n;
+        // the RING-1 blocks described are the last RING-1 taken; the newest is the prepared one
+        auto d_age = [&](int a) { return BLK | ((ld.jstep != 0 ? ld.j0 - BLK * (a + 1) + 1 : 0) << 6); };
+        d_new = d_age(0);
+#pragma unroll
+        for (int q = 0; q < NF; ++q) fifo[NF - 1 - q] = d_age(q);
+        d_nxt = d_age(NF);
+        d_cur = d_age(NF + 1);
+        deep = NF >= 2;
+        cur_masked = masked(d_cur);
+        if (ld.rem == 0) ld.next_segment();
+    }
+};
+
+__device__ __forceinline__ float vmov(float x) {
+    float y;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(x));
+    return y;
+}
+
+// One body of the software pipeline.  Entered with the raw scores of block j in s_b, the
+// probabilities of block j-1 in p and its first V^T fragments in vf[0..3]; it runs
+//     O += P V of block j-1     (matrix cores)  |  s_a <- s_b, K fragments of block j+1, the loads
+//                                                  of the new block, ring bookkeeping
+//     K Q^T of block j+1 -> s_b (matrix cores)  |  softmax of block j (s_a) -> p, V^T fragments of block j
+// as an interleaved instruction stream: an MFMA, then a slice of other work, pinned by scheduling
+// barriers.  What matters is the number of instructions per MFMA, and that they sit between the
+// MFMAs.  The body starts with the PV product because that needs nothing of the block that has
+// just landed: the latency of the first K fragment reads hides behind it.  Without a next block
+// (d_nxt == 0) the scores are computed from a landed slot and dropped.
+// On return the plan describes the next body.
+template <int RB, int RING, bool FAST>
+__device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
                                               const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
-                                              f32x16 (&s_cur)[RB], const Block& nb, bool nxt_masked, const int (&lim)[RB]) {
-    // ---- first half: 8*RB MFMAs of K Q^T, 8*RB slices of the softmax
-    f32x16 s_nxt[RB];
-    bf16x8 p[RB][2];
-    float psum[RB], m_use[RB];
+                                              f32x16 (&s_b)[RB], u32x4 (&p)[RB][2], bf16x8 (&vf)[8],
+                                              RingPlan<RING>& plan, const int (&lim)[RB]) {
+    constexpr int NS = 8 * RB;                                       // MFMAs per half
+    const int d_cur = plan.d_cur, d_nxt = FAST ? BLK : plan.d_nxt;
+    const bool cur_masked = !FAST && plan.cur_masked;
+    const char* slot_pv = lds + pv_off;
+    const char* slot_cur = lds + plan.o_cur;
+    const char* slot_nxt = lds + (d_nxt != 0 ? plan.o_nxt : plan.o_cur);
+
+    // ---- first half: NS MFMAs of O += P V.  Its slices: first the LDS reads (the other V^T
+    // fragments of block j-1, the K fragments of block j+1 -- each several MFMAs ahead of its
+    // use), the new block's loads and the ring bookkeeping; then s_a <- s_b.
+    f32x16 s_a[RB];
     bf16x8 kf[8];
-    kf[0] = read_k_frag(slot_nxt, lo, 0);
-    kf[1] = read_k_frag(slot_nxt, lo, 1);
-    kf[2] = read_k_frag(slot_nxt, lo, 2);
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int f = n / RB, rb = n % RB;                           // fragment f = sl*4 + db
+        st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
+                                                                  st.o[rb][f & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n < 2) {
+            vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
+            vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+        }
+        if (RB == 2) {                                               // K fragments: slices 2, 3, 4
+            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+        } else {                                                     // ... after the wait for the V^T fragments: slices 4, 5
+            if (n == 4 || n == 5) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag(slot_nxt, lo, 4 * (n - 4) + q);
+            }
+        }
+        if (FAST) {
+            if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+            else
+            if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
+        } else if (n == 0) {
+            if (plan.d_new != 0)
+                issue_block_loads(plan.new_k, plan.new_v, desc_n(plan.d_new), plan.ld.stride_b, lds + plan.o_new, full);
+        } else if (d_nxt != 0) {
+            plan.piece(n - 1);                                       // (a uniform branch; nothing to plan after the last block)
+        }
+        if (n >= NS - 4 * RB) {                                      // the last 4*RB slices: four scores each
+            const int c = n - (NS - 4 * RB), r2 = c / 4, part = c % 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) s_a[r2][4 * part + q] = vmov(s_b[r2][4 * part + q]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__builtin_expect(cur_masked, 0)) apply_mask<RB>(s_a, d_cur, lim);   // block tails, the causal diagonal
+
+    // ---- second half: NS MFMAs of K Q^T, each followed by a slice of the softmax
+    float psum[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        psum[rb] = 0.f;
-        m_use[rb] = ref_use(st.m[rb]);
+        psum[rb][0] = psum[rb][1] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_nxt[rb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) s_b[rb][r] = 0.f;
     }
-    // two slices ahead of the first MFMA cover the latency of the first fragment reads
-    softmax_pair<RB>(s_cur, 0, 0, sc2, m_use[0], psum, p);
-    softmax_pair<RB>(s_cur, 0, 1, sc2, m_use[0], psum, p);
-    pin(psum[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 vf[8];
 #pragma unroll
-    for (int n = 0; n < 8 * RB; ++n) {
+    for (int n = 0; n < NS; ++n) {
         const int ks = n / RB, rb = n % RB;
-        if (rb == 0 && ks + 3 < 8) kf[ks + 3] = read_k_frag(slot_nxt, lo, ks + 3);
-        if (rb == 0 && ks == 5) vf[0] = read_v_frag(slot_cur, lo, 0);
-        if (rb == 0 && ks == 6) vf[1] = read_v_frag(slot_cur, lo, 1);
-        if (rb == 0 && ks == 7) vf[2] = read_v_frag(slot_cur, lo, 2);
-#ifdef APE_X_NOMFMA
-        s_nxt[rb][ks] += __builtin_bit_cast(f32x4, kf[ks])[0] * __builtin_bit_cast(f32x4, qf[rb][ks])[1];
-#else
-        s_nxt[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_nxt[rb], 0, 0, 0);
-#endif
+        s_b[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_b[rb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        const int slice = n + 2;                                     // (row block, register pair)
-        if (slice < 8 * RB) {
-            softmax_pair<RB>(s_cur, slice / 8, slice % 8, sc2, m_use[slice / 8], psum, p);
-            pin(psum[slice / 8]);
-        }
+        softmax_slice<RB>(s_a, n / 8, n % 8, sc2, st.m[n / 8], psum, p);
+        if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);             // for the next body's PV
         __builtin_amdgcn_sched_barrier(0);
     }
-    // ---- did every probability stay in range, and is every row that saw a key referenced?
+    // ---- did every probability stay in range?  (kUnset rows that saw a key did not)
     bool bad = false;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-        bad |= !(psum[rb] <= 0x1p40f) || (st.m[rb] == -INFINITY && psum[rb] > 0.f);
-    if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) set_reference<RB>(s_cur, sc2, st, psum, p);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb];
-
-    // ---- second half: 8*RB MFMAs of O += P V; in their shadow the scores of block j+1 become s_cur
-#pragma unroll
-    for (int n = 0; n < 8 * RB; ++n) {
-        const int f = n / RB, rb = n % RB;                           // fragment f = sl*4 + db
-        if (rb == 0 && f + 3 < 8) vf[f + 3] = read_v_frag(slot_cur, lo, f + 3);
-#ifdef APE_X_NOMFMA
-        st.o[rb][f & 3][f] += __builtin_bit_cast(f32x4, vf[f])[0] * __builtin_bit_cast(f32x4, p[rb][f >> 2])[1];
-#else
-        st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], p[rb][f >> 2], st.o[rb][f & 3], 0, 0, 0);
-#endif
-        __builtin_amdgcn_sched_barrier(0);
-        if (n < 4 * RB) {
-            const int r2 = n / 4, part = n % 4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float t = s_nxt[r2][4 * part + e];
-                pin(t);
-                s_cur[r2][4 * part + e] = t;
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    for (int rb = 0; rb < RB; ++rb) {
+        psum[rb][0] += psum[rb][1];
+        bad |= !(psum[rb][0] <= kPsumMax);
     }
-    if (__builtin_expect(nxt_masked, 0)) apply_mask<RB>(s_cur, nb, lim);   // block tails, the causal diagonal
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) set_reference<RB>(s_a, sc2, st, psum, p);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
 }
 
-// Streams every block of the walk `lw`.  Every wavefront of the workgroup
-// executes the same barriers and the same instruction stream; causal blocks a wavefront's rows
-// do not see are simply masked.
+// Streams every block of `ld0` through the ring.  Every wavefront of the workgroup executes the
+// same barriers and the same instruction stream; causal blocks a wavefront's rows do not see are
+// simply masked.
 //   vis_lo smallest causal limit among this wavefront's rows (blocks up to it need no causal mask)
-#ifdef APE_TIMING
-#define APE_T(i) do { const unsigned long long t__ = __builtin_amdgcn_s_memtime(); tacc[i] += t__ - tlast; tlast = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define APE_T(i) do { } while (0)
-#endif
-
 template <int RB>
-__device__ __forceinline__ void run_blocks(Walk lw, long stride_b, char* lds, const bf16x8 (&qf)[RB][8],
-                                           WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo, unsigned long long* tdbg = nullptr) {
-#ifdef APE_TIMING
-    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
-    unsigned long long tlast = __builtin_amdgcn_s_memtime();
-#endif
+__device__ __forceinline__ void run_blocks(const Stream& ld0, char* lds, const bf16x8 (&qf)[RB][8],
+                                           WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo) {
+    constexpr int RING = Ring<RB>::slots;
+    constexpr int NF = RING - 3;
+    if (ld0.rem == 0) return;
+    RingPlan<RING> plan;
+    plan.ld = ld0;
+    plan.vis_lo = vis_lo;
     const LaneOffsets lo = lane_offsets();
-    const LoadOffsets full = load_offsets(stride_b, BLK);
-    // Loads run RING-1 blocks ahead of the compute.  What the compute needs to know of a block
-    // in flight (valid rows, causal index of row 0) waits in a small FIFO: entry i describes
-    // block j+1+i at the top of step j; n_valid == 0 marks "no such block".
-    constexpr int FIFO = RING - 2;
-    int f_nv[FIFO], f_j0[FIFO];
-    Block lb, cb;
-    bool more = lw.next(cb);
-    if (!more) return;
-    issue_block_loads(cb, stride_b, lds, full);
-    int issued = 1;                                   // blocks whose loads have been issued
+    const LoadOffsets full = load_offsets(plan.ld.stride_b, BLK);
+    // prologue: the loads of blocks 0 .. RING-3; the scores of block 0
+    const int d0 = issue_next(plan.ld, lds, full);
+    int first[NF + 1];
 #pragma unroll
-    for (int i = 0; i < FIFO; ++i) {
-        f_nv[i] = 0; f_j0[i] = -1;
-        if (more) {
-            more = lw.next(lb);
-            if (more) {
-                issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full);
-                ++issued;
-                f_nv[i] = lb.n_valid; f_j0[i] = lb.j0;
-            }
-        }
-    }
-
-    f32x16 s_cur[RB];                                 // (masked) scores of block j
-    auto masked = [&](int n_valid, int j0) { return n_valid < BLK || (j0 >= 0 && j0 + BLK - 1 > vis_lo); };
-
-    // block 0: scores (its reference is set by the first step's check)
-    wait_vmcnt(issued - 1);
+    for (int i = 0; i <= NF; ++i) first[i] = 0;
+#pragma unroll
+    for (int i = 0; i < NF; ++i) first[i] = plan.ld.rem > 0 ? issue_next(plan.ld, lds + (i + 1) * SLOTB, full) : 0;
+    f32x16 s_b[RB];
+    if (first[NF - 1] != 0) wait_blocks<NF>(); else wait_blocks<0>();
     ring_barrier();
-    scores<RB>(lds, lo, qf, s_cur);
-    if (masked(cb.n_valid, cb.j0)) apply_mask<RB>(s_cur, cb, lim);
+    scores<RB>(lds, lo, qf, s_b);
 
-    APE_T(0);
-    bool have_cur = true;
-    for (int j = 0; have_cur; ++j) {
-        // block j+1: pop its description
-        Block nb;
-        nb.k = nb.v = nullptr; nb.n_valid = f_nv[0]; nb.j0 = f_j0[0];
-        const bool have_nxt = nb.n_valid > 0;
+    // the plan of body 0, as the pieces would leave it
+    plan.d_cur = d0;
+    plan.d_nxt = first[0];
 #pragma unroll
-        for (int i = 0; i + 1 < FIFO; ++i) { f_nv[i] = f_nv[i + 1]; f_j0[i] = f_j0[i + 1]; }
-        f_nv[FIFO - 1] = 0; f_j0[FIFO - 1] = -1;
-        APE_T(1);
-        if (have_nxt) {
-            // block j+1 must have landed; every wavefront is then also done with block j-1's
-            // slot, which the next loads overwrite
-#ifndef APE_X_NOLOAD
-            wait_vmcnt(issued - (j + 2));
-#endif
-            APE_T(2);
-#ifndef APE_X_NOBARRIER
+    for (int i = 0; i < NF; ++i) plan.fifo[i] = first[i + 1];
+    plan.deep = NF >= 2 && plan.fifo[NF >= 2 ? NF - 2 : 0] != 0;
+    plan.o_pv = (RING - 1) * SLOTB; plan.o_cur = 0; plan.o_nxt = SLOTB; plan.o_new = (RING - 2) * SLOTB;
+    plan.piece(2);
+    plan.piece(3);
+    // body 0 has no block -1: its PV product runs on zero probabilities and block 0's (finite) values
+    u32x4 p[RB][2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) p[rb][0] = p[rb][1] = u32x4{0, 0, 0, 0};
+    bf16x8 vf[8];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) vf[f] = read_v_frag(lds, lo, f);
+    int pv_off = 0;
+    for (;;) {
+        // ---- fast stretch: bodies that need no descriptor, no mask and no table look-up
+        const int n_fast = plan.fast_bodies();
+        for (int i = 0; i < n_fast; ++i) {
+            wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
-#endif
-            APE_T(3);
-            if (more) {
-                more = lw.next(lb);
-                if (more) {
-#ifndef APE_X_NOLOAD
-                    issue_block_loads(lb, stride_b, lds + (issued % RING) * SLOTB, full);
-#endif
-                    ++issued;
-                    f_nv[FIFO - 1] = lb.n_valid; f_j0[FIFO - 1] = lb.j0;
-                }
-            }
+            const int next_pv_off = plan.o_cur;
+            pipeline_body<RB, RING, true>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, plan, lim);
+            pv_off = next_pv_off;
         }
-        const char* slot_cur = lds + (j % RING) * SLOTB;
-        const char* slot_nxt = have_nxt ? lds + ((j + 1) % RING) * SLOTB : slot_cur;
-        APE_T(4);
-        pipeline_step<RB>(slot_cur, slot_nxt, lo, qf, st, sc2, s_cur, nb, have_nxt && masked(nb.n_valid, nb.j0), lim);
-        have_cur = have_nxt;
-        APE_T(5);
+        if (n_fast > 0) plan.finish_fast(n_fast);
+        // ---- generic body
+        const int d_nxt = plan.d_nxt;
+        if (d_nxt != 0) {
+            // block j+1 must have landed: all but the NF-1 youngest blocks, when that many are in flight
+            if (plan.deep) wait_blocks<NF >= 2 ? NF - 1 : 0>(); else wait_blocks<0>();
+            // ... for every wavefront, all of which are then also done with block j-2's slot
+            ring_barrier();
+        }
+        const int next_pv_off = plan.o_cur;
+        pipeline_body<RB, RING, false>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, plan, lim);
+        pv_off = next_pv_off;
+        if (d_nxt == 0) break;
     }
-#ifdef APE_TIMING
-    if (tdbg && threadIdx.x == 0 && blockIdx.x == 0)
-        for (int i = 0; i < 6; ++i) tdbg[i] = tacc[i];
-#endif
+    // the last block's PV product
+#pragma unroll
+    for (int f = 0; f < 8; ++f) {
+        if (f >= 4) vf[f] = read_v_frag(lds + pv_off, lo, f);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
+                                                                      st.o[rb][f & 3], 0, 0, 0);
+    }
 }
 
 template <int RB>
 __device__ __forceinline__ void init_state(WaveState<RB>& st) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        st.m[rb] = -INFINITY; st.l[rb] = 0.f;
+        st.m[rb] = kUnset; st.l[rb] = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -631,32 +731,28 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
             qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
         }
     }
-    const int R_lo = qtile * BM + wave * 32 * RB, R_hi = R_lo + 32 * RB - 1;
-    const int tok_lo = min(R_lo / G, q_len - 1), tok_hi = min(R_hi / G, q_len - 1);
+    const int R_lo = qtile * BM + wave * 32 * RB;
+    const int tok_lo = min(R_lo / G, q_len - 1);
 
     WaveState<RB> st;
     init_state<RB>(st);
     const float inv_sqrt_d = 0.08838834764831845f;      // 1/sqrt(128)
-    Walk walk;
+    Stream walk;
     float sc2 = inv_sqrt_d * LOG2E;
-    int vis_lo = 0, vis_hi = 0;
+    int vis_lo = 0;
     if (split < a.n_ctx_splits) {
         const long t0 = (long)split * a.ctx_split_len;
         const long t1 = min((long)kv.total_ctx, t0 + a.ctx_split_len);
-        walk.init_ctx(kv, t0, t1, stride_b, head_b);
+        walk.init_ctx(kv, (int)t0, (int)t1, stride_b, head_b);
         sc2 = inv_sqrt_d / kv.temperature * LOG2E;
     } else {
         // rows of this workgroup see the causal segment up to the last valid row's limit
         const int wg_tok_hi = min((qtile * BM + BM - 1) / G, q_len - 1);
         walk.init_seq((const char*)kv.k_prefix + head_b, (const char*)kv.v_prefix + head_b, kv.prefix_len,
                       (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
-        vis_lo = tok_lo + causal_off; vis_hi = tok_hi + causal_off;
+        vis_lo = tok_lo + causal_off;
     }
-#ifdef APE_TIMING
-    run_blocks<RB>(walk, stride_b, lds, qf, st, sc2, lim, vis_lo, (unsigned long long*)(a.part_lse + (long)60 * a.units_total));
-#else
-    run_blocks<RB>(walk, stride_b, lds, qf, st, sc2, lim, vis_lo);
-#endif
+    run_blocks<RB>(walk, lds, qf, st, sc2, lim, __builtin_amdgcn_readfirstlane(vis_lo));
 
     // ---- block result (Appendix C.1): normalised values + natural-log LogSumExp
 #pragma unroll
@@ -718,17 +814,17 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
             qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
         }
     }
-    const int R_lo = qtile * BM + wave * 32 * RB, R_hi = R_lo + 32 * RB - 1;
-    const int tok_lo = min(R_lo / G, len - 1), tok_hi = min(R_hi / G, len - 1);
+    const int R_lo = qtile * BM + wave * 32 * RB;
+    const int tok_lo = min(R_lo / G, len - 1);
     const int wg_tok_hi = min((qtile * BM + BM - 1) / G, len - 1);
 
     WaveState<RB> st;
     init_state<RB>(st);
-    Walk walk;
+    Stream walk;
     walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
               (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
               wg_tok_hi + 1, stride_b);
-    run_blocks<RB>(walk, stride_b, lds, qf, st, 0.08838834764831845f * LOG2E, lim, tok_lo);
+    run_blocks<RB>(walk, lds, qf, st, 0.08838834764831845f * LOG2E, lim, __builtin_amdgcn_readfirstlane(tok_lo));
 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -754,17 +850,17 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
 
 template <int RB, int G>
 hipError_t launch_prefill_t(const QueryArgs& a, unsigned grid, int n_qtiles, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute((const void*)flash_prefill_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, LDSB);
+    hipError_t e = hipFuncSetAttribute((const void*)flash_prefill_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
     if (e != hipSuccess) return e;
-    flash_prefill_kernel<RB, G><<<grid, NT, LDSB, s>>>(a, n_qtiles);
+    flash_prefill_kernel<RB, G><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles);
     return hipGetLastError();
 }
 
 template <int RB, int G>
 hipError_t launch_encode_t(const EncodeArgs& a, unsigned grid, int n_qtiles, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute((const void*)flash_encode_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, LDSB);
+    hipError_t e = hipFuncSetAttribute((const void*)flash_encode_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
     if (e != hipSuccess) return e;
-    flash_encode_kernel<RB, G><<<grid, NT, LDSB, s>>>(a, n_qtiles);
+    flash_encode_kernel<RB, G><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles);
     return hipGetLastError();
 }
 
@@ -790,11 +886,7 @@ hipError_t launch_encode_g(int group, const EncodeArgs& a, unsigned grid, int n_
 
 }  // namespace
 
-#ifdef APE_X_RB1
-int flash_block_rows(int rows_per_kv_head) { return 128; }
-#else
 int flash_block_rows(int rows_per_kv_head) { return rows_per_kv_head > 128 ? 256 : 128; }
-#endif
 
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
