@@ -522,6 +522,70 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
     const char* slot_cur = lds + plan.o_cur;
     const char* slot_nxt = lds + (d_nxt != 0 ? plan.o_nxt : plan.o_cur);
 
+    if constexpr (FAST && RB == 2) {
+        // The balanced layout of the fast body.  The vector ALUs, not the matrix cores, bound a
+        // body whose softmax sits wholly in one half, so the softmax of row block 0 moves into the
+        // PV half: the PV MFMAs take row block 0 first, which frees its probabilities for the
+        // second eight slices to overwrite.  It reads its scores straight from s_b (no copy); only
+        // row block 1's scores are copied aside before the K Q^T half overwrites s_b.
+        f32x16 s_a[RB];
+        bf16x8 kf[8];
+        float psum[RB][2];
+        psum[0][0] = psum[0][1] = psum[1][0] = psum[1][1] = 0.f;
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+            const int rb = n / 8, f = n % 8;
+            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
+                                                                      st.o[rb][f & 3], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (n < 2) {
+                vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
+                vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+            }
+            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+            if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+            else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
+            if (n < 8) {
+                s_a[1][2 * n] = vmov(s_b[1][2 * n]);
+                s_a[1][2 * n + 1] = vmov(s_b[1][2 * n + 1]);
+            } else {
+                softmax_slice<RB>(s_b, 0, n - 8, sc2, st.m[0], psum, p);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_b[rb][r] = 0.f;
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+            const int ks = n / 2, rb = n % 2;
+            s_b[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_b[rb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (n < 8) softmax_slice<RB>(s_a, 1, n, sc2, st.m[1], psum, p);
+            if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);         // for the next body's PV
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        bool bad = false;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            psum[rb][0] += psum[rb][1];
+            bad |= !(psum[rb][0] <= kPsumMax);
+        }
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) {
+            // the scores of block j are gone; K of block j is still in its slot
+            f32x16 s_again[RB];
+            scores<RB>(slot_cur, lo, qf, s_again);
+            asm volatile("s_nop 15\n\ts_nop 15");
+            set_reference<RB>(s_again, sc2, st, psum, p);
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
+        return;
+    }
+
     // ---- first half: NS MFMAs of O += P V.  Its slices: first the LDS reads (the other V^T
     // fragments of block j-1, the K fragments of block j+1 -- each several MFMAs ahead of its
     // use), the new block's loads and the ring bookkeeping; then s_a <- s_b.

@@ -33,11 +33,12 @@ def check_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = ""):
 def lse_tol(dtype: str) -> float:
     """Tolerance of the LogSumExp outputs (the benchmark definition states none; derived here).
     fp32 path: fp32 scores, expf, fp32 sums of <= a few hundred terms: 2e-5.
-    bf16 path: the matrix-core kernels sum the probabilities AFTER rounding them to bf16, so that
-    the normaliser carries the same rounding as the P.V numerator.  bf16 keeps 8 significant bits,
-    so each rounded term is off by a relative 2^-8 at most, hence so is the sum of these positive
-    terms and |dLSE| <= 2^-8 ~ 3.9e-3 in the worst case (a row dominated by one key); errors of
-    random sign average out (~4e-4 observed over 131K keys)."""
+    bf16 path: inputs are bf16, scores and the normaliser are fp32.  The bound allows a normaliser
+    summed from bf16-ROUNDED probabilities (so that it carries the same rounding as the P.V
+    numerator): bf16 keeps 8 significant bits, each rounded term is then off by a relative 2^-8 at
+    most, hence so is the sum of these positive terms and |dLSE| <= 2^-8 ~ 3.9e-3 in the worst case
+    (a row dominated by one key).  Kernels that sum the unrounded fp32 probabilities stay far inside
+    it (~1e-5 observed over 131K keys)."""
     return 2e-5 if dtype == "f32" else 4e-3
 
 
