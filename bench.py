@@ -32,7 +32,9 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
 # same counters' reading for a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": None, "flash_prefill_kernel": None, "decode_kernel": None}
+MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": (788636 * 2 + 1048576) * 1024,     # 2.689 GB
+                          "flash_prefill_kernel": (271251 * 2 + 39877) * 1024,     # 0.596 GB
+                          "decode_kernel": (262890 * 2 + 1056) * 1024}             # 0.539 GB
 
 
 def pair_counts(spec):
@@ -52,6 +54,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the batched-decode (config 5) region")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings in a --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
@@ -142,6 +147,13 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(roof["kernel"])
     roof["launch_ms"] = float({"flash_encode_kernel": ms_enc, "flash_prefill_kernel": ms_pre, "decode_kernel": ms_dec / max(1, args.decode_steps)}[roof["kernel"]])
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                                  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- batched decode (config 5): the clean HBM measurement, timed in its own region
     if not args.no_cfg5:
