@@ -92,6 +92,12 @@ def main():
                          B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1)) // 4, dtype=torch.float32, device=dev)
     qd = [r.q_self[spec.q_len + i:spec.q_len + i + 1].contiguous() for i in range(args.decode_steps)]
     outd = torch.empty_like(qd[0]) if qd else None
+    # decode calls marshalled once (argument marshalling only; the request's self_len grows by one per token)
+    dec_calls = []
+    for i in range(args.decode_steps):
+        fn, arr = B.decode_call(shape, [req], qd[i], outd, None, ws)
+        arr[0].self_len = spec.q_len + i + 1
+        dec_calls.append((fn, arr))
 
     def step(ev=None):
         if ev: ev[0].record()
@@ -99,8 +105,8 @@ def main():
         if ev: ev[1].record()
         B.attention_prefill(shape, req, q, out, None, ws)
         if ev: ev[2].record()
-        for i in range(args.decode_steps):
-            B.attention_decode(shape, [req], qd[i], outd, None, ws, self_lens=[spec.q_len + i + 1])
+        for fn, _ in dec_calls:
+            fn()
         if ev: ev[3].record()
 
     for _ in range(args.warmup):
@@ -167,9 +173,16 @@ def main():
         o5 = torch.empty_like(q5[0])
         ws5 = torch.empty(B.workspace_bytes(B.APE_OP_DECODE, shape, spec5.batch, 1) // 4, dtype=torch.float32, device=dev)
 
+        calls5 = []
+        for s in range(spec5.decode_steps):
+            fn, arr = B.decode_call(shape, reqs, q5[s], o5, None, ws5)
+            for b in range(spec5.batch):
+                arr[b].self_len = s + 1
+            calls5.append((fn, arr))
+
         def decode_pass():
-            for s in range(spec5.decode_steps):
-                B.attention_decode(shape, reqs, q5[s], o5, None, ws5, self_lens=[s + 1] * spec5.batch)
+            for fn, _ in calls5:
+                fn()
         decode_pass()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -185,7 +198,7 @@ def main():
         phases["decode_cfg5_batch32"] = {"ms_per_step": ms5 / spec5.decode_steps, "gbs": by5 / (ms5 * 1e-3) / 1e9,
                                          "frac_hbm_peak": by5 / (ms5 * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                          "note": "32 requests x 16.4K KV tokens, 128 steps, 2.15 GB per step"}
-        del rs, reqs, q5, o5, ws5
+        del calls5, rs, reqs, q5, o5, ws5
 
     # ---- the oracle beside it, on a bounded sample of the same workload
     cpu = None

@@ -198,10 +198,46 @@ __global__ __launch_bounds__(kWave) void generic_encode_kernel(const EncodeArgs 
 // Merge of the split results (Appendix C.1 for splits of one group, C.3/C.4 across the two
 // groups): the context splits are merged first, exactly; only then is the pooled context
 // LogSumExp multiplied by S -- (sum of splits)^S is not the sum of the splits^S.
-// grid: x = unit; one wavefront per unit, lanes over head_dim.
+// grid: x = unit; a workgroup of kMergeWaves wavefronts per unit.  Every wavefront computes the
+// split weights (one coalesced read of the LogSumExps, a wavefront reduction); the wavefronts
+// then share out the splits, each accumulating its weighted rows with several loads in flight,
+// and are combined through LDS.  (A serial loop over 64 splits cost 61 us at batch 1.)
+constexpr int kMergeWaves = 4;
+
+// One group of splits [s0, s1): this wavefront's share of sum_s w_s o_s into acc (lane owns dims
+// lane + 64 r), with w_s = exp(lse_s - max); returns the group's max and sum of weights.
+__device__ __forceinline__ void merge_group(const MergeArgs& a, long gunit, int s0, int s1, int wave, int lane,
+                                            float (&acc)[kMaxDimRegs], float& m_out, float& z_out) {
+    const int d = a.head_dim;
+    float m = -INFINITY;
+    for (int s = s0 + lane; s < s1; s += kWave) m = fmaxf(m, a.part_lse[(long)s * a.units_total + gunit]);
+    m = wave_max(m);
+    float z = 0.f;
+    if (m > -INFINITY) {
+        for (int c0 = s0; c0 < s1; c0 += kWave) {                   // chunks of 64 splits: lane <-> split
+            const int s_mine = c0 + lane;
+            const float w_mine = s_mine < s1 ? expf(a.part_lse[(long)s_mine * a.units_total + gunit] - m) : 0.f;   // 0 for empty splits
+            z += w_mine;
+            const int cnt = min(kWave, s1 - c0);
+            for (int i = wave; i < cnt; i += kMergeWaves) {
+                const float w = __shfl(w_mine, i);
+                const float* o = a.part_o + ((long)(c0 + i) * a.units_total + gunit) * d;
+#pragma unroll
+                for (int r = 0; r < kMaxDimRegs; ++r) {
+                    const int c = lane + kWave * r;
+                    if (c < d) acc[r] = fmaf(w, o[c], acc[r]);
+                }
+            }
+        }
+        z = wave_sum(z);
+    }
+    m_out = m; z_out = z;
+}
+
 template <typename T>
-__global__ __launch_bounds__(kWave) void merge_kernel(const MergeArgs a) {
-    const int lane = threadIdx.x;
+__global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeArgs a) {
+    __shared__ float part[2][kMergeWaves][kWave * kMaxDimRegs];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int unit = blockIdx.x;                                    // within this launch
     const int d = a.head_dim, hq = a.n_q_heads;
     const int rq = unit / (hq * a.q_len);
@@ -211,42 +247,24 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const MergeArgs a) {
     float acc_c[kMaxDimRegs], acc_o[kMaxDimRegs];
 #pragma unroll
     for (int r = 0; r < kMaxDimRegs; ++r) { acc_c[r] = 0.f; acc_o[r] = 0.f; }
-
-    // context group
-    float mc = -INFINITY;
-    for (int s = 0; s < a.n_ctx_splits; ++s) mc = fmaxf(mc, a.part_lse[(long)s * a.units_total + gunit]);
-    float zc = 0.f;
-    if (mc > -INFINITY) {
-        for (int s = 0; s < a.n_ctx_splits; ++s) {
-            const long slot = (long)s * a.units_total + gunit;
-            const float w = expf(a.part_lse[slot] - mc);            // 0 for empty splits
-            zc += w;
-            const float* o = a.part_o + slot * d;
+    float mc, zc, mo, zo;
+    merge_group(a, gunit, 0, a.n_ctx_splits, wave, lane, acc_c, mc, zc);                  // context group
+    merge_group(a, gunit, a.n_ctx_splits, a.n_splits_total, wave, lane, acc_o, mo, zo);   // prefix + self: never empty
 #pragma unroll
-            for (int r = 0; r < kMaxDimRegs; ++r) {
-                const int c = lane + kWave * r;
-                if (c < d) acc_c[r] = fmaf(w, o[c], acc_c[r]);
-            }
-        }
+    for (int r = 0; r < kMaxDimRegs; ++r) {
+        part[0][wave][lane + kWave * r] = acc_c[r];
+        part[1][wave][lane + kWave * r] = acc_o[r];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int r = 0; r < kMaxDimRegs; ++r) {
+        acc_c[r] = 0.f; acc_o[r] = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMergeWaves; ++w) { acc_c[r] += part[0][w][lane + kWave * r]; acc_o[r] += part[1][w][lane + kWave * r]; }
     }
     const float lse_c = mc > -INFINITY ? mc + logf(zc) : -INFINITY;   // log Z_ctx
     const float inv_zc = zc > 0.f ? 1.f / zc : 0.f;
-
-    // non-context group (prefix + self): never empty
-    float mo = -INFINITY;
-    for (int s = a.n_ctx_splits; s < a.n_splits_total; ++s) mo = fmaxf(mo, a.part_lse[(long)s * a.units_total + gunit]);
-    float zo = 0.f;
-    for (int s = a.n_ctx_splits; s < a.n_splits_total; ++s) {
-        const long slot = (long)s * a.units_total + gunit;
-        const float w = expf(a.part_lse[slot] - mo);
-        zo += w;
-        const float* o = a.part_o + slot * d;
-#pragma unroll
-        for (int r = 0; r < kMaxDimRegs; ++r) {
-            const int c = lane + kWave * r;
-            if (c < d) acc_o[r] = fmaf(w, o[c], acc_o[r]);
-        }
-    }
     const float lse_o = mo + logf(zo);
     const float inv_zo = 1.f / zo;
 
@@ -292,8 +310,8 @@ hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s) 
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
     dim3 grid((unsigned)(a.n_req * a.q_len * a.n_q_heads));
-    if (a.dtype == APE_F32) merge_kernel<float><<<grid, kWave, 0, s>>>(a);
-    else merge_kernel<__bf16><<<grid, kWave, 0, s>>>(a);
+    if (a.dtype == APE_F32) merge_kernel<float><<<grid, kWave * kMergeWaves, 0, s>>>(a);
+    else merge_kernel<__bf16><<<grid, kWave * kMergeWaves, 0, s>>>(a);
     return hipGetLastError();
 }
 
