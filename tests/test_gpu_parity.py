@@ -157,6 +157,29 @@ def test_values_all_ones_rows_sum_to_one():
     assert (H.f64(o_p) - 1.0).__abs__().max() <= 2 ** -8
 
 
+def test_late_outlier_keys_move_the_softmax_reference():
+    """The flash kernels keep a lazily updated softmax reference and take a rare path when a score
+    exceeds it by more than 2^40.  Keys planted deep inside long segments, aligned with one query
+    each so that their scores tower over everything before them, force that path in the middle
+    of a stretch of full blocks (context chunk, own chunk of the encode, self segment)."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(1024, 700), q_len=64, prefix_len=32, decode_steps=5)
+    r = W.make_request(spec, DEV)
+    g = spec.n_q_heads // spec.n_kv_heads
+    for hk in range(spec.n_kv_heads):
+        r.k_ctx[600 + hk, hk] = 6.0 * r.q_self[5 + hk, hk * g]            # prefill row 5+hk, chunk 0, block 18
+        r.k_ctx[1024 + 650, hk] = 6.0 * r.q_self[40, hk * g + g - 1]      # chunk 1
+        r.k_ctx[900, hk] = 5.0 * r.q_ctx[950, hk * g + 1]                 # encode: row 950 of chunk 0 sees token 900 (diagonal tile)
+        r.k_ctx[500, hk] = 5.0 * r.q_ctx[1000, hk * g + 2]                # ... and row 1000 token 500 (deep inside the stretch)
+        r.k_self[33, hk] = 6.0 * r.q_self[60, hk * g]                     # self segment, second block
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, what="outliers")
+    _check_query(spec, r, h, spec.q_len, spec.q_len, what="outliers")
+    _check_decode(spec, r, h, spec.q_len + 1, what="outliers")
+    # the planted keys really are beyond the lazy threshold (2^40 ~ 27.7 in natural-log units)
+    qk = (r.q_self[5].float()[0] * r.k_ctx[600, 0].float()).sum().item() / spec.head_dim ** 0.5 / r.temperature
+    assert qk > 40.0
+
+
 def test_chunk_table_order_and_separate_buffers():
     """Contexts live in separately allocated buffers reached through the table; permuting the
     table leaves the result unchanged within tolerance (Eq.5 is a sum over contexts)."""
