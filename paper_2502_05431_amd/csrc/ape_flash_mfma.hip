@@ -508,7 +508,8 @@ __device__ __forceinline__ float vmov(float x) {
 // barriers.  What matters is the number of instructions per MFMA, and that they sit between the
 // MFMAs.  The body starts with the PV product because that needs nothing of the block that has
 // just landed: the latency of the first K fragment reads hides behind it.  Without a next block
-// (d_nxt == 0) the scores are computed from a landed slot and dropped.
+// (d_nxt == 0) the scores are computed from a landed slot and dropped.  (Making these MFMAs
+// conditional costs more than it saves: the accumulators then pass through copies.)
 // On return the plan describes the next body.
 template <int RB, int RING, bool FAST>
 __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
@@ -659,28 +660,49 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
     for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
 }
 
-// Streams every block of `ld0` through the ring.  Every wavefront of the workgroup executes the
-// same barriers and the same instruction stream; causal blocks a wavefront's rows do not see are
-// simply masked.
-//   vis_lo smallest causal limit among this wavefront's rows (blocks up to it need no causal mask)
+// The loads of the first blocks of a stream (blocks 0 .. RING-3), started before anything else in
+// the kernel -- the query fragments are fetched while they fly.
+template <int RING>
+struct RingStart {
+    static constexpr int NF = RING - 3;
+    RingPlan<RING> plan;
+    LoadOffsets full;
+    int d0;
+    int first[NF + 1];
+};
+
+template <int RING>
+__device__ __forceinline__ void start_stream(RingStart<RING>& rs, const Stream& ld0, char* lds, int vis_lo) {
+    constexpr int NF = RING - 3;
+    rs.plan.ld = ld0;
+    rs.plan.vis_lo = vis_lo;
+    rs.full = load_offsets(ld0.stride_b, BLK);
+    rs.d0 = 0;
+#pragma unroll
+    for (int i = 0; i <= NF; ++i) rs.first[i] = 0;
+    if (ld0.rem == 0) return;
+    rs.d0 = issue_next(rs.plan.ld, lds, rs.full);
+#pragma unroll
+    for (int i = 0; i < NF; ++i) rs.first[i] = rs.plan.ld.rem > 0 ? issue_next(rs.plan.ld, lds + (i + 1) * SLOTB, rs.full) : 0;
+}
+
+// Streams every block through the ring.  Every wavefront of the workgroup executes the same
+// barriers and the same instruction stream; causal blocks a wavefront's rows do not see are
+// simply masked.  (vis_lo, given to start_stream: the smallest causal limit among this
+// wavefront's rows; blocks up to it need no causal mask.)
 template <int RB>
-__device__ __forceinline__ void run_blocks(const Stream& ld0, char* lds, const bf16x8 (&qf)[RB][8],
-                                           WaveState<RB>& st, float sc2, const int (&lim)[RB], int vis_lo) {
+__device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char* lds, const bf16x8 (&qf)[RB][8],
+                                           WaveState<RB>& st, float sc2, const int (&lim)[RB]) {
     constexpr int RING = Ring<RB>::slots;
     constexpr int NF = RING - 3;
-    if (ld0.rem == 0) return;
-    RingPlan<RING> plan;
-    plan.ld = ld0;
-    plan.vis_lo = vis_lo;
+    if (rs.d0 == 0) return;
+    RingPlan<RING>& plan = rs.plan;
+    const LoadOffsets full = rs.full;
+    const int d0 = rs.d0;
+    const int (&first)[NF + 1] = rs.first;
     const LaneOffsets lo = lane_offsets();
-    const LoadOffsets full = load_offsets(plan.ld.stride_b, BLK);
-    // prologue: the loads of blocks 0 .. RING-3; the scores of block 0
-    const int d0 = issue_next(plan.ld, lds, full);
-    int first[NF + 1];
-#pragma unroll
-    for (int i = 0; i <= NF; ++i) first[i] = 0;
-#pragma unroll
-    for (int i = 0; i < NF; ++i) first[i] = plan.ld.rem > 0 ? issue_next(plan.ld, lds + (i + 1) * SLOTB, full) : 0;
+    // block 0 has landed when at most the NF younger blocks are in flight; loads of the caller
+    // that are younger still (the query fragments) only make this wait longer
     f32x16 s_b[RB];
     if (first[NF - 1] != 0) wait_blocks<NF>(); else wait_blocks<0>();
     ring_barrier();
@@ -760,7 +782,8 @@ __device__ __forceinline__ void team_of_block(int block, int team_size, int& tea
 }
 
 // ------------------------------------------------------------------------------------------
-// Query prefill: grid = 8 * ceil(teams / 8) * n_qtiles, team = (split, KV head).
+// Query prefill: team = (split, KV head); grid = the context teams (padded to a multiple of 8) times
+// n_qtiles, then the prefix+self teams likewise.
 // Rows: R = qtile*BM + wave*32*RB + rb*32 + (lane & 31); query token = R / G, head = hk*G + R % G.
 template <int RB, int G>
 __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, int n_qtiles) {
@@ -768,38 +791,28 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
     constexpr int BM = NW * 32 * RB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
-    int team, qtile;
-    team_of_block(blockIdx.x, n_qtiles, team, qtile);
-    const int n_splits_total = a.n_ctx_splits + 1;
-    if (team >= n_splits_total * a.n_kv_heads) return;
-    const int split = team % n_splits_total, hk = team / n_splits_total;
+    // Blocks of the context splits come first: they are the long ones, and the grid is planned so
+    // that they fill the chip exactly once; the short prefix+self workgroups follow.
+    int team, qtile, split, hk;
+    const int ctx_teams = a.n_ctx_splits * a.n_kv_heads;
+    const int ctx_blocks = (ctx_teams + 7) / 8 * 8 * n_qtiles;
+    if ((int)blockIdx.x < ctx_blocks) {
+        team_of_block(blockIdx.x, n_qtiles, team, qtile);
+        if (team >= ctx_teams) return;
+        split = team % a.n_ctx_splits; hk = team / a.n_ctx_splits;
+    } else {
+        team_of_block(blockIdx.x - ctx_blocks, n_qtiles, team, qtile);
+        if (team >= a.n_kv_heads) return;
+        split = a.n_ctx_splits; hk = team;
+    }
     const KvView& kv = a.req[0];
     const int hq = a.n_q_heads, q_len = a.q_len;
     const long stride_b = (long)a.n_kv_heads * ROWB, head_b = (long)hk * ROWB;
 
-    // Q fragments (B operand: row = lane & 31, dims 16*ks + 8*hi .. +7)
-    bf16x8 qf[RB][8];
-    int lim[RB];
+    // the stream of K/V blocks; its first loads start before anything else
     const int causal_off = kv.self_len - q_len;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
-        const int tok = R / G, g = R % G;
-        const bool valid = tok < q_len;
-        lim[rb] = (valid ? tok : q_len - 1) + causal_off;
-        const char* qp = (const char*)a.q + ((long)tok * hq + hk * G + g) * ROWB + hi * 16;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            u32x4 w = {0, 0, 0, 0};
-            if (valid) w = *(const u32x4*)(qp + ks * 32);
-            qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
-        }
-    }
     const int R_lo = qtile * BM + wave * 32 * RB;
     const int tok_lo = min(R_lo / G, q_len - 1);
-
-    WaveState<RB> st;
-    init_state<RB>(st);
     const float inv_sqrt_d = 0.08838834764831845f;      // 1/sqrt(128)
     Stream walk;
     float sc2 = inv_sqrt_d * LOG2E;
@@ -816,7 +829,30 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
                       (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
         vis_lo = tok_lo + causal_off;
     }
-    run_blocks<RB>(walk, lds, qf, st, sc2, lim, __builtin_amdgcn_readfirstlane(vis_lo));
+    RingStart<Ring<RB>::slots> rs;
+    start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(vis_lo));
+
+    // Q fragments (B operand: row = lane & 31, dims 16*ks + 8*hi .. +7)
+    bf16x8 qf[RB][8];
+    int lim[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
+        const int tok = R / G, g = R % G;
+        const bool valid = tok < q_len;
+        lim[rb] = (valid ? tok : q_len - 1) + causal_off;
+        const char* qp = (const char*)a.q + ((long)tok * hq + hk * G + g) * ROWB + hi * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            u32x4 w = {0, 0, 0, 0};
+            if (valid) w = *(const u32x4*)(qp + ks * 32);
+            qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    WaveState<RB> st;
+    init_state<RB>(st);
+    run_blocks<RB>(rs, lds, qf, st, sc2, lim);
 
     // ---- block result (Appendix C.1): normalised values + natural-log LogSumExp
 #pragma unroll
@@ -862,6 +898,18 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
     const int hq = a.n_q_heads;
     const long stride_b = (long)a.n_kv_heads * ROWB, head_b = (long)hk * ROWB;
 
+    // the stream of K/V blocks (prefix, then the chunk up to this tile's last row); its first loads
+    // start before anything else
+    const int R_lo = qtile * BM + wave * 32 * RB;
+    const int tok_lo = min(R_lo / G, len - 1);
+    const int wg_tok_hi = min((qtile * BM + BM - 1) / G, len - 1);
+    Stream walk;
+    walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
+              (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
+              wg_tok_hi + 1, stride_b);
+    RingStart<Ring<RB>::slots> rs;
+    start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(tok_lo));
+
     bf16x8 qf[RB][8];
     int lim[RB];
 #pragma unroll
@@ -878,17 +926,10 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
             qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
         }
     }
-    const int R_lo = qtile * BM + wave * 32 * RB;
-    const int tok_lo = min(R_lo / G, len - 1);
-    const int wg_tok_hi = min((qtile * BM + BM - 1) / G, len - 1);
 
     WaveState<RB> st;
     init_state<RB>(st);
-    Stream walk;
-    walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
-              (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
-              wg_tok_hi + 1, stride_b);
-    run_blocks<RB>(walk, lds, qf, st, 0.08838834764831845f * LOG2E, lim, __builtin_amdgcn_readfirstlane(tok_lo));
+    run_blocks<RB>(rs, lds, qf, st, 0.08838834764831845f * LOG2E, lim);
 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -957,8 +998,8 @@ hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s) {
     const int rows = a.q_len * group;
     const int bm = flash_block_rows(rows);
     const int n_qtiles = (rows + bm - 1) / bm;
-    const int teams = (a.n_ctx_splits + 1) * a.n_kv_heads;
-    const unsigned grid = (unsigned)((teams + 7) / 8 * 8 * n_qtiles);
+    const int ctx_teams = a.n_ctx_splits * a.n_kv_heads;
+    const unsigned grid = (unsigned)(((ctx_teams + 7) / 8 * 8 + (a.n_kv_heads + 7) / 8 * 8) * n_qtiles);
     return bm == 256 ? launch_prefill_g<2>(group, a, grid, n_qtiles, s) : launch_prefill_g<1>(group, a, grid, n_qtiles, s);
 }
 
