@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the batched-decode (config 5) region")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
+    ap.add_argument("--gemm-reference", action="store_true",
+                    help="also time torch's bf16 GEMM (the vendor library) on zero and on random operands: context "
+                         "for the MFMA roofline, which on this chip depends on the operand data (power limit)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings in a --pmc run)")
@@ -154,6 +157,27 @@ def main():
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(roof["kernel"])
     roof["launch_ms"] = float({"flash_encode_kernel": ms_enc, "flash_prefill_kernel": ms_pre, "decode_kernel": ms_dec / max(1, args.decode_steps)}[roof["kernel"]])
 
+    gemm_ref = None
+    if args.gemm_reference:
+        n = 8192
+        gemm_ref = {}
+        for name in ("zeros", "random"):
+            a_ = torch.zeros(n, n, dtype=torch.bfloat16, device=dev)
+            b_ = torch.zeros(n, n, dtype=torch.bfloat16, device=dev)
+            if name == "random":
+                a_.normal_(); b_.normal_()
+            for _ in range(3):
+                torch.matmul(a_, b_)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                torch.matmul(a_, b_)
+            e1.record()
+            torch.cuda.synchronize()
+            gemm_ref["torch_bf16_gemm_8192_tflops_" + name] = 2.0 * n ** 3 * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            del a_, b_
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -235,6 +259,8 @@ def main():
         "headline_decode_gbs": phases.get("decode_cfg5_batch32", {}).get("gbs"),
         "phases": phases, "roofline": roof, "cpu_baseline": cpu,
     }
+    if gemm_ref is not None:
+        line["gemm_reference"] = gemm_ref
     print(json.dumps(line))
 
 
