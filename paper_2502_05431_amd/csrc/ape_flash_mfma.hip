@@ -523,70 +523,6 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
     const char* slot_cur = lds + plan.o_cur;
     const char* slot_nxt = lds + (d_nxt != 0 ? plan.o_nxt : plan.o_cur);
 
-    if constexpr (FAST && RB == 2) {
-        // The balanced layout of the fast body.  The vector ALUs, not the matrix cores, bound a
-        // body whose softmax sits wholly in one half, so the softmax of row block 0 moves into the
-        // PV half: the PV MFMAs take row block 0 first, which frees its probabilities for the
-        // second eight slices to overwrite.  It reads its scores straight from s_b (no copy); only
-        // row block 1's scores are copied aside before the K Q^T half overwrites s_b.
-        f32x16 s_a[RB];
-        bf16x8 kf[8];
-        float psum[RB][2];
-        psum[0][0] = psum[0][1] = psum[1][0] = psum[1][1] = 0.f;
-#pragma unroll
-        for (int n = 0; n < 16; ++n) {
-            const int rb = n / 8, f = n % 8;
-            st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
-                                                                      st.o[rb][f & 3], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (n < 2) {
-                vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
-                vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
-            }
-            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
-            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
-            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
-            if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
-            else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
-            if (n < 8) {
-                s_a[1][2 * n] = vmov(s_b[1][2 * n]);
-                s_a[1][2 * n + 1] = vmov(s_b[1][2 * n + 1]);
-            } else {
-                softmax_slice<RB>(s_b, 0, n - 8, sc2, st.m[0], psum, p);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s_b[rb][r] = 0.f;
-#pragma unroll
-        for (int n = 0; n < 16; ++n) {
-            const int ks = n / 2, rb = n % 2;
-            s_b[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_b[rb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (n < 8) softmax_slice<RB>(s_a, 1, n, sc2, st.m[1], psum, p);
-            if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);         // for the next body's PV
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        bool bad = false;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            psum[rb][0] += psum[rb][1];
-            bad |= !(psum[rb][0] <= kPsumMax);
-        }
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) {
-            // the scores of block j are gone; K of block j is still in its slot
-            f32x16 s_again[RB];
-            scores<RB>(slot_cur, lo, qf, s_again);
-            asm volatile("s_nop 15\n\ts_nop 15");
-            set_reference<RB>(s_again, sc2, st, psum, p);
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
-        return;
-    }
-
     // ---- first half: NS MFMAs of O += P V.  Its slices: first the LDS reads (the other V^T
     // fragments of block j-1, the K fragments of block j+1 -- each several MFMAs ahead of its
     // use), the new block's loads and the ring bookkeeping; then s_a <- s_b.
@@ -660,6 +596,76 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
     for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
 }
 
+// The fast body again, for pairs of bodies: it reads the scores of block j from s_in and writes
+// those of block j+1 to s_out, two different register sets that swap roles from one body to the
+// next, so no score is ever copied and the softmax is free to sit in either half.  With two row
+// blocks the softmax of row block 0 runs in the PV half (the PV MFMAs take row block 0 first,
+// which frees its probability registers for the second eight slices), that of row block 1 in the
+// K Q^T half; with one row block its first four slices run in the last four of the PV half.
+template <int RB, int RING>
+__device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
+                                                 const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
+                                                 const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB], u32x4 (&p)[RB][2],
+                                                 bf16x8 (&vf)[8], RingPlan<RING>& plan) {
+    constexpr int NS = 8 * RB;
+    const char* slot_pv = lds + pv_off;
+    const char* slot_cur = lds + plan.o_cur;
+    const char* slot_nxt = lds + plan.o_nxt;
+    bf16x8 kf[8];
+    float psum[RB][2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) psum[rb][0] = psum[rb][1] = 0.f;
+    // ---- O += P V of block j-1
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int rb = n / 8, f = n % 8;                             // row block 0 first
+        st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
+                                                                  st.o[rb][f & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n < 2) {
+            vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
+            vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+        }
+        if (RB == 2) {
+            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+        } else if (n == 4 || n == 5) {                               // (after the wait for the V^T fragments)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag(slot_nxt, lo, 4 * (n - 4) + q);
+        }
+        if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+        else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
+        if (RB == 2 && n >= 8) softmax_slice<RB>(s_in, 0, n - 8, sc2, st.m[0], psum, p);
+        if (RB == 1 && n >= 4) softmax_slice<RB>(s_in, 0, n - 4, sc2, st.m[0], psum, p);   // slab 0, last read by MFMA 3
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- K Q^T of block j+1, the rest of the softmax of block j
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_out[rb][r] = 0.f;
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int ks = n / RB, rb = n % RB;
+        s_out[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_out[rb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (RB == 2 && n < 8) softmax_slice<RB>(s_in, 1, n, sc2, st.m[1], psum, p);
+        if (RB == 1 && n < 4) softmax_slice<RB>(s_in, 0, n + 4, sc2, st.m[0], psum, p);
+        if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);             // for the next body's PV
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    bool bad = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        psum[rb][0] += psum[rb][1];
+        bad |= !(psum[rb][0] <= kPsumMax);
+    }
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) set_reference<RB>(s_in, sc2, st, psum, p);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
+}
+
 // The loads of the first blocks of a stream (blocks 0 .. RING-3), started before anything else in
 // the kernel -- the query fragments are fetched while they fly.
 template <int RING>
@@ -703,7 +709,7 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
     const LaneOffsets lo = lane_offsets();
     // block 0 has landed when at most the NF younger blocks are in flight; loads of the caller
     // that are younger still (the query fragments) only make this wait longer
-    f32x16 s_b[RB];
+    f32x16 s_b[RB], s_c[RB];
     if (first[NF - 1] != 0) wait_blocks<NF>(); else wait_blocks<0>();
     ring_barrier();
     scores<RB>(lds, lo, qf, s_b);
@@ -728,7 +734,19 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
     for (;;) {
         // ---- fast stretch: bodies that need no descriptor, no mask and no table look-up
         const int n_fast = plan.fast_bodies();
-        for (int i = 0; i < n_fast; ++i) {
+        for (int i = 0; i + 1 < n_fast; i += 2) {                     // in pairs: the scores ping-pong between s_b and s_c
+            wait_blocks<NF >= 2 ? NF - 1 : 0>();
+            ring_barrier();
+            int next_pv_off = plan.o_cur;
+            pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, vf, plan);
+            pv_off = next_pv_off;
+            wait_blocks<NF >= 2 ? NF - 1 : 0>();
+            ring_barrier();
+            next_pv_off = plan.o_cur;
+            pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, plan);
+            pv_off = next_pv_off;
+        }
+        if (n_fast & 1) {
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             const int next_pv_off = plan.o_cur;
