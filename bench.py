@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
 # same counters' reading for a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": (788636 * 2 + 1048576) * 1024,     # 2.689 GB
-                          "flash_prefill_kernel": (271251 * 2 + 39877) * 1024,     # 0.596 GB
+MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": (790432 * 2 + 1048610) * 1024,     # 2.693 GB
+                          "flash_prefill_kernel": (272131 * 2 + 37786) * 1024,     # 0.596 GB
                           "decode_kernel": (262890 * 2 + 1056) * 1024}             # 0.539 GB
 
 
