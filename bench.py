@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the batched-decode (config 5) region")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
+    ap.add_argument("--sequential-comparator", action="store_true",
+                    help="also time the causal attention that the parallel encoding replaces: the same 131K context "
+                         "tokens encoded as ONE chunk (Eq.2), for an attention-only prefill ratio on this GPU")
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time torch's bf16 GEMM (the vendor library) on zero and on random operands: context "
                          "for the MFMA roofline, which on this chip depends on the operand data (power limit)")
@@ -156,6 +159,28 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(roof["kernel"])
     roof["launch_ms"] = float({"flash_encode_kernel": ms_enc, "flash_prefill_kernel": ms_pre, "decode_kernel": ms_dec / max(1, args.decode_steps)}[roof["kernel"]])
+
+    seq_cmp = None
+    if args.sequential_comparator:
+        m_tok = spec.total_ctx_len
+        cu1 = [0, m_tok]
+        cu1_dev = torch.tensor(cu1, dtype=torch.int32, device=dev)
+
+        def seq_encode():
+            B.encode_chunks(shape, None, r.k_prefix, r.v_prefix, r.q_ctx, r.k_ctx, r.v_ctx, cu1, cu1_dev, None, o_ctx)
+        seq_encode()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            seq_encode()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_seq = e0.elapsed_time(e1) / 3
+        fl_seq = 4.0 * d * hq * (m_tok * (m_tok + 1) // 2 + m_tok * spec.prefix_len)
+        seq_cmp = {"ms": ms_seq, "tflops": fl_seq / (ms_seq * 1e-3) / 1e12,
+                   "attention_time_ratio_vs_parallel_encode": ms_seq / ms_enc,
+                   "note": "one causal chunk of %d tokens vs %d chunks of %d encoded in parallel" % (m_tok, len(r.chunk_lens), r.chunk_lens[0])}
 
     gemm_ref = None
     if args.gemm_reference:
@@ -261,6 +286,8 @@ def main():
     }
     if gemm_ref is not None:
         line["gemm_reference"] = gemm_ref
+    if seq_cmp is not None:
+        line["sequential_comparator"] = seq_cmp
     print(json.dumps(line))
 
 
