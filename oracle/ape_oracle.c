@@ -19,6 +19,10 @@
  *                                (C.3 / C.4, equal to Eq.5); mode 1 applies S
  *                                to each context's LogSumExp separately (C.2
  *                                as literally written).
+ *   - ape_oracle_attention_tree  Appendix C.2 applied recursively to a tree of
+ *                                contexts (Appendix C.5): every node merges
+ *                                its children by a softmax over their
+ *                                LogSumExps and multiplies its own by S_n.
  *   - ape_oracle_encode          Section 2.2 "Pre-caching Contexts" with the
  *                                shared prefix of Section 4.1: every context
  *                                row attends causally to the prefix and to
@@ -275,6 +279,142 @@ int ape_oracle_attention_hier(int n_q_heads, int n_kv_heads, int d,
         }
         if (lse) lse[p] = Ltot;
         free(A); free(Vh); free(x);
+    }
+    return bad ? -1 : 0;
+}
+
+/*
+ * Appendix C.2 applied recursively along a tree of contexts (the tree-shaped
+ * cache of Appendix C.5).
+ *
+ * A node n has a scaling factor S_n and an ordered list of children, which
+ * are either all cached contexts (node_leaf[n] != 0: contexts
+ * node_first[n] .. node_first[n] + node_count[n] - 1 of the chunk table) or
+ * all nodes (node_leaf[n] == 0: nodes node_first[n] .. + node_count[n] - 1,
+ * each with an index larger than n).  Node 0 is the root.
+ *
+ *   context i:  V_i = Softmax(q.K_i / (T sqrt d)) V_i,  A_i = LogSumExp(same scores)
+ *   node n:     V_n = Softmax(A_children) [V_children],
+ *               A_n = S_n * LogSumExp(A_children)
+ *   result:     O = Softmax(A_other, A_root) [V_other, V_root], where "other" is
+ *               the unscaled block of prefix + causal self tokens (C.1-C.2).
+ *
+ * Special cases: a root with scale S over all contexts is the pooled form
+ * (C.3, equal to Eq.5); a root with scale 1 over N one-context nodes of scale
+ * S is C.2 as literally written.
+ */
+typedef struct {
+    const float *qv;            /* the query vector, d floats */
+    const float *k_ctx, *v_ctx; /* packed contexts, already offset to the KV head */
+    const int *cu;
+    int n_chunks, n_nodes, d;
+    long kv_stride;
+    double score_scale;         /* 1 / (T sqrt d) */
+    const double *node_scale;
+    const int *node_first, *node_count, *node_leaf;
+    int bad;
+} tree_query;
+
+/* writes V_n into vh[d], returns A_n */
+static double tree_node_value(tree_query *tq, int n, double *vh)
+{
+    const int d = tq->d, cnt = tq->node_count[n], first = tq->node_first[n];
+    for (int c = 0; c < d; ++c) vh[c] = 0.0;
+    if (cnt <= 0) { tq->bad = 1; return -INFINITY; }
+    double *A = (double *)malloc(sizeof(double) * (size_t)cnt);
+    double *V = (double *)malloc(sizeof(double) * (size_t)cnt * d);
+    for (int i = 0; i < cnt; ++i) {
+        const int ch = first + i;
+        if (tq->node_leaf[n]) {
+            if (ch < 0 || ch >= tq->n_chunks) { tq->bad = 1; A[i] = -INFINITY; continue; }
+            const long t0 = tq->cu[ch], len = tq->cu[ch + 1] - t0;
+            double *x = (double *)malloc(sizeof(double) * (size_t)(len + 1));
+            for (long t = 0; t < len; ++t)
+                x[t] = dot_fd(tq->qv, tq->k_ctx + (t0 + t) * tq->kv_stride, d) * tq->score_scale;
+            A[i] = block_softmax_value(x, len, tq->v_ctx + t0 * tq->kv_stride, tq->kv_stride, d, V + (long)i * d);
+            free(x);
+        } else {
+            if (ch <= n || ch >= tq->n_nodes) { tq->bad = 1; A[i] = -INFINITY; continue; }
+            A[i] = tree_node_value(tq, ch, V + (long)i * d);
+        }
+    }
+    const double L = logsumexp(A, cnt);
+    if (L > -INFINITY)
+        for (int i = 0; i < cnt; ++i) {
+            if (!(A[i] > -INFINITY)) continue;
+            const double w = exp(A[i] - L);
+            for (int c = 0; c < d; ++c) vh[c] += w * V[(long)i * d + c];
+        }
+    free(A); free(V);
+    return tq->node_scale[n] * L;      /* all children empty: stays -inf (S_n > 0) */
+}
+
+int ape_oracle_attention_tree(int n_q_heads, int n_kv_heads, int d,
+                              const float *k_prefix, const float *v_prefix, int prefix_len,
+                              const float *k_ctx, const float *v_ctx,
+                              const int *cu_chunk_lens, int n_chunks,
+                              const float *k_self, const float *v_self, int self_len,
+                              const float *q, int q_len, double T,
+                              const double *node_scale, const int *node_first, const int *node_count,
+                              const int *node_leaf, int n_nodes,
+                              const int *pair_rows, const int *pair_heads, long n_pairs,
+                              double *out, double *lse)
+{
+    if (n_q_heads <= 0 || n_kv_heads <= 0 || d <= 0 || n_q_heads % n_kv_heads) return -1;
+    if (q_len <= 0 || self_len < q_len || prefix_len < 0 || n_chunks < 1 || n_nodes < 1) return -1;
+    if (!(T > 0.0)) return -1;
+    for (int n = 0; n < n_nodes; ++n) if (!(node_scale[n] > 0.0)) return -1;
+    const int G = n_q_heads / n_kv_heads;
+    const long kv_stride = (long)n_kv_heads * d;
+    const double inv_sqrt_d = 1.0 / sqrt((double)d);
+    const int all = (pair_rows == NULL);
+    if (all) n_pairs = (long)q_len * n_q_heads;
+    int bad = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long p = 0; p < n_pairs; ++p) {
+        const int r = all ? (int)(p / n_q_heads) : pair_rows[p];
+        const int h = all ? (int)(p % n_q_heads) : pair_heads[p];
+        if (r < 0 || r >= q_len || h < 0 || h >= n_q_heads) { bad = 1; continue; }
+        const int hk = h / G;
+        const float *qv = q + ((long)r * n_q_heads + h) * d;
+        const long n_self = (long)self_len - q_len + r + 1;
+
+        double *v_root = (double *)malloc(sizeof(double) * (size_t)d);
+        double *v_other = (double *)malloc(sizeof(double) * (size_t)d);
+        double *x = (double *)malloc(sizeof(double) * (size_t)(prefix_len + n_self + 1));
+
+        tree_query tq;
+        tq.qv = qv; tq.k_ctx = k_ctx + (long)hk * d; tq.v_ctx = v_ctx + (long)hk * d;
+        tq.cu = cu_chunk_lens; tq.n_chunks = n_chunks; tq.n_nodes = n_nodes; tq.d = d;
+        tq.kv_stride = kv_stride; tq.score_scale = inv_sqrt_d / T;
+        tq.node_scale = node_scale; tq.node_first = node_first; tq.node_count = node_count;
+        tq.node_leaf = node_leaf; tq.bad = 0;
+        const double A_root = tree_node_value(&tq, 0, v_root);
+        if (tq.bad) bad = 1;
+
+        /* non-context block: prefix and causal self tokens share one softmax (C.1) */
+        for (long j = 0; j < prefix_len; ++j)
+            x[j] = dot_fd(qv, k_prefix + j * kv_stride + (long)hk * d, d) * inv_sqrt_d;
+        for (long j = 0; j < n_self; ++j)
+            x[prefix_len + j] = dot_fd(qv, k_self + j * kv_stride + (long)hk * d, d) * inv_sqrt_d;
+        const double A_other = logsumexp(x, prefix_len + n_self);
+        for (int c = 0; c < d; ++c) v_other[c] = 0.0;
+        for (long j = 0; j < prefix_len + n_self; ++j) {
+            const double w = exp(x[j] - A_other);
+            const float *vv = j < prefix_len ? v_prefix + j * kv_stride + (long)hk * d
+                                             : v_self + (j - prefix_len) * kv_stride + (long)hk * d;
+            for (int c = 0; c < d; ++c) v_other[c] += w * (double)vv[c];
+        }
+
+        const double two[2] = { A_root, A_other };
+        const double Ltot = logsumexp(two, 2);
+        const double w_root = A_root > -INFINITY ? exp(A_root - Ltot) : 0.0;
+        const double w_other = exp(A_other - Ltot);
+        double *o = out + p * d;
+        for (int c = 0; c < d; ++c) o[c] = w_root * v_root[c] + w_other * v_other[c];
+        if (lse) lse[p] = Ltot;
+        free(v_root); free(v_other); free(x);
     }
     return bad ? -1 : 0;
 }

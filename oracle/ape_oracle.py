@@ -47,6 +47,9 @@ def _load():
         lib.ape_oracle_attention_hier.argtypes = [i, i, i, fp, fp, i, fp, fp, ip, i, fp, fp, i, fp, i, d, d, i,
                                                   ip, ip, l, dp, dp]
         lib.ape_oracle_attention_hier.restype = i
+        lib.ape_oracle_attention_tree.argtypes = [i, i, i, fp, fp, i, fp, fp, ip, i, fp, fp, i, fp, i, d,
+                                                  dp, ip, ip, ip, i, ip, ip, l, dp, dp]
+        lib.ape_oracle_attention_tree.restype = i
         lib.ape_oracle_encode.argtypes = [i, i, i, fp, fp, i, fp, fp, fp, ip, i, ip, ip, l, dp, dp]
         lib.ape_oracle_encode.restype = i
         lib.ape_oracle_num_threads.restype = i
@@ -128,6 +131,42 @@ def attention(q, k_prefix, v_prefix, k_ctx, v_ctx, chunk_lens, k_self, v_self, T
     if rc != 0:
         raise ValueError("ape_oracle: bad arguments")
     return out, lse, mass
+
+
+def attention_tree(q, k_prefix, v_prefix, k_ctx, v_ctx, chunk_lens, k_self, v_self, T: float, nodes,
+                   pairs=None):
+    """APE attention over a tree of contexts (Appendix C.2 applied per node, Appendix C.5).
+
+    ``nodes``: list of (scale, first, count, leaf_children); node 0 is the root.  The children
+    of node n are contexts first .. first+count-1 when ``leaf_children`` is true, else nodes
+    first .. first+count-1 (indices above n).  Returns (out [n, d], lse [n]).
+    """
+    lib = _load()
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    q_len, hq, d = q.shape
+    k_self = np.ascontiguousarray(k_self, dtype=np.float32)
+    hkv = k_self.shape[1]
+    tail = (hkv, d)
+    k_self, v_self = _f32(k_self, tail), _f32(v_self, tail)
+    k_prefix, v_prefix = _f32(k_prefix, tail), _f32(v_prefix, tail)
+    k_ctx, v_ctx = _f32(k_ctx, tail), _f32(v_ctx, tail)
+    cu = _cu(chunk_lens)
+    assert cu[-1] == k_ctx.shape[0] == v_ctx.shape[0]
+    scale = np.ascontiguousarray([n[0] for n in nodes], dtype=np.float64)
+    first = np.ascontiguousarray([n[1] for n in nodes], dtype=np.int32)
+    count = np.ascontiguousarray([n[2] for n in nodes], dtype=np.int32)
+    leaf = np.ascontiguousarray([1 if n[3] else 0 for n in nodes], dtype=np.int32)
+    pr, ph, n = _pairs(pairs, q_len, hq)
+    out = np.empty((n, d), dtype=np.float64)
+    lse = np.empty(n, dtype=np.float64)
+    rc = lib.ape_oracle_attention_tree(hq, hkv, d, _ptr(k_prefix), _ptr(v_prefix), k_prefix.shape[0],
+                                       _ptr(k_ctx), _ptr(v_ctx), _ptr(cu), len(chunk_lens),
+                                       _ptr(k_self), _ptr(v_self), k_self.shape[0], _ptr(q), q_len,
+                                       float(T), _ptr(scale), _ptr(first), _ptr(count), _ptr(leaf), len(nodes),
+                                       _ptr(pr), _ptr(ph), n, _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise ValueError("ape_oracle: bad arguments")
+    return out, lse
 
 
 def encode(q_ctx, k_prefix, v_prefix, k_ctx, v_ctx, chunk_lens, pairs=None):

@@ -191,3 +191,51 @@ def make_request(spec: WorkloadSpec, device="cpu", run_index: int = 0, request: 
 def to_numpy_f32(x: torch.Tensor):
     """Exact fp32 copy of an fp32/bf16 tensor on the host (what the oracle reads)."""
     return x.detach().to(torch.float32).cpu().numpy()
+
+
+# ---- context trees (Appendix C.5): structure only, (scale, first, count, leaf_children) per node.
+# Node 0 is the root; the children of a node are either contexts first..first+count-1 of the
+# chunk table or nodes first..first+count-1, and node children are numbered in the order of
+# their parents (breadth-first), so every child index is above its parent's.
+
+def tree_pooled(n_chunks: int, scale: float):
+    """One node over all contexts: the pooled scaling factor of the main-text equation."""
+    return [(float(scale), 0, n_chunks, True)]
+
+
+def tree_per_context(n_chunks: int, scale: float):
+    """Root of scale 1 over one node per context, each with the scaling factor (Appendix C.2)."""
+    return [(1.0, 1, n_chunks, False)] + [(float(scale), i, 1, True) for i in range(n_chunks)]
+
+
+def tree_grouped(n_chunks: int, group: int, root_scale: float, group_scale: float):
+    """Two levels: consecutive runs of `group` contexts under one node each."""
+    n_groups = (n_chunks + group - 1) // group
+    nodes = [(float(root_scale), 1, n_groups, False)]
+    for g in range(n_groups):
+        first = g * group
+        nodes.append((float(group_scale), first, min(group, n_chunks - first), True))
+    return nodes
+
+
+def tree_random(n_chunks: int, seed: int, max_children: int = 4, s_range=(0.6, 1.0)):
+    """A random tree of mixed depth over the contexts in table order.  Built top-down: a node
+    that owns a run of contexts either takes them as leaf children or deals them out to child
+    nodes; breadth-first numbering falls out of the work queue."""
+    import random
+    rng = random.Random(seed)
+    nodes, queue = [], [(0, n_chunks)]
+    while queue:
+        lo, hi = queue.pop(0)
+        scale = rng.uniform(*s_range)
+        n = hi - lo
+        if n <= 2 or rng.random() < 0.3:
+            nodes.append((scale, lo, n, True))
+            continue
+        k = rng.randint(2, min(max_children, n))
+        cuts = sorted(rng.sample(range(lo + 1, hi), k - 1))
+        bounds = [lo] + cuts + [hi]
+        first_child = len(nodes) + 1 + len(queue)
+        nodes.append((scale, first_child, k, False))
+        queue.extend((bounds[i], bounds[i + 1]) for i in range(k))
+    return nodes
