@@ -11,6 +11,8 @@
  *   ape_attention_decode   query's own causal KV with the refined attention of
  *                          Section 4.4 ("Eq.5"): context scores use 1/(T sqrt d),
  *                          the pooled context partition sum is raised to S.
+ *   ape_attention_tree     the same over a tree of contexts with a scaling factor per
+ *                          node (Appendix C.2 and C.5); S per context is one such tree.
  *
  * General conventions
  *   - Every data pointer marked DEVICE points to GPU memory owned by the caller;
@@ -146,6 +148,65 @@ int ape_attention_prefill(const ape_shape *shape, const ape_request *req,
 int ape_attention_decode(const ape_shape *shape, const ape_request *reqs, int32_t batch,
                          const void *q, void *out, float *lse_out,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One node of a tree of contexts (Appendix C.5: a cache whose contexts form a hierarchy).
+ * Appendix C.2 is applied at every node: a node merges its children by a softmax over their
+ * LogSumExp values A, and its own value is A_n = scale * LogSumExp(A_children).  The children
+ * of a node are EITHER cached contexts (leaf_children != 0: contexts first .. first+count-1 of
+ * the request's chunk table, each with the unscaled LogSumExp of its scores q.k/(T sqrt d))
+ * OR nodes (leaf_children == 0: nodes first .. first+count-1).
+ * Numbering: node 0 is the root; node children are numbered breadth-first, i.e. in the order
+ * of their parents (the first non-leaf node's children start at 1, the next one's follow
+ * directly, ...), so that every child index is above its parent's and every level of the tree
+ * is one index range.  Every context of the chunk table belongs to exactly one node.
+ */
+typedef struct {
+    float scale;                /* S_n, finite and > 0                                           */
+    int32_t first;              /* first child: context index or node index                      */
+    int32_t count;              /* number of children, >= 1                                      */
+    int32_t leaf_children;      /* != 0: the children are contexts; 0: they are nodes            */
+} ape_tree_node;
+
+#define APE_TREE_MAX_NODES 2048
+#define APE_TREE_MAX_CONTEXTS 4096
+#define APE_TREE_MAX_DEPTH 16
+
+/*
+ * Bytes of DEVICE workspace ape_attention_tree needs for a request with n_chunks contexts of
+ * at most max_chunk_len tokens and q_len query rows (depends on these sizes only).
+ * Returns 0 on invalid arguments.
+ */
+size_t ape_tree_workspace_bytes(const ape_shape *shape, int32_t n_chunks, int32_t max_chunk_len, int32_t q_len);
+
+/*
+ * Attention of q_len query rows of ONE request over prefix + a tree of cached contexts + own
+ * causal KV: Appendix C.2 applied per node (Appendix C.5).  The result is
+ * Softmax(A_other, A_root) [V_other, V_root] with "other" the unscaled block of prefix and
+ * causal self tokens.  Two trees reproduce the flat forms: one node of scale S over all
+ * contexts is ape_attention_prefill (pooled S, Eq.5); a root of scale 1 over one node of
+ * scale S per context is Appendix C.2 as written (S per context).
+ * Every context is attended in whole blocks of its own (its partial results never mix with a
+ * neighbour's), which is what the per-node scaling needs.
+ *
+ *   req            HOST  as for ape_attention_prefill; req->scale is not used (the nodes carry
+ *                  the scaling factors) but must still be valid; n_chunks >= 1
+ *   nodes_host     HOST  [n_nodes], validated before anything is launched
+ *   nodes_dev      DEVICE copy of the same array (read by the kernels); the caller keeps the
+ *                  two equal
+ *   max_chunk_len  HOST  upper bound of the context lengths; only balances the work (a longer
+ *                  context is still attended completely)
+ *   q, out         DEVICE [q_len, n_q_heads, d]; q_len == 1 is a decode step
+ *   lse_out        DEVICE fp32 [n_q_heads, q_len] or NULL: log(exp(A_other) + exp(A_root))
+ *   workspace      DEVICE, >= ape_tree_workspace_bytes(shape, n_chunks, max_chunk_len, q_len)
+ * Limits: n_nodes <= APE_TREE_MAX_NODES, n_chunks <= APE_TREE_MAX_CONTEXTS, depth <=
+ * APE_TREE_MAX_DEPTH levels of nodes (APE_ERR_UNSUPPORTED beyond).
+ */
+int ape_attention_tree(const ape_shape *shape, const ape_request *req,
+                       const ape_tree_node *nodes_host, const ape_tree_node *nodes_dev, int32_t n_nodes,
+                       int32_t max_chunk_len,
+                       const void *q, int32_t q_len, void *out, float *lse_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /* Text for a status code (static storage). */
 const char *ape_status_string(int status);

@@ -24,7 +24,9 @@ APE_DTYPE_FLAG_GENERIC = 0x100
 APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
 
 EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
+           "ape_tree_workspace_bytes", "ape_attention_tree",
            "ape_status_string", "ape_last_error", "ape_version")
+APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
 
 
 class ApeShape(ctypes.Structure):
@@ -40,6 +42,11 @@ class ApeRequest(ctypes.Structure):
                 ("total_ctx_len", ctypes.c_int32), ("self_len", ctypes.c_int32),
                 ("k_self", ctypes.c_void_p), ("v_self", ctypes.c_void_p),
                 ("temperature", ctypes.c_float), ("scale", ctypes.c_float)]
+
+
+class ApeTreeNode(ctypes.Structure):
+    _fields_ = [("scale", ctypes.c_float), ("first", ctypes.c_int32), ("count", ctypes.c_int32),
+                ("leaf_children", ctypes.c_int32)]
 
 
 class ApeError(RuntimeError):
@@ -71,6 +78,11 @@ def load() -> ctypes.CDLL:
         lib.ape_attention_decode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), i32, vp, vp, vp,
                                              vp, sz, vp]
         lib.ape_attention_decode.restype = ctypes.c_int
+        lib.ape_tree_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32]
+        lib.ape_tree_workspace_bytes.restype = sz
+        lib.ape_attention_tree.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, vp, i32, i32,
+                                           vp, i32, vp, vp, vp, sz, vp]
+        lib.ape_attention_tree.restype = ctypes.c_int
         lib.ape_status_string.argtypes = [ctypes.c_int]
         lib.ape_status_string.restype = ctypes.c_char_p
         lib.ape_last_error.restype = ctypes.c_char_p
@@ -196,6 +208,37 @@ def attention_decode(shape: ApeShape, reqs: Sequence[Request], q: torch.Tensor, 
     arr = (ApeRequest * n)(*[r.as_struct(None if self_lens is None else self_lens[i]) for i, r in enumerate(reqs)])
     rc = load().ape_attention_decode(ctypes.byref(shape), arr, n, _ptr(q), _ptr(out), _ptr(lse_out),
                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc)
+
+
+@dataclass
+class Tree:
+    """A context tree for ``attention_tree``: the host array of ``ape_tree_node`` and its device copy."""
+    host: ctypes.Array
+    dev: torch.Tensor
+    n_nodes: int
+
+
+def make_tree(nodes: Sequence, device) -> Tree:
+    """``nodes``: sequence of (scale, first, count, leaf_children), node 0 the root."""
+    n = len(nodes)
+    host = (ApeTreeNode * max(n, 1))(*[ApeTreeNode(float(s), int(f), int(c), 1 if leaf else 0) for s, f, c, leaf in nodes])
+    raw = torch.frombuffer(bytearray(bytes(host)), dtype=torch.int32).clone()      # bit copy, 4 words per node
+    return Tree(host=host, dev=raw.to(device), n_nodes=n)
+
+
+def tree_workspace_bytes(shape: ApeShape, n_chunks: int, max_chunk_len: int, q_len: int) -> int:
+    return int(load().ape_tree_workspace_bytes(ctypes.byref(shape), n_chunks, max_chunk_len, q_len))
+
+
+def attention_tree(shape: ApeShape, req: Request, tree: Tree, max_chunk_len: int, q: torch.Tensor, out: torch.Tensor,
+                   lse_out: Optional[torch.Tensor], workspace: torch.Tensor, stream=None, self_len=None):
+    """``ape_attention_tree``: q/out [q_len, Hq, d]; lse_out fp32 [Hq, q_len] or None."""
+    r = req.as_struct(self_len)
+    rc = load().ape_attention_tree(ctypes.byref(shape), ctypes.byref(r), ctypes.cast(tree.host, ctypes.c_void_p),
+                                   _ptr(tree.dev), tree.n_nodes, max_chunk_len, _ptr(q), q.shape[0], _ptr(out),
+                                   _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream))
     _check(rc)
 
 

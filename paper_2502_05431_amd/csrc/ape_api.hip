@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 namespace ape {
 namespace {
@@ -86,6 +87,79 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     n = ceil_div(max_ctx, len);
     p.n_ctx_splits = n; p.ctx_split_len = (int)len; p.n_splits_total = n + 1;
     return p;
+}
+
+// Per-context splits of the tree entry point: every context gets `sub` splits of `len` tokens
+// (the last one open-ended), enough of them to fill the chip when the contexts are few and long.
+struct TreePlan {
+    int sub;
+    int len;
+    int n_splits_total;         // n_chunks * sub + 1
+};
+constexpr long kMaxTreeSplits = 16384;
+
+TreePlan plan_tree(const ShapeInfo& si, int n_chunks, int max_chunk_len, int q_len) {
+    const bool decode = q_len == 1;
+    int base, target, min_len;
+    if (si.mfma && decode) { base = si.hkv; target = 2048; min_len = 512; }
+    else if (si.mfma) {
+        const int rows = q_len * si.group;
+        base = si.hkv * ceil_div(rows, flash_block_rows(rows)); target = 256; min_len = 256;
+    } else { base = q_len * si.hq; target = 1024; min_len = 256; }
+    int sub = ceil_div(target, (long)base * n_chunks);
+    const int cap = ceil_div(max_chunk_len > 0 ? max_chunk_len : 1, min_len);
+    if (sub > cap) sub = cap;
+    if ((long)sub * n_chunks > kMaxTreeSplits) sub = (int)(kMaxTreeSplits / n_chunks);
+    if (sub < 1) sub = 1;
+    long len = ((long)(max_chunk_len > 0 ? max_chunk_len : 1) + sub - 1) / sub;
+    len = (len + 63) / 64 * 64;
+    TreePlan p;
+    p.sub = sub; p.len = (int)len; p.n_splits_total = n_chunks * sub + 1;
+    return p;
+}
+
+// Checks the numbering rules of ape_tree_node and finds the level ranges.
+int check_tree(const ape_tree_node* nodes, int n_nodes, int n_chunks, int* n_levels, int32_t* level_start) {
+    if (!nodes) return fail(APE_ERR_INVALID_ARG, "tree nodes are NULL");
+    if (n_nodes < 1) return fail(APE_ERR_INVALID_ARG, "a tree needs at least one node (got %d)", n_nodes);
+    if (n_nodes > APE_TREE_MAX_NODES) return fail(APE_ERR_UNSUPPORTED, "%d tree nodes, at most %d are supported", n_nodes, APE_TREE_MAX_NODES);
+    if (n_chunks < 1) return fail(APE_ERR_INVALID_ARG, "a tree needs at least one context");
+    if (n_chunks > APE_TREE_MAX_CONTEXTS) return fail(APE_ERR_UNSUPPORTED, "%d contexts, at most %d are supported under a tree", n_chunks, APE_TREE_MAX_CONTEXTS);
+    std::vector<char> owned((size_t)n_chunks, 0);
+    long next_child = 1;
+    for (int n = 0; n < n_nodes; ++n) {
+        const ape_tree_node& t = nodes[n];
+        if (!(std::isfinite(t.scale) && t.scale > 0.f)) return fail(APE_ERR_INVALID_ARG, "tree node %d: scale must be finite and > 0", n);
+        if (t.count < 1) return fail(APE_ERR_INVALID_ARG, "tree node %d: count %d < 1", n, t.count);
+        if (t.leaf_children) {
+            if (t.first < 0 || (long)t.first + t.count > n_chunks) return fail(APE_ERR_INVALID_ARG, "tree node %d: contexts %d..%ld are outside the chunk table of %d", n, t.first, (long)t.first + t.count - 1, n_chunks);
+            for (int i = 0; i < t.count; ++i) {
+                if (owned[t.first + i]) return fail(APE_ERR_INVALID_ARG, "tree node %d: context %d already belongs to another node", n, t.first + i);
+                owned[t.first + i] = 1;
+            }
+        } else {
+            if (t.first != next_child) return fail(APE_ERR_INVALID_ARG, "tree node %d: node children must start at %ld (breadth-first numbering), got %d", n, next_child, t.first);
+            next_child += t.count;
+            if (next_child > n_nodes) return fail(APE_ERR_INVALID_ARG, "tree node %d: children run past the %d nodes given", n, n_nodes);
+        }
+    }
+    if (next_child != n_nodes) return fail(APE_ERR_INVALID_ARG, "%ld of the %d nodes are reachable from the root", next_child, n_nodes);
+    for (int c = 0; c < n_chunks; ++c)
+        if (!owned[c]) return fail(APE_ERR_INVALID_ARG, "context %d belongs to no tree node", c);
+    // levels: the node children of one level are the next level, and they are contiguous
+    int lv = 0;
+    level_start[0] = 0; level_start[1] = 1;
+    while (true) {
+        long kids = 0;
+        for (int n = level_start[lv]; n < level_start[lv + 1]; ++n)
+            if (!nodes[n].leaf_children) kids += nodes[n].count;
+        if (kids == 0) break;
+        if (lv + 1 >= kMaxTreeLevels) return fail(APE_ERR_UNSUPPORTED, "the tree is deeper than %d levels of nodes", kMaxTreeLevels);
+        ++lv;
+        level_start[lv + 1] = level_start[lv] + (int32_t)kids;
+    }
+    *n_levels = lv + 1;
+    return APE_OK;
 }
 
 size_t partial_bytes(long units, int n_splits_total, int d) {
@@ -251,6 +325,61 @@ int ape_attention_decode(const ape_shape* shape, const ape_request* reqs, int32_
     if (!reqs || !q || !out) return fail(APE_ERR_INVALID_ARG, "reqs, q and out must not be NULL");
     if (batch < 1) return fail(APE_ERR_INVALID_ARG, "batch %d < 1", batch);
     return run_query(si, reqs, batch, 1, true, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t ape_tree_workspace_bytes(const ape_shape* shape, int32_t n_chunks, int32_t max_chunk_len, int32_t q_len) {
+    ShapeInfo si;
+    if (check_shape(shape, &si) != APE_OK) return 0;
+    if (n_chunks < 1 || n_chunks > APE_TREE_MAX_CONTEXTS || max_chunk_len < 0 || q_len < 1) return 0;
+    const TreePlan p = plan_tree(si, n_chunks, max_chunk_len, q_len);
+    return partial_bytes((long)q_len * si.hq, p.n_splits_total, si.d);
+}
+
+int ape_attention_tree(const ape_shape* shape, const ape_request* req,
+                       const ape_tree_node* nodes_host, const ape_tree_node* nodes_dev, int32_t n_nodes,
+                       int32_t max_chunk_len,
+                       const void* q, int32_t q_len, void* out, float* lse_out,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (!req || !q || !out) return fail(APE_ERR_INVALID_ARG, "req, q and out must not be NULL");
+    if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
+    if (max_chunk_len < 0) return fail(APE_ERR_INVALID_ARG, "max_chunk_len %d < 0", max_chunk_len);
+    rc = check_request(req, q_len, 0);
+    if (rc) return rc;
+    TreeMergeArgs m{};
+    rc = check_tree(nodes_host, n_nodes, req->n_chunks, &m.n_levels, m.level_start);
+    if (rc) return rc;
+    if (!nodes_dev) return fail(APE_ERR_INVALID_ARG, "the device copy of the tree nodes is NULL");
+
+    const TreePlan plan = plan_tree(si, req->n_chunks, max_chunk_len, q_len);
+    const long units = (long)q_len * si.hq;
+    const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
+    if (!workspace || workspace_bytes < need)
+        return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_tree_workspace_bytes gives the size)", workspace_bytes, need);
+    if ((uintptr_t)workspace % kWsAlign) return fail(APE_ERR_WORKSPACE, "workspace must be %d-byte aligned", kWsAlign);
+    float* part_o = (float*)workspace;
+    float* part_lse = (float*)((char*)workspace + align_up((size_t)units * plan.n_splits_total * si.d * sizeof(float), kWsAlign));
+    hipStream_t st = (hipStream_t)stream;
+
+    QueryArgs a{};
+    a.req[0] = to_view(req);
+    a.q = q; a.part_o = part_o; a.part_lse = part_lse;
+    a.n_req = 1; a.q_len = q_len; a.n_q_heads = si.hq; a.n_kv_heads = si.hkv; a.head_dim = si.d;
+    a.n_ctx_splits = plan.n_splits_total - 1; a.ctx_split_len = plan.len; a.sub_splits = plan.sub;
+    a.units_total = (int)units; a.req_base = 0;
+    hipError_t he;
+    if (si.mfma) he = q_len == 1 ? launch_decode_mfma(a, st) : launch_flash_prefill(a, st);
+    else he = launch_generic_query(a, si.dtype, st);
+    if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
+
+    m.part_o = part_o; m.part_lse = part_lse; m.out = out; m.lse_out = lse_out; m.nodes = nodes_dev;
+    m.n_nodes = n_nodes; m.n_chunks = req->n_chunks; m.sub_splits = plan.sub; m.units_total = (int)units;
+    m.q_len = q_len; m.n_q_heads = si.hq; m.head_dim = si.d; m.dtype = si.dtype;
+    he = launch_tree_merge(m, st);
+    if (he != hipSuccess) return fail(APE_ERR_DEVICE, "tree merge kernel: %s", hipGetErrorString(he));
+    return APE_OK;
 }
 
 }  // extern "C"

@@ -255,8 +255,8 @@ __global__ __launch_bounds__(NT, 2) void decode_kernel(const QueryArgs a) {
 
     Stream sm;
     if (split < a.n_ctx_splits) {
-        const long t0 = (long)split * a.ctx_split_len;
-        const long t1 = min((long)kv.total_ctx, t0 + a.ctx_split_len);
+        long t0, t1;
+        ctx_split_range(a, kv, split, t0, t1);
         // this wavefront's share: a multiple of 32 tokens
         const long per = t0 < t1 ? ((t1 - t0 + NW - 1) / NW + BT - 1) / BT * BT : 0;
         const long t = t0 + wave * per;

@@ -114,8 +114,8 @@ __global__ __launch_bounds__(kWave) void generic_query_kernel(const QueryArgs a)
     if (split < a.n_ctx_splits) {
         // context group, tokens [t0, t1) of the pooled contexts, temperature in the scale
         const float scale = inv_sqrt_d / kv.temperature;
-        long t0 = (long)split * a.ctx_split_len;
-        const long t1 = min((long)kv.total_ctx, t0 + a.ctx_split_len);
+        long t0, t1;
+        ctx_split_range(a, kv, split, t0, t1);
         if (t0 < t1) {
             int c = 0;                                   // chunk that holds t0 (upper-bound search)
             int lo = 0, hi = kv.n_chunks - 1;
@@ -291,6 +291,159 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeA
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Tree merge (Appendix C.2 applied at every node of a tree of contexts, Appendix C.5).
+// The attention kernels ran with per-context splits, so every partial belongs to one context.
+// One workgroup of kMergeWaves wavefronts per (row, head), everything in log units:
+//   1. L_i  = LogSumExp of the splits of context i                          (C.1, exact)
+//   2. bottom-up, one level of nodes at a time, deepest first:
+//        L_n = LogSumExp over the children of their values A, A_leaf = L_i, A_node = S_n L_n
+//   3. the root meets the prefix+self block: Ltot = log(exp(A_root) + exp(L_other)); top-down,
+//      the log-weight of a child is W_child = W_n + A_child - L_n, starting at W_root = A_root - Ltot
+//   4. the output is sum over splits of exp(W_i + lse_split - L_i) o_split, plus the prefix+self
+//      block with weight exp(L_other - Ltot): the weights sum to one, nothing is divided.
+// A level with many nodes gives each thread a node (children read serially); a narrow level
+// gives each wavefront a node (children across the lanes).
+__device__ __forceinline__ float child_value(const ape_tree_node* nd, const float* leaf_l, const float* node_l,
+                                             bool leaf_children, int child) {
+    return leaf_children ? leaf_l[child] : nd[child].scale * node_l[child];    // S_n > 0: -inf stays -inf
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const TreeMergeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char tree_lds[];
+    __shared__ float part[kMergeWaves][kWave * kMaxDimRegs];
+    __shared__ float s_ltot;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    constexpr int NT = kWave * kMergeWaves;
+    const int unit = blockIdx.x;
+    const int d = a.head_dim, U = a.units_total, k = a.sub_splits;
+    const int n_nodes = a.n_nodes, n_chunks = a.n_chunks, n_ctx_splits = n_chunks * k;
+
+    ape_tree_node* nd = (ape_tree_node*)tree_lds;                  // [n_nodes]
+    float* node_l = (float*)(nd + n_nodes);                        // [n_nodes] LogSumExp of the children's values
+    float* node_w = node_l + n_nodes;                              // [n_nodes] log-weight in the result
+    float* leaf_l = node_w + n_nodes;                              // [n_chunks] LogSumExp of a context
+    float* leaf_w = leaf_l + n_chunks;                             // [n_chunks] log-weight of a context
+
+    for (int n = tid; n < n_nodes; n += NT) nd[n] = a.nodes[n];
+    for (int c = tid; c < n_chunks; c += NT) {
+        const float* p = a.part_lse + (long)c * k * U + unit;
+        float m = -INFINITY;
+        for (int j = 0; j < k; ++j) m = fmaxf(m, p[(long)j * U]);
+        float z = 0.f;
+        if (m > -INFINITY)
+            for (int j = 0; j < k; ++j) z += expf(p[(long)j * U] - m);
+        leaf_l[c] = m > -INFINITY ? m + logf(z) : -INFINITY;
+    }
+    __syncthreads();
+
+    // ---- bottom-up
+    for (int lv = a.n_levels - 1; lv >= 0; --lv) {
+        const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
+        if (n1 - n0 >= kWave) {
+            for (int n = n0 + tid; n < n1; n += NT) {
+                const ape_tree_node me = nd[n];
+                float m = -INFINITY;
+                for (int i = 0; i < me.count; ++i) m = fmaxf(m, child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i));
+                float z = 0.f;
+                if (m > -INFINITY)
+                    for (int i = 0; i < me.count; ++i) z += expf(child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i) - m);
+                node_l[n] = m > -INFINITY ? m + logf(z) : -INFINITY;
+            }
+        } else {
+            for (int n = n0 + wave; n < n1; n += kMergeWaves) {
+                const ape_tree_node me = nd[n];
+                float m = -INFINITY;
+                for (int i = lane; i < me.count; i += kWave) m = fmaxf(m, child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i));
+                m = wave_max(m);
+                float z = 0.f;
+                if (m > -INFINITY)
+                    for (int i = lane; i < me.count; i += kWave) z += expf(child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i) - m);
+                z = wave_sum(z);
+                if (lane == 0) node_l[n] = m > -INFINITY ? m + logf(z) : -INFINITY;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- the root against the prefix + self block (never empty)
+    const float l_other = a.part_lse[(long)n_ctx_splits * U + unit];
+    if (tid == 0) {
+        const float a_root = nd[0].scale * node_l[0];
+        const float mx = fmaxf(a_root, l_other);
+        const float ltot = mx + logf(expf(a_root - mx) + expf(l_other - mx));
+        s_ltot = ltot;
+        node_w[0] = a_root > -INFINITY ? a_root - ltot : -INFINITY;
+    }
+    __syncthreads();
+    const float ltot = s_ltot;
+
+    // ---- top-down
+    for (int lv = 0; lv < a.n_levels; ++lv) {
+        const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
+        const bool per_thread = n1 - n0 >= kWave;
+        for (int n = n0 + (per_thread ? tid : wave); n < n1; n += per_thread ? NT : kMergeWaves) {
+            const ape_tree_node me = nd[n];
+            const float w_n = node_w[n], l_n = node_l[n];
+            const bool leaf = me.leaf_children != 0;
+            for (int i = per_thread ? 0 : lane; i < me.count; i += per_thread ? 1 : kWave) {
+                const float v = child_value(nd, leaf_l, node_l, leaf, me.first + i);
+                const float w = (w_n > -INFINITY && v > -INFINITY) ? w_n + v - l_n : -INFINITY;
+                if (leaf) leaf_w[me.first + i] = w; else node_w[me.first + i] = w;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- weighted sum of the split results
+    float acc[kMaxDimRegs];
+#pragma unroll
+    for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = 0.f;
+    const int n_splits = n_ctx_splits + 1;
+    for (int s0 = 0; s0 < n_splits; s0 += kWave) {
+        const int s = s0 + lane;
+        float w_mine = 0.f;
+        if (s < n_ctx_splits) {
+            const int c = s / k;
+            const float wl = leaf_w[c];
+            if (wl > -INFINITY) {
+                const float ls = a.part_lse[(long)s * U + unit];
+                if (ls > -INFINITY) w_mine = expf(wl + (ls - leaf_l[c]));
+            }
+        } else if (s == n_ctx_splits) {
+            w_mine = expf(l_other - ltot);
+        }
+        const int cnt = min(kWave, n_splits - s0);
+        for (int i = wave; i < cnt; i += kMergeWaves) {
+            const float w = __shfl(w_mine, i);
+            const float* o = a.part_o + ((long)(s0 + i) * U + unit) * d;
+#pragma unroll
+            for (int r = 0; r < kMaxDimRegs; ++r) {
+                const int c = lane + kWave * r;
+                if (c < d) acc[r] = fmaf(w, o[c], acc[r]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kMaxDimRegs; ++r) part[wave][lane + kWave * r] = acc[r];
+    __syncthreads();
+    if (wave != 0) return;
+    T* out = (T*)a.out + (long)unit * d;
+#pragma unroll
+    for (int r = 0; r < kMaxDimRegs; ++r) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMergeWaves; ++w) v += part[w][lane + kWave * r];
+        const int c = lane + kWave * r;
+        if (c < d) out[c] = (T)v;
+    }
+    if (a.lse_out && lane == 0) {
+        const int h = unit % a.n_q_heads, row = unit / a.n_q_heads;
+        a.lse_out[(long)h * a.q_len + row] = ltot;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s) {
@@ -312,6 +465,22 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
     dim3 grid((unsigned)(a.n_req * a.q_len * a.n_q_heads));
     if (a.dtype == APE_F32) merge_kernel<float><<<grid, kWave * kMergeWaves, 0, s>>>(a);
     else merge_kernel<__bf16><<<grid, kWave * kMergeWaves, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s) {
+    dim3 grid((unsigned)a.units_total);
+    const size_t lds = (size_t)a.n_nodes * (sizeof(ape_tree_node) + 2 * sizeof(float)) + (size_t)a.n_chunks * 2 * sizeof(float);
+    hipError_t e;
+    if (a.dtype == APE_F32) {
+        e = hipFuncSetAttribute((const void*)tree_merge_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        tree_merge_kernel<float><<<grid, kWave * kMergeWaves, lds, s>>>(a);
+    } else {
+        e = hipFuncSetAttribute((const void*)tree_merge_kernel<__bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        tree_merge_kernel<__bf16><<<grid, kWave * kMergeWaves, lds, s>>>(a);
+    }
     return hipGetLastError();
 }
 

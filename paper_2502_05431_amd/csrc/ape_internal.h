@@ -43,6 +43,10 @@ struct QueryArgs {
     int32_t head_dim;
     int32_t n_ctx_splits;       // splits of the context group; split index n_ctx_splits is prefix + self
     int32_t ctx_split_len;      // context tokens per split (multiple of 64)
+    int32_t sub_splits;         // 0: the splits cut the pooled contexts into runs of ctx_split_len tokens.
+                                // k >= 1 (one request only): every context has k splits of its own, split s
+                                // covering tokens [sub*ctx_split_len, ...) of context s / k, sub = s % k; the
+                                // last one runs to the end of the context
     int32_t units_total;        // n_req * q_len * Hq (stride of the split dimension)
     int32_t req_base;           // index of req[0] in the whole batch
 };
@@ -63,6 +67,26 @@ struct MergeArgs {
     int32_t req_base;
     int32_t lse_head_major;     // 1: lse_out[h*q_len + r] (prefill); 0: lse_out[unit] (decode)
     int32_t dtype;
+};
+
+// Kernel-argument block of the tree merge (Appendix C.2 per node, C.5).
+constexpr int kMaxTreeLevels = APE_TREE_MAX_DEPTH;
+struct TreeMergeArgs {
+    const float* part_o;        // [n_chunks*sub_splits + 1][units][d]; the last split is prefix + self
+    const float* part_lse;
+    void* out;
+    float* lse_out;             // NULL or fp32 [Hq, q_len]
+    const ape_tree_node* nodes; // device [n_nodes]
+    int32_t n_nodes;
+    int32_t n_chunks;
+    int32_t sub_splits;
+    int32_t units_total;        // q_len * Hq
+    int32_t q_len;
+    int32_t n_q_heads;
+    int32_t head_dim;
+    int32_t dtype;
+    int32_t n_levels;
+    int32_t level_start[kMaxTreeLevels + 1];   // nodes of level l: [level_start[l], level_start[l+1])
 };
 
 struct EncodeArgs {
@@ -118,6 +142,20 @@ __device__ __forceinline__ const void* scalar_load_ptr(const void* const* p) {
     return (const void*)v;
 }
 
+// Context tokens [t0, t1) (indices into the pooled contexts) that split `split` of request view
+// `kv` covers; t0 >= t1 for an empty split.  `split` must be wavefront-uniform.
+__device__ __forceinline__ void ctx_split_range(const QueryArgs& a, const KvView& kv, int split, long& t0, long& t1) {
+    if (a.sub_splits == 0) {
+        t0 = (long)split * a.ctx_split_len;
+        t1 = min((long)kv.total_ctx, t0 + a.ctx_split_len);
+        return;
+    }
+    const int c = split / a.sub_splits, sub = split - c * a.sub_splits;
+    const long c0 = scalar_load_i32(kv.cu + c), c1 = scalar_load_i32(kv.cu + c + 1);
+    t0 = min(c1, c0 + (long)sub * a.ctx_split_len);
+    t1 = sub == a.sub_splits - 1 ? c1 : min(c1, t0 + a.ctx_split_len);
+}
+
 template <typename Args>
 __device__ __forceinline__ KvView load_view(int rq) {
     auto ap = kernarg<Args>();
@@ -143,6 +181,7 @@ struct QueryPlan {
 hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s);
 hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s);     // bf16, d = 128
 hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s);     // bf16, d = 128
 hipError_t launch_decode_mfma(const QueryArgs& a, hipStream_t s);       // bf16, d = 128, q_len = 1

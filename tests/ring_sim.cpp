@@ -185,6 +185,21 @@ int main() {
                 run_case(t, what, [&] { Stream ld; ld.init_ctx(cu.data(), kc.data(), vc.data(), (int)lens.size(), t0, t1, stride_b, 0); return ld; }, valid,
                          {0}, t1 - t0);
             }
+        // per-context splits (tree merge): every context cut into `sub` runs of its own, the last
+        // one open-ended; empty runs never reach the block loop
+        const int max_len = *std::max_element(lens.begin(), lens.end());
+        for (int sub : {1, 2, 3, 5})
+            for (size_t c = 0; c < lens.size(); ++c)
+                for (int j = 0; j < sub; ++j) {
+                    const int len = ((max_len + sub - 1) / sub + 63) / 64 * 64;
+                    const int c0 = cu[c], c1 = cu[c + 1];
+                    const int t0 = std::min(c1, c0 + j * len);
+                    const int t1 = j == sub - 1 ? c1 : std::min(c1, t0 + len);
+                    if (t0 >= t1) continue;
+                    std::snprintf(what, sizeof what, "ctx table=%zu context=%zu sub=%d/%d", v, c, j, sub);
+                    run_case(t, what, [&] { Stream ld; ld.init_ctx(cu.data(), kc.data(), vc.data(), (int)lens.size(), t0, t1, stride_b, 0); return ld; }, valid,
+                             {0}, t1 - t0);
+                }
     }
     std::printf("%d streams, %d failed; %d of %d bodies fast\n", t.cases, t.failed, t.fast, t.bodies);
     return t.failed != 0;
