@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--sequential-comparator", action="store_true",
                     help="also time the causal attention that the parallel encoding replaces: the same 131K context "
                          "tokens encoded as ONE chunk (Eq.2), for an attention-only prefill ratio on this GPU")
+    ap.add_argument("--tree-variants", action="store_true",
+                    help="also time the query prefill and one decode step of the same 128K cache through the tree "
+                         "entry point: one pooled node, a scaling factor per context, and a two-level tree")
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time torch's bf16 GEMM (the vendor library) on zero and on random operands: context "
                          "for the MFMA roofline, which on this chip depends on the operand data (power limit)")
@@ -182,6 +185,38 @@ def main():
                    "attention_time_ratio_vs_parallel_encode": ms_seq / ms_enc,
                    "note": "one causal chunk of %d tokens vs %d chunks of %d encoded in parallel" % (m_tok, len(r.chunk_lens), r.chunk_lens[0])}
 
+    tree_var = None
+    if args.tree_variants:
+        n_ch = len(r.chunk_lens)
+        ws_t = torch.empty(max(B.tree_workspace_bytes(shape, spec.total_ctx_len, n_ch + 1, spec.q_len),
+                               B.tree_workspace_bytes(shape, spec.total_ctx_len, n_ch + 1, 1)) // 4, dtype=torch.float32, device=dev)
+        qd1 = r.q_self[spec.q_len - 1:spec.q_len].contiguous()
+        od1 = torch.empty_like(qd1)
+        tree_var = {}
+        for name, nodes in (("pooled_one_node", W.tree_pooled(n_ch, r.scale)),
+                            ("scaling_factor_per_context", W.tree_per_context(n_ch, r.scale)),
+                            ("two_levels_groups_of_8", W.tree_grouped(n_ch, 8, 0.9, r.scale))):
+            tree = B.make_tree(nodes, dev)
+            res = {"nodes": len(nodes)}
+            for kind, fn in (("prefill_ms", lambda: B.attention_tree(shape, req, tree, q, out, None, ws_t)),
+                             ("decode_ms_per_token", lambda: B.attention_tree(shape, req, tree, qd1, od1, None, ws_t))):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                res[kind] = e0.elapsed_time(e1) / 20
+            res["prefill_tflops"] = fl_pre / (res["prefill_ms"] * 1e-3) / 1e12
+            res["decode_gbs"] = (kv_row_bytes * (spec.prefix_len + spec.total_ctx_len + spec.q_len)) / (res["decode_ms_per_token"] * 1e-3) / 1e9
+            tree_var[name] = res
+        tree_var["note"] = ("same cache and query as the prefill phase (flat entry point: %.3f ms); the contexts of every "
+                            "node are attended in splits of their own and the tree merge replaces the two-group merge" % ms_pre)
+        del ws_t
+
     gemm_ref = None
     if args.gemm_reference:
         n = 8192
@@ -288,6 +323,8 @@ def main():
         line["gemm_reference"] = gemm_ref
     if seq_cmp is not None:
         line["sequential_comparator"] = seq_cmp
+    if tree_var is not None:
+        line["tree_variants"] = tree_var
     print(json.dumps(line))
 
 

@@ -173,11 +173,11 @@ typedef struct {
 #define APE_TREE_MAX_DEPTH 16
 
 /*
- * Bytes of DEVICE workspace ape_attention_tree needs for a request with n_chunks contexts of
- * at most max_chunk_len tokens and q_len query rows (depends on these sizes only).
+ * Bytes of DEVICE workspace ape_attention_tree needs for a request with total_ctx_len context
+ * tokens, a tree of n_nodes nodes and q_len query rows (depends on these sizes only).
  * Returns 0 on invalid arguments.
  */
-size_t ape_tree_workspace_bytes(const ape_shape *shape, int32_t n_chunks, int32_t max_chunk_len, int32_t q_len);
+size_t ape_tree_workspace_bytes(const ape_shape *shape, int32_t total_ctx_len, int32_t n_nodes, int32_t q_len);
 
 /*
  * Attention of q_len query rows of ONE request over prefix + a tree of cached contexts + own
@@ -186,25 +186,23 @@ size_t ape_tree_workspace_bytes(const ape_shape *shape, int32_t n_chunks, int32_
  * causal self tokens.  Two trees reproduce the flat forms: one node of scale S over all
  * contexts is ape_attention_prefill (pooled S, Eq.5); a root of scale 1 over one node of
  * scale S per context is Appendix C.2 as written (S per context).
- * Every context is attended in whole blocks of its own (its partial results never mix with a
- * neighbour's), which is what the per-node scaling needs.
+ * The contexts of one node merge exactly (Appendix C.1) and are attended as one run of tokens;
+ * partial results never mix contexts of different nodes, which is what the per-node scaling needs.
  *
  *   req            HOST  as for ape_attention_prefill; req->scale is not used (the nodes carry
  *                  the scaling factors) but must still be valid; n_chunks >= 1
  *   nodes_host     HOST  [n_nodes], validated before anything is launched
  *   nodes_dev      DEVICE copy of the same array (read by the kernels); the caller keeps the
  *                  two equal
- *   max_chunk_len  HOST  upper bound of the context lengths; only balances the work (a longer
- *                  context is still attended completely)
  *   q, out         DEVICE [q_len, n_q_heads, d]; q_len == 1 is a decode step
  *   lse_out        DEVICE fp32 [n_q_heads, q_len] or NULL: log(exp(A_other) + exp(A_root))
- *   workspace      DEVICE, >= ape_tree_workspace_bytes(shape, n_chunks, max_chunk_len, q_len)
+ *   workspace      DEVICE, >= ape_tree_workspace_bytes(shape, req->total_ctx_len, n_nodes, q_len),
+ *                  256-byte aligned
  * Limits: n_nodes <= APE_TREE_MAX_NODES, n_chunks <= APE_TREE_MAX_CONTEXTS, depth <=
  * APE_TREE_MAX_DEPTH levels of nodes (APE_ERR_UNSUPPORTED beyond).
  */
 int ape_attention_tree(const ape_shape *shape, const ape_request *req,
                        const ape_tree_node *nodes_host, const ape_tree_node *nodes_dev, int32_t n_nodes,
-                       int32_t max_chunk_len,
                        const void *q, int32_t q_len, void *out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *stream);
 

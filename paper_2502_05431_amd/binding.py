@@ -80,7 +80,7 @@ def load() -> ctypes.CDLL:
         lib.ape_attention_decode.restype = ctypes.c_int
         lib.ape_tree_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32]
         lib.ape_tree_workspace_bytes.restype = sz
-        lib.ape_attention_tree.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, vp, i32, i32,
+        lib.ape_attention_tree.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, vp, i32,
                                            vp, i32, vp, vp, vp, sz, vp]
         lib.ape_attention_tree.restype = ctypes.c_int
         lib.ape_status_string.argtypes = [ctypes.c_int]
@@ -227,16 +227,16 @@ def make_tree(nodes: Sequence, device) -> Tree:
     return Tree(host=host, dev=raw.to(device), n_nodes=n)
 
 
-def tree_workspace_bytes(shape: ApeShape, n_chunks: int, max_chunk_len: int, q_len: int) -> int:
-    return int(load().ape_tree_workspace_bytes(ctypes.byref(shape), n_chunks, max_chunk_len, q_len))
+def tree_workspace_bytes(shape: ApeShape, total_ctx_len: int, n_nodes: int, q_len: int) -> int:
+    return int(load().ape_tree_workspace_bytes(ctypes.byref(shape), total_ctx_len, n_nodes, q_len))
 
 
-def attention_tree(shape: ApeShape, req: Request, tree: Tree, max_chunk_len: int, q: torch.Tensor, out: torch.Tensor,
+def attention_tree(shape: ApeShape, req: Request, tree: Tree, q: torch.Tensor, out: torch.Tensor,
                    lse_out: Optional[torch.Tensor], workspace: torch.Tensor, stream=None, self_len=None):
     """``ape_attention_tree``: q/out [q_len, Hq, d]; lse_out fp32 [Hq, q_len] or None."""
     r = req.as_struct(self_len)
     rc = load().ape_attention_tree(ctypes.byref(shape), ctypes.byref(r), ctypes.cast(tree.host, ctypes.c_void_p),
-                                   _ptr(tree.dev), tree.n_nodes, max_chunk_len, _ptr(q), q.shape[0], _ptr(out),
+                                   _ptr(tree.dev), tree.n_nodes, _ptr(q), q.shape[0], _ptr(out),
                                    _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream))
     _check(rc)

@@ -89,32 +89,31 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     return p;
 }
 
-// Per-context splits of the tree entry point: every context gets `sub` splits of `len` tokens
-// (the last one open-ended), enough of them to fill the chip when the contexts are few and long.
+// Splits of the tree entry point: the contexts of every node that holds contexts are cut into
+// runs of `len` tokens; `len` is what the flat entry points would use for the same sizes, so a
+// one-node tree runs exactly like them.  max_splits bounds the splits in use from sizes only:
+// sum over such nodes of ceil(tokens / len) <= total / len + number of nodes.
 struct TreePlan {
-    int sub;
     int len;
-    int n_splits_total;         // n_chunks * sub + 1
+    int max_splits;
+    size_t partial_bytes, plan_bytes;
 };
-constexpr long kMaxTreeSplits = 16384;
 
-TreePlan plan_tree(const ShapeInfo& si, int n_chunks, int max_chunk_len, int q_len) {
-    const bool decode = q_len == 1;
-    int base, target, min_len;
-    if (si.mfma && decode) { base = si.hkv; target = 2048; min_len = 512; }
-    else if (si.mfma) {
+TreePlan plan_tree(const ShapeInfo& si, long total_ctx, int n_nodes, int q_len) {
+    QueryPlan qp;
+    if (q_len == 1) qp = plan_query(si.mfma ? si.hkv : si.hq, total_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
+    else {
         const int rows = q_len * si.group;
-        base = si.hkv * ceil_div(rows, flash_block_rows(rows)); target = 256; min_len = 256;
-    } else { base = q_len * si.hq; target = 1024; min_len = 256; }
-    int sub = ceil_div(target, (long)base * n_chunks);
-    const int cap = ceil_div(max_chunk_len > 0 ? max_chunk_len : 1, min_len);
-    if (sub > cap) sub = cap;
-    if ((long)sub * n_chunks > kMaxTreeSplits) sub = (int)(kMaxTreeSplits / n_chunks);
-    if (sub < 1) sub = 1;
-    long len = ((long)(max_chunk_len > 0 ? max_chunk_len : 1) + sub - 1) / sub;
-    len = (len + 63) / 64 * 64;
+        const int base = si.mfma ? si.hkv * ceil_div(rows, flash_block_rows(rows)) : q_len * si.hq;
+        qp = plan_query(base, total_ctx, 256, si.mfma ? 256 : 1024);
+    }
     TreePlan p;
-    p.sub = sub; p.len = (int)len; p.n_splits_total = n_chunks * sub + 1;
+    p.len = qp.ctx_split_len;
+    p.max_splits = ceil_div(total_ctx > 0 ? total_ctx : 1, p.len) + n_nodes;
+    const long units = (long)q_len * si.hq;
+    p.partial_bytes = align_up((size_t)units * (p.max_splits + 1) * si.d * sizeof(float), kWsAlign) +
+                      align_up((size_t)units * (p.max_splits + 1) * sizeof(float), kWsAlign);
+    p.plan_bytes = align_up((size_t)TreePlanLayout{n_nodes, p.max_splits}.words() * sizeof(int32_t), kWsAlign);
     return p;
 }
 
@@ -327,17 +326,17 @@ int ape_attention_decode(const ape_shape* shape, const ape_request* reqs, int32_
     return run_query(si, reqs, batch, 1, true, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
-size_t ape_tree_workspace_bytes(const ape_shape* shape, int32_t n_chunks, int32_t max_chunk_len, int32_t q_len) {
+size_t ape_tree_workspace_bytes(const ape_shape* shape, int32_t total_ctx_len, int32_t n_nodes, int32_t q_len) {
     ShapeInfo si;
     if (check_shape(shape, &si) != APE_OK) return 0;
-    if (n_chunks < 1 || n_chunks > APE_TREE_MAX_CONTEXTS || max_chunk_len < 0 || q_len < 1) return 0;
-    const TreePlan p = plan_tree(si, n_chunks, max_chunk_len, q_len);
-    return partial_bytes((long)q_len * si.hq, p.n_splits_total, si.d);
+    if (total_ctx_len < 0 || n_nodes < 1 || n_nodes > APE_TREE_MAX_NODES || q_len < 1) return 0;
+    const TreePlan p = plan_tree(si, total_ctx_len, n_nodes, q_len);
+    if (p.max_splits > kMaxTreeSplits) return 0;
+    return p.partial_bytes + p.plan_bytes;
 }
 
 int ape_attention_tree(const ape_shape* shape, const ape_request* req,
                        const ape_tree_node* nodes_host, const ape_tree_node* nodes_dev, int32_t n_nodes,
-                       int32_t max_chunk_len,
                        const void* q, int32_t q_len, void* out, float* lse_out,
                        void* workspace, size_t workspace_bytes, void* stream) {
     ShapeInfo si;
@@ -345,7 +344,6 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     if (rc) return rc;
     if (!req || !q || !out) return fail(APE_ERR_INVALID_ARG, "req, q and out must not be NULL");
     if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
-    if (max_chunk_len < 0) return fail(APE_ERR_INVALID_ARG, "max_chunk_len %d < 0", max_chunk_len);
     rc = check_request(req, q_len, 0);
     if (rc) return rc;
     TreeMergeArgs m{};
@@ -353,29 +351,38 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     if (rc) return rc;
     if (!nodes_dev) return fail(APE_ERR_INVALID_ARG, "the device copy of the tree nodes is NULL");
 
-    const TreePlan plan = plan_tree(si, req->n_chunks, max_chunk_len, q_len);
+    const TreePlan plan = plan_tree(si, req->total_ctx_len, n_nodes, q_len);
+    if (plan.max_splits > kMaxTreeSplits)
+        return fail(APE_ERR_UNSUPPORTED, "%d splits would be needed, at most %d are supported", plan.max_splits, kMaxTreeSplits);
     const long units = (long)q_len * si.hq;
-    const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
+    const size_t need = plan.partial_bytes + plan.plan_bytes;
     if (!workspace || workspace_bytes < need)
         return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_tree_workspace_bytes gives the size)", workspace_bytes, need);
     if ((uintptr_t)workspace % kWsAlign) return fail(APE_ERR_WORKSPACE, "workspace must be %d-byte aligned", kWsAlign);
     float* part_o = (float*)workspace;
-    float* part_lse = (float*)((char*)workspace + align_up((size_t)units * plan.n_splits_total * si.d * sizeof(float), kWsAlign));
+    float* part_lse = (float*)((char*)workspace + align_up((size_t)units * (plan.max_splits + 1) * si.d * sizeof(float), kWsAlign));
+    int32_t* plan_dev = (int32_t*)((char*)workspace + plan.partial_bytes);
     hipStream_t st = (hipStream_t)stream;
+
+    TreePlanArgs tp{};
+    tp.nodes = nodes_dev; tp.cu = req->cu_chunk_lens; tp.plan = plan_dev;
+    tp.n_nodes = n_nodes; tp.max_splits = plan.max_splits; tp.split_len = plan.len;
+    hipError_t he = launch_tree_plan(tp, st);
+    if (he != hipSuccess) return fail(APE_ERR_DEVICE, "tree plan kernel: %s", hipGetErrorString(he));
 
     QueryArgs a{};
     a.req[0] = to_view(req);
     a.q = q; a.part_o = part_o; a.part_lse = part_lse;
     a.n_req = 1; a.q_len = q_len; a.n_q_heads = si.hq; a.n_kv_heads = si.hkv; a.head_dim = si.d;
-    a.n_ctx_splits = plan.n_splits_total - 1; a.ctx_split_len = plan.len; a.sub_splits = plan.sub;
+    a.n_ctx_splits = plan.max_splits; a.ctx_split_len = plan.len;
+    a.split_ranges = plan_dev + TreePlanLayout{n_nodes, plan.max_splits}.ranges_at();
     a.units_total = (int)units; a.req_base = 0;
-    hipError_t he;
     if (si.mfma) he = q_len == 1 ? launch_decode_mfma(a, st) : launch_flash_prefill(a, st);
     else he = launch_generic_query(a, si.dtype, st);
     if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
 
-    m.part_o = part_o; m.part_lse = part_lse; m.out = out; m.lse_out = lse_out; m.nodes = nodes_dev;
-    m.n_nodes = n_nodes; m.n_chunks = req->n_chunks; m.sub_splits = plan.sub; m.units_total = (int)units;
+    m.part_o = part_o; m.part_lse = part_lse; m.out = out; m.lse_out = lse_out; m.nodes = nodes_dev; m.plan = plan_dev;
+    m.n_nodes = n_nodes; m.max_splits = plan.max_splits; m.units_total = (int)units;
     m.q_len = q_len; m.n_q_heads = si.hq; m.head_dim = si.d; m.dtype = si.dtype;
     he = launch_tree_merge(m, st);
     if (he != hipSuccess) return fail(APE_ERR_DEVICE, "tree merge kernel: %s", hipGetErrorString(he));

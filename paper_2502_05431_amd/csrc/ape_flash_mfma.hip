@@ -674,17 +674,14 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
         long t0, t1;
         ctx_split_range(a, kv, split, t0, t1);
         if (t0 >= t1) {
-            // an empty split (only possible with per-context splits): weight zero in the merge.
-            // The whole workgroup leaves here, before any barrier or load.
+            // An empty split (only a tree plan has them: slots past the splits in use).  Its
+            // LogSumExp says so and the merge never reads its values.  The whole workgroup
+            // leaves here, before any barrier or load.
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
                 const int tok = R / G, g = R % G;
-                if (tok >= q_len) continue;
-                const long slot = (long)split * a.units_total + (long)tok * hq + hk * G + g;
-                float* o = a.part_o + slot * D;
-                for (int c = hi * 64; c < hi * 64 + 64; c += 4) *(f32x4*)(o + c) = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (hi == 0) a.part_lse[slot] = -INFINITY;
+                if (tok < q_len && hi == 0) a.part_lse[(long)split * a.units_total + (long)tok * hq + hk * G + g] = -INFINITY;
             }
             return;
         }

@@ -292,21 +292,89 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeA
 }
 
 // ------------------------------------------------------------------------------------------
-// Tree merge (Appendix C.2 applied at every node of a tree of contexts, Appendix C.5).
-// The attention kernels ran with per-context splits, so every partial belongs to one context.
-// One workgroup of kMergeWaves wavefronts per (row, head), everything in log units:
-//   1. L_i  = LogSumExp of the splits of context i                          (C.1, exact)
-//   2. bottom-up, one level of nodes at a time, deepest first:
-//        L_n = LogSumExp over the children of their values A, A_leaf = L_i, A_node = S_n L_n
-//   3. the root meets the prefix+self block: Ltot = log(exp(A_root) + exp(L_other)); top-down,
-//      the log-weight of a child is W_child = W_n + A_child - L_n, starting at W_root = A_root - Ltot
-//   4. the output is sum over splits of exp(W_i + lse_split - L_i) o_split, plus the prefix+self
-//      block with weight exp(L_other - Ltot): the weights sum to one, nothing is divided.
+// Tree of contexts (Appendix C.2 applied at every node, Appendix C.5).
+//
+// Plan kernel: one workgroup.  A node whose children are contexts owns the tokens
+// [cu[first], cu[first + count]) of the pooled contexts (contexts of one node merge exactly,
+// Appendix C.1, so they need no boundary between them) and gets ceil(tokens / split_len) splits.
+// An exclusive scan over the nodes gives every such node its first split; the ranges of the
+// splits in use are written out, the slots behind them are left empty.
+constexpr int kPlanThreads = 1024;
+__global__ __launch_bounds__(kPlanThreads) void tree_plan_kernel(const TreePlanArgs a) {
+    __shared__ int cnt[APE_TREE_MAX_NODES];
+    __shared__ int off[APE_TREE_MAX_NODES];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const TreePlanLayout lay{a.n_nodes, a.max_splits};
+    int32_t* first_split = a.plan + lay.first_split_at();
+    int32_t* n_splits = a.plan + lay.n_splits_at();
+    int32_t* ranges = a.plan + lay.ranges_at();
+    for (int i = tid; i < 2 * a.max_splits; i += kPlanThreads) ranges[i] = 0;
+    for (int n = tid; n < APE_TREE_MAX_NODES; n += kPlanThreads) {
+        int c = 0;
+        if (n < a.n_nodes) {
+            const ape_tree_node me = a.nodes[n];
+            if (me.leaf_children) c = (a.cu[me.first + me.count] - a.cu[me.first] + a.split_len - 1) / a.split_len;
+        }
+        cnt[n] = c;
+    }
+    __syncthreads();
+    if (tid < kWave) {
+        // lane owns a run of consecutive nodes; wavefront scan of the run sums, then the runs
+        constexpr int RUN = APE_TREE_MAX_NODES / kWave;
+        int sum = 0;
+        for (int j = 0; j < RUN; ++j) sum += cnt[lane * RUN + j];
+        int incl = sum;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        int run = incl - sum;
+        for (int j = 0; j < RUN; ++j) { off[lane * RUN + j] = run; run += cnt[lane * RUN + j]; }
+        if (lane == kWave - 1) a.plan[0] = min(incl, a.max_splits);
+    }
+    __syncthreads();
+    for (int n = tid; n < a.n_nodes; n += kPlanThreads) {
+        first_split[n] = off[n];
+        n_splits[n] = cnt[n];
+        if (cnt[n] > 0) {
+            const ape_tree_node me = a.nodes[n];
+            const int t_begin = a.cu[me.first], t_end = a.cu[me.first + me.count];
+            for (int j = 0; j < cnt[n]; ++j) {
+                const int s = off[n] + j;
+                if (s >= a.max_splits) break;              // cannot happen with the host's bound; stay in bounds
+                const int t0 = t_begin + j * a.split_len;
+                ranges[2 * s] = t0;
+                ranges[2 * s + 1] = min(t_end, t0 + a.split_len);
+            }
+        }
+    }
+}
+
+// Tree merge.  One workgroup of kMergeWaves wavefronts per (row, head), everything in log units:
+//   1. bottom-up, one level of nodes at a time, deepest first:
+//        L_n = LogSumExp over the children of their values A; a child that is a split (of a node
+//        whose children are contexts: exact merge, C.1) has A = its LogSumExp, a child node has
+//        A = S_child L_child
+//   2. the root meets the prefix+self block: Ltot = log(exp(S_root L_root) + exp(L_other)); top-down,
+//      the log-weight of a child is W_child = W_n + A_child - L_n, starting at W_root = S_root L_root - Ltot
+//   3. the output is the sum over splits of exp(W_split) o_split plus the prefix+self block with
+//      weight exp(L_other - Ltot): the weights sum to one, nothing is divided.
 // A level with many nodes gives each thread a node (children read serially); a narrow level
 // gives each wavefront a node (children across the lanes).
-__device__ __forceinline__ float child_value(const ape_tree_node* nd, const float* leaf_l, const float* node_l,
-                                             bool leaf_children, int child) {
-    return leaf_children ? leaf_l[child] : nd[child].scale * node_l[child];    // S_n > 0: -inf stays -inf
+struct TreeLds {
+    const ape_tree_node* nd;
+    const int* first_split;
+    const float* node_l;
+    const float* split_v;
+};
+__device__ __forceinline__ int child_count(const TreeLds& t, const int* n_splits, int n) {
+    return t.nd[n].leaf_children ? n_splits[n] : t.nd[n].count;
+}
+__device__ __forceinline__ float child_value(const TreeLds& t, int n, int i) {
+    if (t.nd[n].leaf_children) return t.split_v[t.first_split[n] + i];
+    const int c = t.nd[n].first + i;
+    return t.nd[c].scale * t.node_l[c];                   // S > 0: -inf stays -inf
 }
 
 template <typename T>
@@ -317,49 +385,49 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const T
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr int NT = kWave * kMergeWaves;
     const int unit = blockIdx.x;
-    const int d = a.head_dim, U = a.units_total, k = a.sub_splits;
-    const int n_nodes = a.n_nodes, n_chunks = a.n_chunks, n_ctx_splits = n_chunks * k;
+    const int d = a.head_dim, U = a.units_total, n_nodes = a.n_nodes;
+    const TreePlanLayout lay{a.n_nodes, a.max_splits};
+    const int n_used = a.plan[0];
 
     ape_tree_node* nd = (ape_tree_node*)tree_lds;                  // [n_nodes]
     float* node_l = (float*)(nd + n_nodes);                        // [n_nodes] LogSumExp of the children's values
     float* node_w = node_l + n_nodes;                              // [n_nodes] log-weight in the result
-    float* leaf_l = node_w + n_nodes;                              // [n_chunks] LogSumExp of a context
-    float* leaf_w = leaf_l + n_chunks;                             // [n_chunks] log-weight of a context
+    int* first_split = (int*)(node_w + n_nodes);                   // [n_nodes]
+    int* n_splits = first_split + n_nodes;                         // [n_nodes]
+    float* split_v = (float*)(n_splits + n_nodes);                 // [max_splits] LogSumExp, later log-weight
 
-    for (int n = tid; n < n_nodes; n += NT) nd[n] = a.nodes[n];
-    for (int c = tid; c < n_chunks; c += NT) {
-        const float* p = a.part_lse + (long)c * k * U + unit;
-        float m = -INFINITY;
-        for (int j = 0; j < k; ++j) m = fmaxf(m, p[(long)j * U]);
-        float z = 0.f;
-        if (m > -INFINITY)
-            for (int j = 0; j < k; ++j) z += expf(p[(long)j * U] - m);
-        leaf_l[c] = m > -INFINITY ? m + logf(z) : -INFINITY;
+    for (int n = tid; n < n_nodes; n += NT) {
+        nd[n] = a.nodes[n];
+        first_split[n] = a.plan[lay.first_split_at() + n];
+        n_splits[n] = a.plan[lay.n_splits_at() + n];
     }
+    for (int s = tid; s < n_used; s += NT) split_v[s] = a.part_lse[(long)s * U + unit];
+    const float l_other = a.part_lse[(long)a.max_splits * U + unit];
     __syncthreads();
+    const TreeLds t{nd, first_split, node_l, split_v};
 
     // ---- bottom-up
     for (int lv = a.n_levels - 1; lv >= 0; --lv) {
         const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
         if (n1 - n0 >= kWave) {
             for (int n = n0 + tid; n < n1; n += NT) {
-                const ape_tree_node me = nd[n];
+                const int cn = child_count(t, n_splits, n);
                 float m = -INFINITY;
-                for (int i = 0; i < me.count; ++i) m = fmaxf(m, child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i));
+                for (int i = 0; i < cn; ++i) m = fmaxf(m, child_value(t, n, i));
                 float z = 0.f;
                 if (m > -INFINITY)
-                    for (int i = 0; i < me.count; ++i) z += expf(child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i) - m);
+                    for (int i = 0; i < cn; ++i) z += expf(child_value(t, n, i) - m);
                 node_l[n] = m > -INFINITY ? m + logf(z) : -INFINITY;
             }
         } else {
             for (int n = n0 + wave; n < n1; n += kMergeWaves) {
-                const ape_tree_node me = nd[n];
+                const int cn = child_count(t, n_splits, n);
                 float m = -INFINITY;
-                for (int i = lane; i < me.count; i += kWave) m = fmaxf(m, child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i));
+                for (int i = lane; i < cn; i += kWave) m = fmaxf(m, child_value(t, n, i));
                 m = wave_max(m);
                 float z = 0.f;
                 if (m > -INFINITY)
-                    for (int i = lane; i < me.count; i += kWave) z += expf(child_value(nd, leaf_l, node_l, me.leaf_children != 0, me.first + i) - m);
+                    for (int i = lane; i < cn; i += kWave) z += expf(child_value(t, n, i) - m);
                 z = wave_sum(z);
                 if (lane == 0) node_l[n] = m > -INFINITY ? m + logf(z) : -INFINITY;
             }
@@ -368,7 +436,6 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const T
     }
 
     // ---- the root against the prefix + self block (never empty)
-    const float l_other = a.part_lse[(long)n_ctx_splits * U + unit];
     if (tid == 0) {
         const float a_root = nd[0].scale * node_l[0];
         const float mx = fmaxf(a_root, l_other);
@@ -379,45 +446,38 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const T
     __syncthreads();
     const float ltot = s_ltot;
 
-    // ---- top-down
+    // ---- top-down: log-weights of nodes, and of splits in place of their LogSumExps
     for (int lv = 0; lv < a.n_levels; ++lv) {
         const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
         const bool per_thread = n1 - n0 >= kWave;
         for (int n = n0 + (per_thread ? tid : wave); n < n1; n += per_thread ? NT : kMergeWaves) {
-            const ape_tree_node me = nd[n];
+            const int cn = child_count(t, n_splits, n);
             const float w_n = node_w[n], l_n = node_l[n];
-            const bool leaf = me.leaf_children != 0;
-            for (int i = per_thread ? 0 : lane; i < me.count; i += per_thread ? 1 : kWave) {
-                const float v = child_value(nd, leaf_l, node_l, leaf, me.first + i);
+            const bool leaf = nd[n].leaf_children != 0;
+            for (int i = per_thread ? 0 : lane; i < cn; i += per_thread ? 1 : kWave) {
+                const float v = child_value(t, n, i);
                 const float w = (w_n > -INFINITY && v > -INFINITY) ? w_n + v - l_n : -INFINITY;
-                if (leaf) leaf_w[me.first + i] = w; else node_w[me.first + i] = w;
+                if (leaf) split_v[first_split[n] + i] = w; else node_w[nd[n].first + i] = w;
             }
         }
         __syncthreads();
     }
 
-    // ---- weighted sum of the split results
+    // ---- weighted sum of the split results; index n_used stands for the prefix + self block
     float acc[kMaxDimRegs];
 #pragma unroll
     for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = 0.f;
-    const int n_splits = n_ctx_splits + 1;
-    for (int s0 = 0; s0 < n_splits; s0 += kWave) {
+    for (int s0 = 0; s0 <= n_used; s0 += kWave) {
         const int s = s0 + lane;
         float w_mine = 0.f;
-        if (s < n_ctx_splits) {
-            const int c = s / k;
-            const float wl = leaf_w[c];
-            if (wl > -INFINITY) {
-                const float ls = a.part_lse[(long)s * U + unit];
-                if (ls > -INFINITY) w_mine = expf(wl + (ls - leaf_l[c]));
-            }
-        } else if (s == n_ctx_splits) {
-            w_mine = expf(l_other - ltot);
-        }
-        const int cnt = min(kWave, n_splits - s0);
+        if (s < n_used) w_mine = expf(split_v[s]);                 // exp(-inf) = 0
+        else if (s == n_used) w_mine = expf(l_other - ltot);
+        const int cnt = min(kWave, n_used + 1 - s0);
         for (int i = wave; i < cnt; i += kMergeWaves) {
             const float w = __shfl(w_mine, i);
-            const float* o = a.part_o + ((long)(s0 + i) * U + unit) * d;
+            if (w == 0.f) continue;                                // never read what an empty split left
+            const int sp = s0 + i < n_used ? s0 + i : a.max_splits;
+            const float* o = a.part_o + ((long)sp * U + unit) * d;
 #pragma unroll
             for (int r = 0; r < kMaxDimRegs; ++r) {
                 const int c = lane + kWave * r;
@@ -468,9 +528,14 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s) {
+    tree_plan_kernel<<<1, kPlanThreads, 0, s>>>(a);
+    return hipGetLastError();
+}
+
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s) {
     dim3 grid((unsigned)a.units_total);
-    const size_t lds = (size_t)a.n_nodes * (sizeof(ape_tree_node) + 2 * sizeof(float)) + (size_t)a.n_chunks * 2 * sizeof(float);
+    const size_t lds = (size_t)a.n_nodes * (sizeof(ape_tree_node) + 4 * sizeof(float)) + (size_t)a.max_splits * sizeof(float);
     hipError_t e;
     if (a.dtype == APE_F32) {
         e = hipFuncSetAttribute((const void*)tree_merge_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

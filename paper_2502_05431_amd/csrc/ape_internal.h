@@ -43,10 +43,9 @@ struct QueryArgs {
     int32_t head_dim;
     int32_t n_ctx_splits;       // splits of the context group; split index n_ctx_splits is prefix + self
     int32_t ctx_split_len;      // context tokens per split (multiple of 64)
-    int32_t sub_splits;         // 0: the splits cut the pooled contexts into runs of ctx_split_len tokens.
-                                // k >= 1 (one request only): every context has k splits of its own, split s
-                                // covering tokens [sub*ctx_split_len, ...) of context s / k, sub = s % k; the
-                                // last one runs to the end of the context
+    const int32_t* split_ranges; // NULL: split s covers tokens [s*ctx_split_len, ...) of the pooled contexts.
+                                // Else (one request only) DEVICE [2*n_ctx_splits]: split s covers tokens
+                                // [split_ranges[2s], split_ranges[2s+1]) of the pooled contexts; empty if equal
     int32_t units_total;        // n_req * q_len * Hq (stride of the split dimension)
     int32_t req_base;           // index of req[0] in the whole batch
 };
@@ -69,17 +68,41 @@ struct MergeArgs {
     int32_t dtype;
 };
 
+// Device-side plan of a tree call, written into the workspace by the plan kernel and read by the
+// attention and merge kernels.  Every node whose children are contexts ("group") owns a run of
+// consecutive splits that cover its contexts' tokens in runs of split_len; contexts of one group
+// merge exactly (Appendix C.1), so no split ever needs to stop at a context boundary inside a group.
+// Layout in int32 words: [0] number of splits in use, [1..3] unused, then first_split[n_nodes],
+// n_splits[n_nodes] (0 for nodes whose children are nodes), split_ranges[2 * max_splits].
+struct TreePlanLayout {
+    int n_nodes, max_splits;
+    __host__ __device__ long first_split_at() const { return 4; }
+    __host__ __device__ long n_splits_at() const { return 4 + (long)n_nodes; }
+    __host__ __device__ long ranges_at() const { return 4 + 2 * (long)n_nodes; }
+    __host__ __device__ long words() const { return 4 + 2 * (long)n_nodes + 2 * (long)max_splits; }
+};
+
+struct TreePlanArgs {
+    const ape_tree_node* nodes; // device [n_nodes]
+    const int32_t* cu;          // device [n_chunks + 1]
+    int32_t* plan;              // device, TreePlanLayout
+    int32_t n_nodes;
+    int32_t max_splits;
+    int32_t split_len;
+};
+
 // Kernel-argument block of the tree merge (Appendix C.2 per node, C.5).
 constexpr int kMaxTreeLevels = APE_TREE_MAX_DEPTH;
+constexpr int kMaxTreeSplits = 8192;
 struct TreeMergeArgs {
-    const float* part_o;        // [n_chunks*sub_splits + 1][units][d]; the last split is prefix + self
+    const float* part_o;        // [max_splits + 1][units][d]; split max_splits is prefix + self
     const float* part_lse;
     void* out;
     float* lse_out;             // NULL or fp32 [Hq, q_len]
     const ape_tree_node* nodes; // device [n_nodes]
+    const int32_t* plan;        // device, TreePlanLayout
     int32_t n_nodes;
-    int32_t n_chunks;
-    int32_t sub_splits;
+    int32_t max_splits;
     int32_t units_total;        // q_len * Hq
     int32_t q_len;
     int32_t n_q_heads;
@@ -145,15 +168,13 @@ __device__ __forceinline__ const void* scalar_load_ptr(const void* const* p) {
 // Context tokens [t0, t1) (indices into the pooled contexts) that split `split` of request view
 // `kv` covers; t0 >= t1 for an empty split.  `split` must be wavefront-uniform.
 __device__ __forceinline__ void ctx_split_range(const QueryArgs& a, const KvView& kv, int split, long& t0, long& t1) {
-    if (a.sub_splits == 0) {
+    if (a.split_ranges == nullptr) {
         t0 = (long)split * a.ctx_split_len;
         t1 = min((long)kv.total_ctx, t0 + a.ctx_split_len);
         return;
     }
-    const int c = split / a.sub_splits, sub = split - c * a.sub_splits;
-    const long c0 = scalar_load_i32(kv.cu + c), c1 = scalar_load_i32(kv.cu + c + 1);
-    t0 = min(c1, c0 + (long)sub * a.ctx_split_len);
-    t1 = sub == a.sub_splits - 1 ? c1 : min(c1, t0 + a.ctx_split_len);
+    t0 = scalar_load_i32(a.split_ranges + 2 * split);
+    t1 = scalar_load_i32(a.split_ranges + 2 * split + 1);
 }
 
 template <typename Args>
@@ -181,6 +202,7 @@ struct QueryPlan {
 hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s);
 hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s);
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s);     // bf16, d = 128
 hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s);     // bf16, d = 128

@@ -89,18 +89,16 @@ def run_prefill(spec: W.WorkloadSpec, r: W.RequestData, q_len: int, self_len: in
 
 
 def run_tree(spec: W.WorkloadSpec, r: W.RequestData, nodes, q_len: int, self_len: int, generic=False, req=None,
-             want_lse=True, max_chunk_len=None):
+             want_lse=True):
     dev = r.k_self.device
     shape = B.make_shape(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.torch_dtype, generic=generic)
     req = req or make_binding_request(r, self_len)
     tree = B.make_tree(nodes, dev)
-    if max_chunk_len is None:
-        max_chunk_len = max(r.chunk_lens)
     q = r.q_self[self_len - q_len:self_len].contiguous()
     out = torch.full_like(q, float("nan"))
     lse = torch.full((spec.n_q_heads, q_len), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
-    ws = poisoned_workspace(B.tree_workspace_bytes(shape, len(r.chunk_lens), max_chunk_len, q_len), dev)
-    B.attention_tree(shape, req, tree, max_chunk_len, q, out, lse, ws, self_len=self_len)
+    ws = poisoned_workspace(B.tree_workspace_bytes(shape, sum(r.chunk_lens), len(nodes), q_len), dev)
+    B.attention_tree(shape, req, tree, q, out, lse, ws, self_len=self_len)
     torch.cuda.synchronize()
     return out, lse
 

@@ -119,12 +119,12 @@ def test_decode_and_encode_argument_errors():
     assert enc(ctypes.cast(cu2, ctypes.c_void_p), FAKE, prefix_len=-2) == B.APE_ERR_INVALID_ARG
 
 
-def _tree(nodes, req=None, nodes_dev=FAKE, n_nodes=None, ws=None, ws_bytes=0, max_chunk_len=64, q_len=8):
+def _tree(nodes, req=None, nodes_dev=FAKE, n_nodes=None, ws=None, ws_bytes=0, q_len=8):
     sh = B.make_shape(32, 8, 128, B.APE_BF16)
     arr = (B.ApeTreeNode * max(len(nodes), 1))(*[B.ApeTreeNode(*n) for n in nodes])
     r = req or _req(n_chunks=4, total_ctx_len=200)
     return B.load().ape_attention_tree(ctypes.byref(sh), ctypes.byref(r), ctypes.cast(arr, ctypes.c_void_p), nodes_dev,
-                                       len(nodes) if n_nodes is None else n_nodes, max_chunk_len, FAKE, q_len, FAKE, None,
+                                       len(nodes) if n_nodes is None else n_nodes, FAKE, q_len, FAKE, None,
                                        ws, ws_bytes, None)
 
 
@@ -154,7 +154,6 @@ def test_tree_limits_and_workspace_size():
     lib = B.load()
     assert _tree([(0.9, 0, 4, 1)], nodes_dev=None, ws=FAKE * 256, ws_bytes=1 << 40) == B.APE_ERR_INVALID_ARG
     assert _tree([(0.9, 0, 4, 1)], req=_req(n_chunks=0, total_ctx_len=0)) == B.APE_ERR_INVALID_ARG       # a tree needs contexts
-    assert _tree([(0.9, 0, 4, 1)], max_chunk_len=-1) == B.APE_ERR_INVALID_ARG
     assert _tree([(0.9, 0, 4, 1)], req=_req(n_chunks=4, total_ctx_len=200, self_len=3)) == B.APE_ERR_INVALID_ARG
     # a chain deeper than the supported number of levels
     depth = B.APE_TREE_MAX_DEPTH + 1
@@ -166,15 +165,18 @@ def test_tree_limits_and_workspace_size():
     too_many = [(1.0, 1, B.APE_TREE_MAX_NODES, 0)] + [(0.9, 0, 1, 1)] * B.APE_TREE_MAX_NODES
     assert _tree(too_many) == B.APE_ERR_UNSUPPORTED
     sh = B.make_shape(32, 8, 128, B.APE_BF16)
-    w1 = B.tree_workspace_bytes(sh, 64, 2048, 256)
+    w1 = B.tree_workspace_bytes(sh, 131072, 65, 256)
     assert w1 > 0 and w1 % 256 == 0
-    # one split per context at least, plus the prefix+self block: 65 partial results of 256*32 units
+    # one split per context node at least, plus the prefix+self block: 65 partial results of 256*32 units
     assert w1 >= 65 * 256 * 32 * (128 + 1) * 4
-    assert B.tree_workspace_bytes(sh, 0, 2048, 256) == 0
-    assert B.tree_workspace_bytes(sh, B.APE_TREE_MAX_CONTEXTS + 1, 16, 1) == 0
-    assert B.tree_workspace_bytes(sh, 2, 32768, 1) > B.tree_workspace_bytes(sh, 2, 512, 1)   # long contexts are cut further
-    assert B.tree_workspace_bytes(sh, 4, 64, 8) < (1 << 24)
-    assert _tree([(0.9, 0, 4, 1)], ws=FAKE * 256, ws_bytes=B.tree_workspace_bytes(sh, 4, 64, 8) - 1) == B.APE_ERR_WORKSPACE
+    assert B.tree_workspace_bytes(sh, 131072, 0, 256) == 0
+    assert B.tree_workspace_bytes(sh, 131072, B.APE_TREE_MAX_NODES + 1, 1) == 0
+    assert B.tree_workspace_bytes(sh, -1, 4, 1) == 0
+    # a one-node tree needs about what the flat entry point needs
+    flat = B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256)
+    assert B.tree_workspace_bytes(sh, 131072, 1, 256) <= flat
+    assert B.tree_workspace_bytes(sh, 200, 1, 8) < (1 << 22)
+    assert _tree([(0.9, 0, 4, 1)], ws=FAKE * 256, ws_bytes=B.tree_workspace_bytes(sh, 200, 1, 8) - 1) == B.APE_ERR_WORKSPACE
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

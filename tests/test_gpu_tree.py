@@ -13,8 +13,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _check_tree(spec, r, h, nodes, q_len, self_len, generic=False, what="", max_chunk_len=None):
-    out, lse = H.run_tree(spec, r, nodes, q_len, self_len, generic=generic, max_chunk_len=max_chunk_len)
+def _check_tree(spec, r, h, nodes, q_len, self_len, generic=False, what=""):
+    out, lse = H.run_tree(spec, r, nodes, q_len, self_len, generic=generic)
     ref, ref_lse = H.oracle_tree(h, q_len, self_len, r.temperature, nodes)
     H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, spec.dtype, what + " tree out")
     got_lse = H.f64(lse).T.reshape(-1)
@@ -61,9 +61,9 @@ def test_fp32_ragged_contexts_empty_context_and_deep_tree():
     # a chain of single-child nodes above one node that holds everything (16 levels)
     chain = [(0.97, i + 1, 1, False) for i in range(B.APE_TREE_MAX_DEPTH - 1)] + [(0.9, 0, 7, True)]
     _check_tree(spec, r, h, chain, spec.q_len, spec.q_len, what="chain")
-    # the hint about the context length may be too small: every context is still read to its end
-    _check_tree(spec, r, h, W.tree_per_context(7, 0.8), spec.q_len, spec.q_len, what="low hint", max_chunk_len=16)
-    _check_tree(spec, r, h, W.tree_per_context(7, 0.8), spec.q_len, spec.q_len, what="zero hint", max_chunk_len=0)
+    # the subtrees in another order than the chunk table
+    swapped = [(0.9, 1, 3, False), (0.8, 5, 2, True), (0.7, 0, 2, True), (0.85, 2, 3, True)]
+    _check_tree(spec, r, h, swapped, spec.q_len, spec.q_len, what="groups out of table order")
 
 
 def test_fp32_wide_levels():
@@ -86,6 +86,7 @@ SMALL = [
     dict(chunk_lens=(257, 255, 3), q_len=96, prefix_len=32, n_q_heads=8, n_kv_heads=8),
     dict(chunk_lens=(200, 90, 64), q_len=40, prefix_len=5, n_q_heads=16, n_kv_heads=2),
     dict(chunk_lens=(3000, 2500), q_len=130, prefix_len=32, k_scale=1.0),      # few long contexts: several splits each
+    dict(chunk_lens=(700, 5, 1200, 64, 900, 33, 2048, 1), q_len=17, prefix_len=32),   # very unequal groups
 ]
 
 
