@@ -5,7 +5,9 @@ Usage: ``python -m paper_2502_05431_amd.build`` (cross-compiles without a GPU).
 from __future__ import annotations
 
 import glob
+import json
 import os
+import re
 import subprocess
 import sys
 
@@ -13,6 +15,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libape_hip.so")
+RESOURCES = os.path.join(PKG, "_build", "kernel_resources.json")
 
 # -packed-fp32-ops off: packed fp32 VALU forms are not used on the test machines.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -33,6 +36,25 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+_REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|"
+                     r"LDS Size \[bytes/block\]|SGPRs): (\S+)")
+
+
+def parse_resources(compiler_output: str) -> dict:
+    """Per-kernel register, scratch and LDS use from hipcc's kernel-resource-usage remarks."""
+    res, cur = {}, None
+    for line in compiler_output.splitlines():
+        m = _REMARK.search(line)
+        if not m:
+            continue
+        key, val = m.group(1), m.group(2)
+        if key == "Function Name":
+            cur = res.setdefault(val, {})
+        elif cur is not None:
+            cur[key.split(" [")[0]] = int(val)
+    return res
+
+
 def build(verbose: bool = True, extra=()) -> str:
     objs = []
     procs = []
@@ -40,13 +62,16 @@ def build(verbose: bool = True, extra=()) -> str:
         obj = os.path.join(PKG, "_build", os.path.basename(src) + ".o")
         os.makedirs(os.path.dirname(obj), exist_ok=True)
         cmd = ["hipcc", *[f for f in HIPCC_FLAGS if f != "-shared"], *EXTRA_FLAGS.get(os.path.basename(src), []),
-               *extra, "-c", src, "-o", obj]
+               "-Rpass-analysis=kernel-resource-usage", *extra, "-c", src, "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False
+    resources = {}
     for src, p in procs:
         out, _ = p.communicate()
-        lines = [l for l in out.splitlines() if "packed-fp32-ops" not in l]
+        resources[os.path.basename(src)] = parse_resources(out)
+        lines = [l for l in out.splitlines() if "packed-fp32-ops" not in l and "-Rpass-analysis" not in l
+                 and "remark:" not in l]
         if p.returncode != 0:
             failed = True
         if verbose and lines:
@@ -56,6 +81,8 @@ def build(verbose: bool = True, extra=()) -> str:
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
     os.replace(tmp, LIB)
+    with open(RESOURCES, "w") as f:
+        json.dump(resources, f, indent=1, sort_keys=True)
     return LIB
 
 

@@ -673,18 +673,9 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
     if (split < a.n_ctx_splits) {
         long t0, t1;
         ctx_split_range(a, kv, split, t0, t1);
-        if (t0 >= t1) {
-            // An empty split (only a tree plan has them: slots past the splits in use).  Its
-            // LogSumExp says so and the merge never reads its values.  The whole workgroup
-            // leaves here, before any barrier or load.
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
-                const int tok = R / G, g = R % G;
-                if (tok < q_len && hi == 0) a.part_lse[(long)split * a.units_total + (long)tok * hq + hk * G + g] = -INFINITY;
-            }
-            return;
-        }
+        // An empty split is a slot past the splits a tree plan uses, which the merge never looks
+        // at: the whole workgroup leaves here, before any barrier or load.
+        if (t0 >= t1) return;
         walk.init_ctx(kv.cu, kv.k_chunks, kv.v_chunks, kv.n_chunks, (int)t0, (int)t1, stride_b, head_b);
         sc2 = inv_sqrt_d / kv.temperature * LOG2E;
     } else {

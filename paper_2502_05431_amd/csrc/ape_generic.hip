@@ -219,14 +219,24 @@ __device__ __forceinline__ void merge_group(const MergeArgs& a, long gunit, int 
             const float w_mine = s_mine < s1 ? expf(a.part_lse[(long)s_mine * a.units_total + gunit] - m) : 0.f;   // 0 for empty splits
             z += w_mine;
             const int cnt = min(kWave, s1 - c0);
-            for (int i = wave; i < cnt; i += kMergeWaves) {
-                const float w = __shfl(w_mine, i);
-                const float* o = a.part_o + ((long)(c0 + i) * a.units_total + gunit) * d;
+            constexpr int UN = 4;                                       // rows in flight per wavefront
+            for (int i = wave; i < cnt; i += UN * kMergeWaves) {
+                float w[UN], v[UN][kMaxDimRegs];
 #pragma unroll
-                for (int r = 0; r < kMaxDimRegs; ++r) {
-                    const int c = lane + kWave * r;
-                    if (c < d) acc[r] = fmaf(w, o[c], acc[r]);
+                for (int u = 0; u < UN; ++u) {
+                    const int ii = i + u * kMergeWaves;
+                    w[u] = ii < cnt ? __shfl(w_mine, min(ii, kWave - 1)) : 0.f;
+                    const float* o = a.part_o + ((long)(c0 + min(ii, cnt - 1)) * a.units_total + gunit) * d;
+#pragma unroll
+                    for (int r = 0; r < kMaxDimRegs; ++r) {
+                        const int c = lane + kWave * r;
+                        v[u][r] = c < d ? o[c] : 0.f;
+                    }
                 }
+#pragma unroll
+                for (int u = 0; u < UN; ++u)
+#pragma unroll
+                    for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = fmaf(w[u], v[u][r], acc[r]);
             }
         }
         z = wave_sum(z);
@@ -473,16 +483,31 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const T
         if (s < n_used) w_mine = expf(split_v[s]);                 // exp(-inf) = 0
         else if (s == n_used) w_mine = expf(l_other - ltot);
         const int cnt = min(kWave, n_used + 1 - s0);
-        for (int i = wave; i < cnt; i += kMergeWaves) {
-            const float w = __shfl(w_mine, i);
-            if (w == 0.f) continue;                                // never read what an empty split left
-            const int sp = s0 + i < n_used ? s0 + i : a.max_splits;
-            const float* o = a.part_o + ((long)sp * U + unit) * d;
+        // four rows in flight per wavefront; a row of weight zero (an empty split, a slot past the
+        // end) is replaced by the prefix+self row, which always holds finite values
+        constexpr int UN = 4;
+        for (int i = wave; i < cnt; i += UN * kMergeWaves) {
+            float w[UN];
+            const float* o[UN];
 #pragma unroll
-            for (int r = 0; r < kMaxDimRegs; ++r) {
-                const int c = lane + kWave * r;
-                if (c < d) acc[r] = fmaf(w, o[c], acc[r]);
+            for (int u = 0; u < UN; ++u) {
+                const int ii = i + u * kMergeWaves;
+                w[u] = ii < cnt ? __shfl(w_mine, min(ii, kWave - 1)) : 0.f;
+                const int sp = (w[u] != 0.f && s0 + ii < n_used) ? s0 + ii : a.max_splits;
+                o[u] = a.part_o + ((long)sp * U + unit) * d;
             }
+            float v[UN][kMaxDimRegs];
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+#pragma unroll
+                for (int r = 0; r < kMaxDimRegs; ++r) {
+                    const int c = lane + kWave * r;
+                    v[u][r] = c < d ? o[u][c] : 0.f;
+                }
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+#pragma unroll
+                for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = fmaf(w[u], v[u][r], acc[r]);
         }
     }
 #pragma unroll
