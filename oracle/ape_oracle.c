@@ -23,6 +23,10 @@
  *                                contexts (Appendix C.5): every node merges
  *                                its children by a softmax over their
  *                                LogSumExps and multiplies its own by S_n.
+ *   - ape_oracle_rope            rotary position embedding with the positions
+ *                                re-used across contexts (Section 1), the step
+ *                                that produces the rotated Q/K the attention
+ *                                routines read.
  *   - ape_oracle_encode          Section 2.2 "Pre-caching Contexts" with the
  *                                shared prefix of Section 4.1: every context
  *                                row attends causally to the prefix and to
@@ -481,4 +485,45 @@ int ape_oracle_encode(int n_q_heads, int n_kv_heads, int d,
         free(x);
     }
     return bad ? -1 : 0;
+}
+
+/*
+ * Rotary position embedding with re-used positions (Section 1 "Re-using
+ * Positions": every context is placed in the same range of positions;
+ * Section 2.3 names relative position embeddings, the rotary one being what
+ * the Llama-3 models of the paper use).
+ *
+ * x is packed [M, heads, d] over n_chunks segments given by cu_chunk_lens;
+ * the token at index j of ANY segment has position position_offset + j.
+ * Rotation of the published rotary embedding in its half-split pairing:
+ * dims (c, c + d/2), c = 0 .. d/2-1, are one plane, turned by the angle
+ * pos * base^(-2c/d):
+ *   y[c]       = x[c] cos(a) - x[c + d/2] sin(a)
+ *   y[c + d/2] = x[c + d/2] cos(a) + x[c] sin(a)
+ * Everything in double.  Returns 0, or -1 on bad arguments (d must be even).
+ */
+int ape_oracle_rope(const float *x, int heads, int d,
+                    const int *cu_chunk_lens, int n_chunks,
+                    long position_offset, double base, double *y)
+{
+    if (heads <= 0 || d <= 0 || (d & 1) || n_chunks < 0 || !(base > 0.0)) return -1;
+    const int half = d / 2;
+    for (int i = 0; i < n_chunks; ++i) {
+        if (cu_chunk_lens[i + 1] < cu_chunk_lens[i]) return -1;
+        for (long t = cu_chunk_lens[i]; t < cu_chunk_lens[i + 1]; ++t) {
+            const double pos = (double)(position_offset + (t - cu_chunk_lens[i]));
+            for (int h = 0; h < heads; ++h) {
+                const float *xr = x + (t * heads + h) * (long)d;
+                double *yr = y + (t * heads + h) * (long)d;
+                for (int c = 0; c < half; ++c) {
+                    const double a = pos * pow(base, -2.0 * (double)c / (double)d);
+                    const double cs = cos(a), sn = sin(a);
+                    const double x1 = (double)xr[c], x2 = (double)xr[c + half];
+                    yr[c] = x1 * cs - x2 * sn;
+                    yr[c + half] = x2 * cs + x1 * sn;
+                }
+            }
+        }
+    }
+    return 0;
 }

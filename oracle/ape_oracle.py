@@ -53,6 +53,8 @@ def _load():
         lib.ape_oracle_encode.argtypes = [i, i, i, fp, fp, i, fp, fp, fp, ip, i, ip, ip, l, dp, dp]
         lib.ape_oracle_encode.restype = i
         lib.ape_oracle_num_threads.restype = i
+        lib.ape_oracle_rope.argtypes = [fp, i, i, ip, i, l, d, dp]
+        lib.ape_oracle_rope.restype = i
         _lib = lib
     return _lib
 
@@ -194,3 +196,20 @@ def encode(q_ctx, k_prefix, v_prefix, k_ctx, v_ctx, chunk_lens, pairs=None):
     if rc != 0:
         raise ValueError("ape_oracle: bad arguments")
     return out, lse
+
+
+def rope(x, chunk_lens, position_offset: int, base: float):
+    """Rotary position embedding of packed segments ``x`` [sum(chunk_lens), heads, d]: token j of
+    every segment sits at position ``position_offset + j`` (positions re-used across contexts,
+    Section 1).  Half-split pairing.  Returns float64 [M, heads, d]."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.ndim == 3
+    cu = _cu(chunk_lens)
+    assert cu[-1] == x.shape[0]
+    y = np.empty(x.shape, dtype=np.float64)
+    rc = lib.ape_oracle_rope(_ptr(x), x.shape[1], x.shape[2], _ptr(cu), len(chunk_lens),
+                             int(position_offset), float(base), _ptr(y))
+    if rc != 0:
+        raise ValueError("ape_oracle: bad arguments")
+    return y
