@@ -11,6 +11,8 @@
  *   ape_attention_decode   query's own causal KV with the refined attention of
  *                          Section 4.4 ("Eq.5"): context scores use 1/(T sqrt d),
  *                          the pooled context partition sum is raised to S.
+ *   ape_rope_write_cache   rotary embedding with positions re-used across contexts
+ *                          (Section 1) fused with the KV-cache write, in front of the above.
  *   ape_attention_tree     the same over a tree of contexts with a scaling factor per
  *                          node (Appendix C.2 and C.5); S per context is one such tree.
  *
@@ -205,6 +207,30 @@ int ape_attention_tree(const ape_shape *shape, const ape_request *req,
                        const ape_tree_node *nodes_host, const ape_tree_node *nodes_dev, int32_t n_nodes,
                        const void *q, int32_t q_len, void *out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Rotary position embedding with positions re-used across contexts (Section 1, "Re-using
+ * Positions": every context occupies the same range of positions), fused with the write of the
+ * KV cache -- the step in front of ape_encode_chunks and of the query-time calls.
+ * The packed rows [M, heads, d] are n_chunks segments given by cu_chunk_lens; token j of EVERY
+ * segment has position position_offset + j.  Rotation: the published rotary embedding in
+ * half-split pairing, dims (c, c + d/2) turn by pos * rope_base^(-2c/d); fp32 arithmetic on
+ * angles reduced in fp64.  (Prefix: one segment at offset 0.  Contexts: offset prefix_len.
+ * Query and generated tokens: one segment at offset prefix_len + max_i l_i.)
+ *
+ *   q_raw, q_rot   DEVICE packed [M, n_q_heads, d], or both NULL; q_rot may be q_raw (in place)
+ *   k_raw          DEVICE packed [M, n_kv_heads, d] or NULL: rotated keys of segment i go to
+ *   k_cache        DEVICE array [n_chunks] of DEVICE pointers, k_cache[i]: [l_i, n_kv_heads, d]
+ *                  (views into one packed buffer are fine: that buffer then feeds ape_encode_chunks)
+ *   v_raw, v_cache same for the values, which are copied unchanged; or both NULL
+ *   cu_chunk_lens_host / _dev  HOST and DEVICE [n_chunks + 1] prefix sums of the segment lengths
+ * head_dim must be even (it is a multiple of 8).  No workspace.
+ */
+int ape_rope_write_cache(const ape_shape *shape,
+                         const void *q_raw, const void *k_raw, const void *v_raw,
+                         const int32_t *cu_chunk_lens_host, const int32_t *cu_chunk_lens_dev, int32_t n_chunks,
+                         int32_t position_offset, float rope_base,
+                         void *q_rot, void *const *k_cache, void *const *v_cache, void *stream);
 
 /* Text for a status code (static storage). */
 const char *ape_status_string(int status);

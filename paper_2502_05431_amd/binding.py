@@ -24,7 +24,7 @@ APE_DTYPE_FLAG_GENERIC = 0x100
 APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
 
 EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
-           "ape_tree_workspace_bytes", "ape_attention_tree",
+           "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
            "ape_status_string", "ape_last_error", "ape_version")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
 
@@ -83,6 +83,9 @@ def load() -> ctypes.CDLL:
         lib.ape_attention_tree.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, vp, i32,
                                            vp, i32, vp, vp, vp, sz, vp]
         lib.ape_attention_tree.restype = ctypes.c_int
+        lib.ape_rope_write_cache.argtypes = [ctypes.POINTER(ApeShape), vp, vp, vp, vp, vp, i32, i32, ctypes.c_float,
+                                             vp, vp, vp, vp]
+        lib.ape_rope_write_cache.restype = ctypes.c_int
         lib.ape_status_string.argtypes = [ctypes.c_int]
         lib.ape_status_string.restype = ctypes.c_char_p
         lib.ape_last_error.restype = ctypes.c_char_p
@@ -239,6 +242,19 @@ def attention_tree(shape: ApeShape, req: Request, tree: Tree, q: torch.Tensor, o
                                    _ptr(tree.dev), tree.n_nodes, _ptr(q), q.shape[0], _ptr(out),
                                    _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream))
+    _check(rc)
+
+
+def rope_write_cache(shape: ApeShape, q_raw, k_raw, v_raw, cu_chunk_lens: Sequence[int], cu_chunk_lens_dev,
+                     position_offset: int, rope_base: float, q_rot, k_cache_table, v_cache_table, stream=None):
+    """``ape_rope_write_cache``: packed raw rows [M, H, d]; ``k_cache_table`` / ``v_cache_table`` are int64
+    device tensors holding one device pointer per segment (or None)."""
+    n_chunks = len(cu_chunk_lens) - 1 if cu_chunk_lens is not None and len(cu_chunk_lens) else 0
+    cu_host = (ctypes.c_int32 * (n_chunks + 1))(*cu_chunk_lens) if n_chunks else None
+    rc = load().ape_rope_write_cache(ctypes.byref(shape), _ptr(q_raw), _ptr(k_raw), _ptr(v_raw),
+                                     ctypes.cast(cu_host, ctypes.c_void_p) if cu_host is not None else None,
+                                     _ptr(cu_chunk_lens_dev), n_chunks, position_offset, rope_base,
+                                     _ptr(q_rot), _ptr(k_cache_table), _ptr(v_cache_table), _stream(stream))
     _check(rc)
 
 

@@ -389,4 +389,33 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     return APE_OK;
 }
 
+int ape_rope_write_cache(const ape_shape* shape,
+                         const void* q_raw, const void* k_raw, const void* v_raw,
+                         const int32_t* cu_host, const int32_t* cu_dev, int32_t n_chunks,
+                         int32_t position_offset, float rope_base,
+                         void* q_rot, void* const* k_cache, void* const* v_cache, void* stream) {
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (n_chunks < 0) return fail(APE_ERR_INVALID_ARG, "n_chunks %d < 0", n_chunks);
+    if (position_offset < 0) return fail(APE_ERR_INVALID_ARG, "position_offset %d < 0", position_offset);
+    if (!(std::isfinite(rope_base) && rope_base > 0.f)) return fail(APE_ERR_INVALID_ARG, "rope_base must be finite and > 0");
+    if ((q_raw == nullptr) != (q_rot == nullptr)) return fail(APE_ERR_INVALID_ARG, "q_raw and q_rot must both be given or both be NULL");
+    if ((k_raw == nullptr) != (k_cache == nullptr)) return fail(APE_ERR_INVALID_ARG, "k_raw and k_cache must both be given or both be NULL");
+    if ((v_raw == nullptr) != (v_cache == nullptr)) return fail(APE_ERR_INVALID_ARG, "v_raw and v_cache must both be given or both be NULL");
+    if (n_chunks == 0) return APE_OK;
+    if (!cu_host || !cu_dev) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens (host and device) are required");
+    if (cu_host[0] != 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens[0] must be 0");
+    for (int i = 0; i < n_chunks; ++i)
+        if (cu_host[i + 1] < cu_host[i]) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens is not non-decreasing at %d", i);
+    RopeArgs a{};
+    a.q_raw = q_raw; a.k_raw = k_raw; a.v_raw = v_raw; a.q_rot = q_rot; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.cu = cu_dev; a.n_chunks = n_chunks; a.total_rows = cu_host[n_chunks];
+    a.n_q_heads = si.hq; a.n_kv_heads = si.hkv; a.head_dim = si.d; a.position_offset = position_offset;
+    for (int c = 0; c < si.d / 2; ++c) a.inv_freq[c] = std::pow((double)rope_base, -2.0 * c / si.d);
+    hipError_t he = launch_rope_write(a, si.dtype, (hipStream_t)stream);
+    if (he != hipSuccess) return fail(APE_ERR_DEVICE, "rope kernel: %s", hipGetErrorString(he));
+    return APE_OK;
+}
+
 }  // extern "C"

@@ -130,6 +130,24 @@ struct EncodeArgs {
     int32_t head_dim;
 };
 
+// Kernel-argument block of the rotary embedding + cache write.
+struct RopeArgs {
+    const void* q_raw;          // packed [M, Hq, d] or NULL
+    const void* k_raw;          // packed [M, Hkv, d] or NULL
+    const void* v_raw;          // packed [M, Hkv, d] or NULL
+    void* q_rot;                // packed [M, Hq, d]
+    void* const* k_cache;       // device [n_chunks] of device pointers [l_i, Hkv, d]
+    void* const* v_cache;
+    const int32_t* cu;          // device [n_chunks + 1]
+    int32_t n_chunks;
+    int32_t total_rows;         // M
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;           // even, <= 256
+    int32_t position_offset;    // position of the first token of every segment
+    double inv_freq[128];       // base^(-2c/d), c < d/2, computed on the host in double
+};
+
 #if defined(__HIPCC__)
 // Field access into the kernel-argument segment.  A by-value argument struct that is indexed
 // with a run-time index would be copied to scratch as a whole; reading it through the
@@ -202,6 +220,7 @@ struct QueryPlan {
 hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s);
 hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_rope_write(const RopeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s);
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s);     // bf16, d = 128

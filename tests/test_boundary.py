@@ -179,6 +179,31 @@ def test_tree_limits_and_workspace_size():
     assert _tree([(0.9, 0, 4, 1)], ws=FAKE * 256, ws_bytes=B.tree_workspace_bytes(sh, 200, 1, 8) - 1) == B.APE_ERR_WORKSPACE
 
 
+def test_rope_argument_errors():
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    cu = (ctypes.c_int32 * 3)(0, 5, 9)
+    cuh = ctypes.cast(cu, ctypes.c_void_p)
+
+    def rope(cu_host=cuh, cu_dev=FAKE, n=2, off=32, base=500000.0, q=FAKE, k=FAKE, v=FAKE, qo=FAKE, kc=FAKE, vc=FAKE, shape=sh):
+        return lib.ape_rope_write_cache(ctypes.byref(shape), q, k, v, cu_host, cu_dev, n, off, base, qo, kc, vc, None)
+    assert rope(off=-1) == B.APE_ERR_INVALID_ARG
+    assert rope(base=0.0) == B.APE_ERR_INVALID_ARG
+    assert rope(base=float("inf")) == B.APE_ERR_INVALID_ARG
+    assert rope(qo=None) == B.APE_ERR_INVALID_ARG            # q_raw without q_rot
+    assert rope(k=None) == B.APE_ERR_INVALID_ARG             # k_cache without k_raw
+    assert rope(vc=None) == B.APE_ERR_INVALID_ARG
+    assert rope(cu_host=None) == B.APE_ERR_INVALID_ARG
+    assert rope(cu_dev=None) == B.APE_ERR_INVALID_ARG
+    assert rope(n=-1) == B.APE_ERR_INVALID_ARG
+    bad = (ctypes.c_int32 * 3)(0, 5, 3)
+    assert rope(cu_host=ctypes.cast(bad, ctypes.c_void_p)) == B.APE_ERR_INVALID_ARG
+    assert rope(shape=B.make_shape(32, 8, 100, B.APE_BF16)) == B.APE_ERR_UNSUPPORTED
+    assert rope(n=0, cu_host=None, cu_dev=None) == B.APE_OK    # nothing to do, nothing launched
+    empty = (ctypes.c_int32 * 3)(0, 0, 0)
+    assert rope(cu_host=ctypes.cast(empty, ctypes.c_void_p)) == B.APE_OK
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
