@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--tree-variants", action="store_true",
                     help="also time the query prefill and one decode step of the same 128K cache through the tree "
                          "entry point: one pooled node, a scaling factor per context, and a two-level tree")
+    ap.add_argument("--rope-write", action="store_true",
+                    help="also time the rotary embedding + KV-cache write in front of the encode (raw Q/K/V of the "
+                         "same 64 x 2048 contexts), a bandwidth-bound kernel")
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time torch's bf16 GEMM (the vendor library) on zero and on random operands: context "
                          "for the MFMA roofline, which on this chip depends on the operand data (power limit)")
@@ -217,6 +220,32 @@ def main():
                             "node are attended in splits of their own and the tree merge replaces the two-group merge" % ms_pre)
         del ws_t
 
+    rope_res = None
+    if args.rope_write:
+        q_raw = torch.empty_like(r.q_ctx).normal_()
+        k_raw = torch.empty_like(r.k_ctx).normal_()
+        v_raw = torch.empty_like(r.v_ctx).normal_()
+        q_rot, k_c, v_c = torch.empty_like(q_raw), torch.empty_like(k_raw), torch.empty_like(v_raw)
+        kt = torch.tensor([k_c[cu[i]:].data_ptr() for i in range(len(r.chunk_lens))], dtype=torch.int64, device=dev)
+        vt = torch.tensor([v_c[cu[i]:].data_ptr() for i in range(len(r.chunk_lens))], dtype=torch.int64, device=dev)
+
+        def rope_call():
+            B.rope_write_cache(shape, q_raw, k_raw, v_raw, cu, cu_dev, spec.prefix_len, 500000.0, q_rot, kt, vt)
+        for _ in range(2):
+            rope_call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            rope_call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_rope = e0.elapsed_time(e1) / 10
+        by_rope = 2.0 * (q_raw.numel() + k_raw.numel() + v_raw.numel()) * 2          # every element read once, written once
+        rope_res = {"ms": ms_rope, "gbs": by_rope / (ms_rope * 1e-3) / 1e9, "frac_hbm_peak": by_rope / (ms_rope * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                    "bytes": by_rope, "note": "131072 tokens x (32 q + 8 k + 8 v heads) x 128, bf16, read once and written once"}
+        del q_raw, k_raw, v_raw, q_rot, k_c, v_c
+
     gemm_ref = None
     if args.gemm_reference:
         n = 8192
@@ -325,6 +354,8 @@ def main():
         line["sequential_comparator"] = seq_cmp
     if tree_var is not None:
         line["tree_variants"] = tree_var
+    if rope_res is not None:
+        line["rope_write_cache"] = rope_res
     print(json.dumps(line))
 
 
