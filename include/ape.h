@@ -91,7 +91,7 @@ typedef struct {
  * Bytes of caller-provided DEVICE workspace an operation needs (0 is possible).
  * An upper bound that depends only on the arguments given, never on the data.
  *   op       ape_op
- *   batch    requests (decode); 1 otherwise
+ *   batch    requests (decode, batched prefill); 1 for ape_attention_prefill; ignored for encode
  *   q_len    query rows per request (prefill); 1 for decode; ignored for encode
  * Returns 0 on invalid arguments as well; the entry points re-validate.
  */
@@ -136,6 +136,20 @@ int ape_encode_chunks(const ape_shape *shape,
 int ape_attention_prefill(const ape_shape *shape, const ape_request *req,
                           const void *q, int32_t q_len, void *out, float *lse_out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Query prefill of a batch of independent requests with the same number of query rows (the
+ * serving setting of Section 5.4 runs several queries at once): ape_attention_prefill for every
+ * request, in one launch.  Each request has its own prefix, contexts, self KV, T and S.
+ *
+ *   reqs      HOST array [batch]
+ *   q, out    DEVICE [batch, q_len, n_q_heads, d]
+ *   lse_out   DEVICE fp32 [batch, n_q_heads, q_len] or NULL
+ *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_PREFILL, shape, batch, q_len), 256-byte aligned
+ */
+int ape_attention_prefill_batch(const ape_shape *shape, const ape_request *reqs, int32_t batch,
+                                const void *q, int32_t q_len, void *out, float *lse_out,
+                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * One decode step for a batch of independent requests: Eq.5 with a single query row per

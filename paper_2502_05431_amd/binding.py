@@ -24,6 +24,7 @@ APE_DTYPE_FLAG_GENERIC = 0x100
 APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
 
 EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
+           "ape_attention_prefill_batch",
            "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
            "ape_status_string", "ape_last_error", "ape_version")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
@@ -75,6 +76,9 @@ def load() -> ctypes.CDLL:
         lib.ape_attention_prefill.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, i32, vp, vp,
                                               vp, sz, vp]
         lib.ape_attention_prefill.restype = ctypes.c_int
+        lib.ape_attention_prefill_batch.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), i32, vp, i32, vp, vp,
+                                                    vp, sz, vp]
+        lib.ape_attention_prefill_batch.restype = ctypes.c_int
         lib.ape_attention_decode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), i32, vp, vp, vp,
                                              vp, sz, vp]
         lib.ape_attention_decode.restype = ctypes.c_int
@@ -200,6 +204,17 @@ def attention_prefill(shape: ApeShape, req: Request, q: torch.Tensor, out: torch
     r = req.as_struct(self_len)
     rc = load().ape_attention_prefill(ctypes.byref(shape), ctypes.byref(r), _ptr(q), q.shape[0], _ptr(out), _ptr(lse_out),
                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc)
+
+
+def attention_prefill_batch(shape: ApeShape, reqs: Sequence[Request], q: torch.Tensor, out: torch.Tensor,
+                            lse_out: Optional[torch.Tensor], workspace: torch.Tensor, stream=None,
+                            self_lens: Optional[Sequence[int]] = None):
+    """``ape_attention_prefill_batch``: q/out [batch, q_len, Hq, d]; lse_out fp32 [batch, Hq, q_len] or None."""
+    n = len(reqs)
+    arr = (ApeRequest * n)(*[r.as_struct(None if self_lens is None else self_lens[i]) for i, r in enumerate(reqs)])
+    rc = load().ape_attention_prefill_batch(ctypes.byref(shape), arr, n, _ptr(q), q.shape[1], _ptr(out), _ptr(lse_out),
+                                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc)
 
 

@@ -192,8 +192,7 @@ size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_
     if (check_shape(shape, &si) != APE_OK) return 0;
     if (op == APE_OP_ENCODE) return 0;
     if (op == APE_OP_DECODE) q_len = 1;
-    else if (op == APE_OP_PREFILL) batch = 1;
-    else return 0;
+    else if (op != APE_OP_PREFILL) return 0;
     if (batch < 1 || q_len < 1) return 0;
     // worst case over every context length: kMaxSplits context splits + 1
     return partial_bytes((long)batch * q_len * si.hq, kMaxSplits + 1, si.d);
@@ -269,7 +268,7 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         plan = plan_query(base, max_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
     } else {
         const int rows = q_len * si.group;
-        const int base = si.mfma ? si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
+        const int base = si.mfma ? batch * si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
         plan = plan_query(base, max_ctx, si.mfma ? 256 : 256, si.mfma ? 256 : 1024);
     }
     const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
@@ -283,7 +282,12 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         const int nb = batch - b0 < kMaxReqPerLaunch ? batch - b0 : kMaxReqPerLaunch;
         QueryArgs a{};
         MergeArgs m{};
-        for (int i = 0; i < nb; ++i) { a.req[i] = to_view(&reqs[b0 + i]); m.scale[i] = reqs[b0 + i].scale; }
+        for (int i = 0; i < nb; ++i) {
+            a.req[i] = to_view(&reqs[b0 + i]);
+            m.scale[i] = reqs[b0 + i].scale;
+            m.total_ctx[i] = a.req[i].total_ctx;
+        }
+        m.ctx_split_len = plan.ctx_split_len;
         a.q = (const char*)q + (size_t)b0 * q_len * si.hq * si.d * (si.dtype == APE_F32 ? 4 : 2);
         a.part_o = part_o; a.part_lse = part_lse;
         a.n_req = nb; a.q_len = q_len; a.n_q_heads = si.hq; a.n_kv_heads = si.hkv; a.head_dim = si.d;
@@ -313,6 +317,18 @@ int ape_attention_prefill(const ape_shape* shape, const ape_request* req,
     if (!req || !q || !out) return fail(APE_ERR_INVALID_ARG, "req, q and out must not be NULL");
     if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
     return run_query(si, req, 1, q_len, false, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int ape_attention_prefill_batch(const ape_shape* shape, const ape_request* reqs, int32_t batch,
+                                const void* q, int32_t q_len, void* out, float* lse_out,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (!reqs || !q || !out) return fail(APE_ERR_INVALID_ARG, "reqs, q and out must not be NULL");
+    if (batch < 1) return fail(APE_ERR_INVALID_ARG, "batch %d < 1", batch);
+    if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
+    return run_query(si, reqs, batch, q_len, false, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int ape_attention_decode(const ape_shape* shape, const ape_request* reqs, int32_t batch,

@@ -658,7 +658,8 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
         if (team >= a.n_kv_heads) return;
         split = a.n_ctx_splits; hk = team;
     }
-    const KvView& kv = a.req[0];
+    const int rq = blockIdx.y;                           // request
+    const KvView kv = load_view<QueryArgs>(rq);
     const int hq = a.n_q_heads, q_len = a.q_len;
     const long stride_b = (long)a.n_kv_heads * ROWB, head_b = (long)hk * ROWB;
 
@@ -673,8 +674,9 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
     if (split < a.n_ctx_splits) {
         long t0, t1;
         ctx_split_range(a, kv, split, t0, t1);
-        // An empty split is a slot past the splits a tree plan uses, which the merge never looks
-        // at: the whole workgroup leaves here, before any barrier or load.
+        // An empty split (a slot past the splits a tree plan uses; in a batch, a split past the end
+        // of a request's context) is one the merge never looks at: the whole workgroup leaves
+        // here, before any barrier or load.
         if (t0 >= t1) return;
         walk.init_ctx(kv.cu, kv.k_chunks, kv.v_chunks, kv.n_chunks, (int)t0, (int)t1, stride_b, head_b);
         sc2 = inv_sqrt_d / kv.temperature * LOG2E;
@@ -697,7 +699,7 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
         const int tok = R / G, g = R % G;
         const bool valid = tok < q_len;
         lim[rb] = (valid ? tok : q_len - 1) + causal_off;
-        const char* qp = (const char*)a.q + ((long)tok * hq + hk * G + g) * ROWB + hi * 16;
+        const char* qp = (const char*)a.q + (((long)rq * q_len + tok) * hq + hk * G + g) * ROWB + hi * 16;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             u32x4 w = {0, 0, 0, 0};
@@ -718,7 +720,7 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
         const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
         if (tok >= q_len) continue;
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        const long unit = (long)tok * hq + hk * G + g;
+        const long unit = ((long)(a.req_base + rq) * q_len + tok) * hq + hk * G + g;
         const long slot = (long)split * a.units_total + unit;
         float* o = a.part_o + slot * D;
 #pragma unroll
@@ -810,7 +812,7 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
 }
 
 template <int RB, int G>
-hipError_t launch_prefill_t(const QueryArgs& a, unsigned grid, int n_qtiles, hipStream_t s) {
+hipError_t launch_prefill_t(const QueryArgs& a, dim3 grid, int n_qtiles, hipStream_t s) {
     hipError_t e = hipFuncSetAttribute((const void*)flash_prefill_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
     if (e != hipSuccess) return e;
     flash_prefill_kernel<RB, G><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles);
@@ -826,7 +828,7 @@ hipError_t launch_encode_t(const EncodeArgs& a, unsigned grid, int n_qtiles, hip
 }
 
 template <int RB>
-hipError_t launch_prefill_g(int group, const QueryArgs& a, unsigned grid, int n_qtiles, hipStream_t s) {
+hipError_t launch_prefill_g(int group, const QueryArgs& a, dim3 grid, int n_qtiles, hipStream_t s) {
     switch (group) {
         case 1: return launch_prefill_t<RB, 1>(a, grid, n_qtiles, s);
         case 2: return launch_prefill_t<RB, 2>(a, grid, n_qtiles, s);
@@ -855,7 +857,8 @@ hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s) {
     const int bm = flash_block_rows(rows);
     const int n_qtiles = (rows + bm - 1) / bm;
     const int ctx_teams = a.n_ctx_splits * a.n_kv_heads;
-    const unsigned grid = (unsigned)(((ctx_teams + 7) / 8 * 8 + (a.n_kv_heads + 7) / 8 * 8) * n_qtiles);
+    // x is a multiple of 8, so the workgroups of every request start on the same XCD phase
+    const dim3 grid((unsigned)(((ctx_teams + 7) / 8 * 8 + (a.n_kv_heads + 7) / 8 * 8) * n_qtiles), (unsigned)a.n_req);
     return bm == 256 ? launch_prefill_g<2>(group, a, grid, n_qtiles, s) : launch_prefill_g<1>(group, a, grid, n_qtiles, s);
 }
 

@@ -258,7 +258,11 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeA
 #pragma unroll
     for (int r = 0; r < kMaxDimRegs; ++r) { acc_c[r] = 0.f; acc_o[r] = 0.f; }
     float mc, zc, mo, zo;
-    merge_group(a, gunit, 0, a.n_ctx_splits, wave, lane, acc_c, mc, zc);                  // context group
+    // context group: only the splits that hold tokens of THIS request (a shorter context in a
+    // batch leaves the trailing splits untouched)
+    const int tc = kernarg<MergeArgs>()->total_ctx[rq];
+    const int n_ctx = min(a.n_ctx_splits, (tc + a.ctx_split_len - 1) / a.ctx_split_len);
+    merge_group(a, gunit, 0, n_ctx, wave, lane, acc_c, mc, zc);
     merge_group(a, gunit, a.n_ctx_splits, a.n_splits_total, wave, lane, acc_o, mo, zo);   // prefix + self: never empty
 #pragma unroll
     for (int r = 0; r < kMaxDimRegs; ++r) {
@@ -292,9 +296,9 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeA
     }
     if (a.lse_out && lane == 0) {
         const float lse = mx + logf(ec + eo);
-        if (a.lse_head_major) {
+        if (a.lse_head_major) {                                     // [request, head, row]
             const int h = unit % hq, row = (unit / hq) % a.q_len;
-            a.lse_out[(long)h * a.q_len + row] = lse;
+            a.lse_out[((long)(a.req_base + rq) * hq + h) * a.q_len + row] = lse;
         } else {
             a.lse_out[gunit] = lse;
         }

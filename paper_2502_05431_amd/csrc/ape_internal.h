@@ -56,6 +56,8 @@ struct MergeArgs {
     void* out;                  // [units][d], dtype
     float* lse_out;             // NULL or fp32
     float scale[kMaxReqPerLaunch];
+    int32_t total_ctx[kMaxReqPerLaunch];   // context tokens of each request: splits past them were never written
+    int32_t ctx_split_len;
     int32_t n_req;
     int32_t q_len;
     int32_t n_q_heads;

@@ -40,9 +40,9 @@ def test_workspace_bytes():
     p = B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256)
     assert d > 0 and p > d
     assert d % 256 == 0 and p % 256 == 0
-    # decode ignores q_len, prefill ignores batch
+    # decode ignores q_len; a batched prefill needs room for every request
     assert B.workspace_bytes(B.APE_OP_DECODE, sh, 32, 77) == d
-    assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 9, 256) == p
+    assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 4, 256) == 4 * p
     bad = B.make_shape(32, 7, 128, B.APE_BF16)
     assert B.workspace_bytes(B.APE_OP_DECODE, bad, 1, 1) == 0
     assert B.workspace_bytes(99, sh, 1, 1) == 0
@@ -177,6 +177,18 @@ def test_tree_limits_and_workspace_size():
     assert B.tree_workspace_bytes(sh, 131072, 1, 256) <= flat
     assert B.tree_workspace_bytes(sh, 200, 1, 8) < (1 << 22)
     assert _tree([(0.9, 0, 4, 1)], ws=FAKE * 256, ws_bytes=B.tree_workspace_bytes(sh, 200, 1, 8) - 1) == B.APE_ERR_WORKSPACE
+
+
+def test_batched_prefill_argument_errors():
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    arr = (B.ApeRequest * 2)(_req(), _req(self_len=3))
+    call = lambda n, q_len=8, q=FAKE: lib.ape_attention_prefill_batch(ctypes.byref(sh), arr, n, q, q_len, FAKE, None, None, 0, None)
+    assert call(2) == B.APE_ERR_INVALID_ARG and b"request 1" in lib.ape_last_error()     # self_len 3 < q_len 8
+    assert call(0) == B.APE_ERR_INVALID_ARG
+    assert call(1, q_len=0) == B.APE_ERR_INVALID_ARG
+    assert call(1, q=None) == B.APE_ERR_INVALID_ARG
+    assert call(1) == B.APE_ERR_WORKSPACE
 
 
 def test_rope_argument_errors():

@@ -232,3 +232,41 @@ def test_errors_leave_outputs_untouched():
     assert e.value.status == B.APE_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert (out == 7.0).all()
+
+
+# ------------------------------------------------------------------ batched query prefill
+def _check_prefill_batch(specs, q_len, self_lens, generic=False, what=""):
+    rs = [W.make_request(sp, DEV, request=b) for b, sp in enumerate(specs)]
+    sp0 = specs[0]
+    shape = B.make_shape(sp0.n_q_heads, sp0.n_kv_heads, sp0.head_dim, sp0.torch_dtype, generic=generic)
+    reqs = [H.make_binding_request(r, sl) for r, sl in zip(rs, self_lens)]
+    q = torch.stack([r.q_self[sl - q_len:sl] for r, sl in zip(rs, self_lens)]).contiguous()
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((len(rs), sp0.n_q_heads, q_len), float("nan"), dtype=torch.float32, device=DEV)
+    ws = H.poisoned_workspace(B.workspace_bytes(B.APE_OP_PREFILL, shape, len(rs), q_len), DEV)
+    B.attention_prefill_batch(shape, reqs, q, out, lse, ws, self_lens=list(self_lens))
+    torch.cuda.synchronize()
+    for b, (r, sl) in enumerate(zip(rs, self_lens)):
+        h = H.HostArrays(r)
+        ref, ref_lse, _ = H.oracle_prefill(h, q_len, sl, r.temperature, r.scale)
+        H.check_close(H.f64(out[b]).reshape(-1, sp0.head_dim), ref, sp0.dtype, "%s request %d" % (what, b))
+        assert np.abs(H.f64(lse[b]).T.reshape(-1) - ref_lse).max() <= H.lse_tol(sp0.dtype), "%s request %d lse" % (what, b)
+
+
+def test_batched_prefill_mixed_requests_bf16():
+    """Four requests in one call: different numbers and lengths of contexts (one without any),
+    prefix lengths, self lengths, T and S; the shorter contexts leave trailing splits unwritten."""
+    base = W.CONFIGS[2].replace(temperature=None, scale=None, decode_steps=40)
+    specs = [base.replace(chunk_lens=(512,) * 6, q_len=48),
+             base.replace(chunk_lens=(100, 1, 65, 300, 31), q_len=48, prefix_len=7),
+             base.replace(chunk_lens=(), q_len=48),
+             base.replace(chunk_lens=(2000,), q_len=48, prefix_len=0)]
+    _check_prefill_batch(specs, 48, [48, 60, 48, 88], what="bf16 batch")
+    _check_prefill_batch(specs[:2], 33, [33, 70], what="bf16 batch of 2")
+    _check_prefill_batch(specs, 48, [48, 60, 48, 88], generic=True, what="bf16 generic batch")
+
+
+def test_batched_prefill_fp32_and_more_than_one_launch():
+    base = W.CONFIGS[1].replace(temperature=None, scale=None)
+    specs = [base.replace(chunk_lens=tuple(5 + (3 * b + i) % 29 for i in range(1 + b % 4))) for b in range(35)]   # > 32 requests
+    _check_prefill_batch(specs, 6, [6 + b % 5 for b in range(35)], what="fp32 batch of 35")
