@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--tree-variants", action="store_true",
                     help="also time the query prefill and one decode step of the same 128K cache through the tree "
                          "entry point: one pooled node, a scaling factor per context, and a two-level tree")
+    ap.add_argument("--prefill-batch", type=int, default=0,
+                    help="also time the batched query prefill: this many requests, each over its own 128K cache")
     ap.add_argument("--rope-write", action="store_true",
                     help="also time the rotary embedding + KV-cache write in front of the encode (raw Q/K/V of the "
                          "same 64 x 2048 contexts), a bandwidth-bound kernel")
@@ -220,6 +222,35 @@ def main():
                             "node are attended in splits of their own and the tree merge replaces the two-group merge" % ms_pre)
         del ws_t
 
+    batch_res = None
+    if args.prefill_batch > 0:
+        nb = args.prefill_batch
+        rb = [r] + [W.make_request(spec, dev, request=b) for b in range(1, nb)]
+        reqs_b = [req]
+        for rr in rb[1:]:
+            kb_, vb_ = rr.chunk_views()
+            reqs_b.append(B.Request(rr.k_prefix, rr.v_prefix, kb_, vb_, rr.k_self, rr.v_self, spec.q_len, rr.temperature, rr.scale))
+        qb = torch.stack([rr.q_self[:spec.q_len] for rr in rb]).contiguous()
+        ob = torch.empty_like(qb)
+        ws_b = torch.empty(B.workspace_bytes(B.APE_OP_PREFILL, shape, nb, spec.q_len) // 4, dtype=torch.float32, device=dev)
+
+        def batch_call():
+            B.attention_prefill_batch(shape, reqs_b, qb, ob, None, ws_b)
+        for _ in range(2):
+            batch_call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            batch_call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_b = e0.elapsed_time(e1) / 10
+        batch_res = {"batch": nb, "ms": ms_b, "tflops": nb * fl_pre / (ms_b * 1e-3) / 1e12,
+                     "frac_mfma_peak": nb * fl_pre / (ms_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "note": "%d requests x 256 query rows, each over its own 128K cache (T, S per request)" % nb}
+        del rb, reqs_b, qb, ob, ws_b
+
     rope_res = None
     if args.rope_write:
         q_raw = torch.empty_like(r.q_ctx).normal_()
@@ -356,6 +387,8 @@ def main():
         line["tree_variants"] = tree_var
     if rope_res is not None:
         line["rope_write_cache"] = rope_res
+    if batch_res is not None:
+        line["prefill_batch"] = batch_res
     print(json.dumps(line))
 
 
