@@ -270,3 +270,41 @@ def test_batched_prefill_fp32_and_more_than_one_launch():
     base = W.CONFIGS[1].replace(temperature=None, scale=None)
     specs = [base.replace(chunk_lens=tuple(5 + (3 * b + i) % 29 for i in range(1 + b % 4))) for b in range(35)]   # > 32 requests
     _check_prefill_batch(specs, 6, [6 + b % 5 for b in range(35)], what="fp32 batch of 35")
+
+
+# ------------------------------------------------------------------ paged caches
+def test_paged_cache_is_a_chunk_table_of_pages():
+    """A paged KV cache needs no entry point of its own: under the pooled scaling factor the
+    chunk table may just as well list PAGES (here 64-token pages scattered over separate
+    buffers, the last page of a context partly filled), and under the tree entry point a node per
+    context lists that context's pages, which merge exactly.  Both must match the oracle run on
+    the unpaged contexts."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(300, 64, 513, 100), q_len=40, decode_steps=6)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    page = 64
+    ks, vs = r.chunk_views()
+    k_pages, v_pages, pages_of = [], [], []
+    for k, v in zip(ks, vs):
+        first = len(k_pages)
+        for p0 in range(0, k.shape[0], page):
+            k_pages.append(k[p0:p0 + page].clone())
+            v_pages.append(v[p0:p0 + page].clone())
+        pages_of.append((first, len(k_pages) - first))
+    order = list(range(len(k_pages)))[::-1]                # the table need not follow allocation order ...
+    req = B.Request(r.k_prefix, r.v_prefix, [k_pages[i] for i in order], [v_pages[i] for i in order],
+                    r.k_self, r.v_self, spec.q_len, r.temperature, r.scale)
+    _check_query(spec, r, h, spec.q_len, spec.q_len, req=req, what="pages, pooled")
+    # ... but a tree node owns a run of consecutive table entries: table in context order here
+    req = B.Request(r.k_prefix, r.v_prefix, k_pages, v_pages, r.k_self, r.v_self, spec.q_len, r.temperature, r.scale)
+    nodes = [(1.0, 1, len(pages_of), False)] + [(0.85, first, n, True) for first, n in pages_of]
+    shape = B.make_shape(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.torch_dtype)
+    tree = B.make_tree(nodes, DEV)
+    for q_len, sl in ((spec.q_len, spec.q_len), (1, spec.self_len_max)):
+        q = r.q_self[sl - q_len:sl].contiguous()
+        out = torch.full_like(q, float("nan"))
+        ws = H.poisoned_workspace(B.tree_workspace_bytes(shape, spec.total_ctx_len, len(nodes), q_len), DEV)
+        B.attention_tree(shape, req, tree, q, out, None, ws, self_len=sl)
+        torch.cuda.synchronize()
+        ref, _ = H.oracle_tree(h, q_len, sl, r.temperature, W.tree_per_context(4, 0.85))
+        H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, "bf16", "pages under one node per context, q_len %d" % q_len)
