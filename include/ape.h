@@ -13,6 +13,8 @@
  *                          the pooled context partition sum is raised to S.
  *   ape_rope_write_cache   rotary embedding with positions re-used across contexts
  *                          (Section 1) fused with the KV-cache write, in front of the above.
+ *   ape_layer_encode       one whole layer (projections and MLP as library GEMMs) around the
+ *                          encode attention, for a per-layer prefill latency (Section 5.4).
  *   ape_attention_tree     the same over a tree of contexts with a scaling factor per
  *                          node (Appendix C.2 and C.5); S per context is one such tree.
  *
@@ -245,6 +247,48 @@ int ape_rope_write_cache(const ape_shape *shape,
                          const int32_t *cu_chunk_lens_host, const int32_t *cu_chunk_lens_dev, int32_t n_chunks,
                          int32_t position_offset, float rope_base,
                          void *q_rot, void *const *k_cache, void *const *v_cache, void *stream);
+
+/*
+ * Weights of one transformer layer (the published Llama layer of the models the paper evaluates;
+ * Section 5.4 measures their prefill).  All DEVICE, dtype of the shape, [out_features, in_features]
+ * row-major.
+ */
+typedef struct {
+    int32_t hidden;             /* model width, multiple of 8                                        */
+    int32_t intermediate;       /* MLP width, multiple of 8                                          */
+    float rms_eps;              /* RMSNorm epsilon                                                   */
+    float rope_base;            /* rotary base                                                       */
+    const void *attn_norm;      /* [hidden]                                                          */
+    const void *w_qkv;          /* [(n_q_heads + 2 n_kv_heads) d, hidden]: Q rows, then K, then V    */
+    const void *w_o;            /* [hidden, n_q_heads d]                                             */
+    const void *mlp_norm;       /* [hidden]                                                          */
+    const void *w_gate_up;      /* [2 intermediate, hidden]: gate rows, then up rows                 */
+    const void *w_down;         /* [hidden, intermediate]                                            */
+} ape_layer_weights;
+
+/* Bytes of DEVICE workspace ape_layer_encode needs for total_rows packed context tokens. */
+size_t ape_layer_workspace_bytes(const ape_shape *shape, int32_t hidden, int32_t intermediate, int32_t total_rows);
+
+/*
+ * One layer of the context pre-caching pass (Section 2.2) over the packed contexts:
+ *   h = RMSNorm(x);  q, k, v = h Wqkv^T;  q, k rotated with positions re-used across contexts
+ *   (token j of every context at prefix_len + j);  k, v written to the cache;
+ *   a = ape_encode_chunks attention (prefix KV + own context, causal);  x1 = x + a Wo^T;
+ *   y = x1 + (SiLU(g) * u) Wd^T with [g, u] = RMSNorm(x1) Wgate_up^T.
+ * The four matrix products are rocBLAS GEMMs with fp32 accumulation (this entry point alone makes
+ * the library keep state: one rocBLAS handle per device, created at the first call); everything
+ * between them runs in this library's kernels.  Intermediate tensors have the dtype of the shape.
+ *
+ *   x, y               DEVICE packed [M, hidden], M = cu_chunk_lens_host[n_chunks]; y may not alias x
+ *   k_prefix, v_prefix DEVICE [prefix_len, n_kv_heads, d]: THIS layer's cached prefix KV (rotated)
+ *   k_cache, v_cache   DEVICE packed [M, n_kv_heads, d]: receive this layer's context KV
+ *   workspace          DEVICE, >= ape_layer_workspace_bytes(shape, hidden, intermediate, M)
+ */
+int ape_layer_encode(const ape_shape *shape, const ape_layer_weights *weights, const void *x,
+                     const void *k_prefix, const void *v_prefix, int32_t prefix_len,
+                     const int32_t *cu_chunk_lens_host, const int32_t *cu_chunk_lens_dev, int32_t n_chunks,
+                     void *k_cache, void *v_cache, void *y,
+                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* Text for a status code (static storage). */
 const char *ape_status_string(int status);

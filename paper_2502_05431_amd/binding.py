@@ -26,6 +26,7 @@ APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
 EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
            "ape_attention_prefill_batch",
            "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
+           "ape_layer_workspace_bytes", "ape_layer_encode",
            "ape_status_string", "ape_last_error", "ape_version")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
 
@@ -48,6 +49,13 @@ class ApeRequest(ctypes.Structure):
 class ApeTreeNode(ctypes.Structure):
     _fields_ = [("scale", ctypes.c_float), ("first", ctypes.c_int32), ("count", ctypes.c_int32),
                 ("leaf_children", ctypes.c_int32)]
+
+
+class ApeLayerWeights(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int32), ("intermediate", ctypes.c_int32), ("rms_eps", ctypes.c_float),
+                ("rope_base", ctypes.c_float), ("attn_norm", ctypes.c_void_p), ("w_qkv", ctypes.c_void_p),
+                ("w_o", ctypes.c_void_p), ("mlp_norm", ctypes.c_void_p), ("w_gate_up", ctypes.c_void_p),
+                ("w_down", ctypes.c_void_p)]
 
 
 class ApeError(RuntimeError):
@@ -90,6 +98,11 @@ def load() -> ctypes.CDLL:
         lib.ape_rope_write_cache.argtypes = [ctypes.POINTER(ApeShape), vp, vp, vp, vp, vp, i32, i32, ctypes.c_float,
                                              vp, vp, vp, vp]
         lib.ape_rope_write_cache.restype = ctypes.c_int
+        lib.ape_layer_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32]
+        lib.ape_layer_workspace_bytes.restype = sz
+        lib.ape_layer_encode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeLayerWeights), vp, vp, vp, i32,
+                                         vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.ape_layer_encode.restype = ctypes.c_int
         lib.ape_status_string.argtypes = [ctypes.c_int]
         lib.ape_status_string.restype = ctypes.c_char_p
         lib.ape_last_error.restype = ctypes.c_char_p
@@ -270,6 +283,33 @@ def rope_write_cache(shape: ApeShape, q_raw, k_raw, v_raw, cu_chunk_lens: Sequen
                                      ctypes.cast(cu_host, ctypes.c_void_p) if cu_host is not None else None,
                                      _ptr(cu_chunk_lens_dev), n_chunks, position_offset, rope_base,
                                      _ptr(q_rot), _ptr(k_cache_table), _ptr(v_cache_table), _stream(stream))
+    _check(rc)
+
+
+def layer_weights(hidden: int, intermediate: int, rms_eps: float, rope_base: float, attn_norm, w_qkv, w_o, mlp_norm,
+                  w_gate_up, w_down) -> ApeLayerWeights:
+    """``ape_layer_weights`` over device tensors (the caller keeps them alive)."""
+    for t in (attn_norm, w_qkv, w_o, mlp_norm, w_gate_up, w_down):
+        assert t.is_contiguous()
+    return ApeLayerWeights(hidden, intermediate, rms_eps, rope_base, attn_norm.data_ptr(), w_qkv.data_ptr(), w_o.data_ptr(),
+                           mlp_norm.data_ptr(), w_gate_up.data_ptr(), w_down.data_ptr())
+
+
+def layer_workspace_bytes(shape: ApeShape, hidden: int, intermediate: int, total_rows: int) -> int:
+    return int(load().ape_layer_workspace_bytes(ctypes.byref(shape), hidden, intermediate, total_rows))
+
+
+def layer_encode(shape: ApeShape, weights: ApeLayerWeights, x, k_prefix, v_prefix, cu_chunk_lens: Sequence[int],
+                 cu_chunk_lens_dev, k_cache, v_cache, y, workspace, stream=None):
+    """``ape_layer_encode``: x/y [M, hidden]; k_cache/v_cache packed [M, Hkv, d]."""
+    n_chunks = len(cu_chunk_lens) - 1 if cu_chunk_lens is not None and len(cu_chunk_lens) else 0
+    cu_host = (ctypes.c_int32 * (n_chunks + 1))(*cu_chunk_lens) if n_chunks else None
+    prefix_len = 0 if k_prefix is None else k_prefix.shape[0]
+    rc = load().ape_layer_encode(ctypes.byref(shape), ctypes.byref(weights), _ptr(x), _ptr(k_prefix), _ptr(v_prefix), prefix_len,
+                                 ctypes.cast(cu_host, ctypes.c_void_p) if cu_host is not None else None,
+                                 _ptr(cu_chunk_lens_dev), n_chunks, _ptr(k_cache), _ptr(v_cache), _ptr(y),
+                                 _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                 _stream(stream))
     _check(rc)
 
 

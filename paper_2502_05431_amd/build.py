@@ -79,7 +79,7 @@ def build(verbose: bool = True, extra=()) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     tmp = LIB + ".tmp%d" % os.getpid()
-    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs, "-lrocblas"])
     os.replace(tmp, LIB)
     with open(RESOURCES, "w") as f:
         json.dump(resources, f, indent=1, sort_keys=True)

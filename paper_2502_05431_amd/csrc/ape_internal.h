@@ -138,8 +138,11 @@ struct RopeArgs {
     const void* k_raw;          // packed [M, Hkv, d] or NULL
     const void* v_raw;          // packed [M, Hkv, d] or NULL
     void* q_rot;                // packed [M, Hq, d]
-    void* const* k_cache;       // device [n_chunks] of device pointers [l_i, Hkv, d]
+    void* const* k_cache;       // device [n_chunks] of device pointers [l_i, Hkv, d], or NULL with k_packed set
     void* const* v_cache;
+    void* k_packed;             // alternative destination: one packed buffer [M, Hkv, d]
+    void* v_packed;
+    int64_t q_stride, k_stride, v_stride;   // elements between consecutive tokens of the raw inputs
     const int32_t* cu;          // device [n_chunks + 1]
     int32_t n_chunks;
     int32_t total_rows;         // M
@@ -223,6 +226,11 @@ hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s);
 hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
 hipError_t launch_rope_write(const RopeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_rmsnorm(const void* x, const void* w, void* y, long rows, int hidden, float eps, int dtype, hipStream_t s);
+hipError_t launch_swiglu(const void* gate_up, void* act, long rows, int inter, int dtype, hipStream_t s);
+// y[rows, n] = x[rows, k] W[n, k]^T (+ residual); 0 on success
+int gemm_xwT(const void* x, long ldx, const void* w, const void* residual, void* y, long ldy, long rows, int n, int k,
+             int dtype, hipStream_t s);
 hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s);
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s);     // bf16, d = 128

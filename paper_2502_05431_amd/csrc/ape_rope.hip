@@ -70,10 +70,11 @@ __global__ __launch_bounds__(kRopeThreads) void rope_write_kernel(const RopeArgs
     }
     __syncthreads();
 
-    const T* q_src = (const T*)a.q_raw;
-    T* q_dst = (T*)a.q_rot;
-    const T* k_src = (const T*)a.k_raw;
-    T* k_dst = k_src ? (T*)scalar_load_ptr((const void* const*)a.k_cache + lo) : nullptr;
+    const T* q_src = a.q_raw ? (const T*)a.q_raw + t * a.q_stride : nullptr;     // this token's rows
+    T* q_dst = (T*)a.q_rot + t * hq * d;
+    const T* k_src = a.k_raw ? (const T*)a.k_raw + t * a.k_stride : nullptr;
+    T* k_dst = nullptr;
+    if (k_src) k_dst = a.k_packed ? (T*)a.k_packed + t * hkv * d : (T*)scalar_load_ptr((const void* const*)a.k_cache + lo) + j * hkv * d;
     const int rows_q = q_src ? hq : 0, rows_k = k_src ? hkv : 0;
 
     if constexpr (VEC) {
@@ -82,8 +83,8 @@ __global__ __launch_bounds__(kRopeThreads) void rope_write_kernel(const RopeArgs
         for (int item = tid; item < (rows_q + rows_k) * gpr; item += kRopeThreads) {
             const int row = item / gpr, c = (item - row * gpr) * N;
             const T* src; T* dst;
-            if (row < rows_q) { src = q_src + (t * hq + row) * d; dst = q_dst + (t * hq + row) * d; }
-            else { src = k_src + (t * hkv + (row - rows_q)) * d; dst = k_dst + (j * hkv + (row - rows_q)) * d; }
+            if (row < rows_q) { src = q_src + row * d; dst = q_dst + row * d; }
+            else { src = k_src + (row - rows_q) * d; dst = k_dst + (row - rows_q) * d; }
             float x1[N], x2[N], y1[N], y2[N];
             load16<T>(src + c, x1);
             load16<T>(src + c + half, x2);
@@ -100,16 +101,16 @@ __global__ __launch_bounds__(kRopeThreads) void rope_write_kernel(const RopeArgs
         for (int item = tid; item < (rows_q + rows_k) * half; item += kRopeThreads) {
             const int row = item / half, c = item - row * half;
             const T* src; T* dst;
-            if (row < rows_q) { src = q_src + (t * hq + row) * d; dst = q_dst + (t * hq + row) * d; }
-            else { src = k_src + (t * hkv + (row - rows_q)) * d; dst = k_dst + (j * hkv + (row - rows_q)) * d; }
+            if (row < rows_q) { src = q_src + row * d; dst = q_dst + row * d; }
+            else { src = k_src + (row - rows_q) * d; dst = k_dst + (row - rows_q) * d; }
             const float x1 = (float)src[c], x2 = (float)src[c + half];
             dst[c] = (T)(x1 * cs[c] - x2 * sn[c]);
             dst[c + half] = (T)(x2 * cs[c] + x1 * sn[c]);
         }
     }
     if (a.v_raw) {                                        // values: copied unchanged, 16 bytes at a time (d * sizeof(T) is a multiple of 16)
-        const uint4* src = (const uint4*)((const T*)a.v_raw + t * hkv * d);
-        uint4* dst = (uint4*)((T*)scalar_load_ptr((const void* const*)a.v_cache + lo) + j * hkv * d);
+        const uint4* src = (const uint4*)((const T*)a.v_raw + t * a.v_stride);
+        uint4* dst = (uint4*)(a.v_packed ? (T*)a.v_packed + t * hkv * d : (T*)scalar_load_ptr((const void* const*)a.v_cache + lo) + j * hkv * d);
         const int n16 = hkv * d * (int)sizeof(T) / 16;
         for (int i = tid; i < n16; i += kRopeThreads) dst[i] = src[i];
     }

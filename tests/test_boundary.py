@@ -191,6 +191,39 @@ def test_batched_prefill_argument_errors():
     assert call(1) == B.APE_ERR_WORKSPACE
 
 
+def test_layer_argument_errors():
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    cu = (ctypes.c_int32 * 3)(0, 5, 9)
+    cuh = ctypes.cast(cu, ctypes.c_void_p)
+
+    def weights(**kw):
+        w = B.ApeLayerWeights(4096, 14336, 1e-5, 500000.0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+        for k, v in kw.items():
+            setattr(w, k, v)
+        return w
+
+    def layer(w=None, x=FAKE, kp=FAKE, vp=FAKE, lp=4, cu_host=cuh, cu_dev=FAKE, n=2, kc=FAKE, vc=FAKE, y=FAKE, ws=None, wsb=0):
+        w = w or weights()
+        return lib.ape_layer_encode(ctypes.byref(sh), ctypes.byref(w), x, kp, vp, lp, cu_host, cu_dev, n, kc, vc, y, ws, wsb, None)
+    assert layer(w=weights(hidden=4095)) == B.APE_ERR_UNSUPPORTED
+    assert layer(w=weights(intermediate=0)) == B.APE_ERR_UNSUPPORTED
+    assert layer(w=weights(rms_eps=-1.0)) == B.APE_ERR_INVALID_ARG
+    assert layer(w=weights(rope_base=0.0)) == B.APE_ERR_INVALID_ARG
+    assert layer(w=weights(w_o=None)) == B.APE_ERR_INVALID_ARG
+    assert layer(kp=None) == B.APE_ERR_INVALID_ARG
+    assert layer(lp=-1) == B.APE_ERR_INVALID_ARG
+    assert layer(cu_host=None) == B.APE_ERR_INVALID_ARG
+    assert layer(x=None) == B.APE_ERR_INVALID_ARG
+    assert layer(kc=None) == B.APE_ERR_INVALID_ARG
+    assert layer() == B.APE_ERR_WORKSPACE
+    assert layer(ws=FAKE + 8, wsb=1 << 40) == B.APE_ERR_WORKSPACE
+    assert layer(n=0) == B.APE_OK                                  # nothing to do
+    need = B.layer_workspace_bytes(sh, 4096, 14336, 131072)
+    assert need % 256 == 0 and 4 * 2 ** 30 < need < 8 * 2 ** 30    # the MLP runs in slabs: a few GiB, not 16
+    assert B.layer_workspace_bytes(sh, 4095, 14336, 10) == 0
+
+
 def test_rope_argument_errors():
     lib = B.load()
     sh = B.make_shape(32, 8, 128, B.APE_BF16)
