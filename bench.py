@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--tree-variants", action="store_true",
                     help="also time the query prefill and one decode step of the same 128K cache through the tree "
                          "entry point: one pooled node, a scaling factor per context, and a two-level tree")
+    ap.add_argument("--layer", action="store_true",
+                    help="also time one whole Llama-3-8B-shaped layer (hidden 4096, MLP 14336, random weights) of the "
+                         "context pre-caching pass over the same 64 x 2048 contexts")
     ap.add_argument("--prefill-batch", type=int, default=0,
                     help="also time the batched query prefill: this many requests, each over its own 128K cache")
     ap.add_argument("--rope-write", action="store_true",
@@ -221,6 +224,41 @@ def main():
         tree_var["note"] = ("same cache and query as the prefill phase (flat entry point: %.3f ms); the contexts of every "
                             "node are attended in splits of their own and the tree merge replaces the two-group merge" % ms_pre)
         del ws_t
+
+    layer_res = None
+    if args.layer:
+        hidden, inter = 4096, 14336
+        gw = torch.Generator(device=dev)
+        gw.manual_seed(r.seed + 7)
+        rn = lambda *sh, scale=1.0: (torch.randn(sh, generator=gw, device=dev, dtype=torch.float32) * scale).to(torch.bfloat16)
+        wts = dict(attn_norm=torch.ones(hidden, dtype=torch.bfloat16, device=dev), w_qkv=rn((hq + 2 * hkv) * d, hidden, scale=hidden ** -0.5),
+                   w_o=rn(hidden, hq * d, scale=(hq * d) ** -0.5), mlp_norm=torch.ones(hidden, dtype=torch.bfloat16, device=dev),
+                   w_gate_up=rn(2 * inter, hidden, scale=hidden ** -0.5), w_down=rn(hidden, inter, scale=inter ** -0.5))
+        lw = B.layer_weights(hidden, inter, 1e-5, 500000.0, **wts)
+        m_tok = spec.total_ctx_len
+        xl = rn(m_tok, hidden)
+        yl = torch.empty_like(xl)
+        kcl, vcl = torch.empty_like(r.k_ctx), torch.empty_like(r.v_ctx)
+        ws_l = torch.empty(B.layer_workspace_bytes(shape, hidden, inter, m_tok) // 4, dtype=torch.float32, device=dev)
+
+        def layer_call():
+            B.layer_encode(shape, lw, xl, r.k_prefix, r.v_prefix, cu, cu_dev, kcl, vcl, yl, ws_l)
+        layer_call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            layer_call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_l = e0.elapsed_time(e1) / 3
+        fl_gemm = 2.0 * m_tok * hidden * ((hq + 2 * hkv) * d + hq * d + 3 * inter)
+        layer_res = {"ms": ms_l, "tflops": (fl_gemm + fl_enc) / (ms_l * 1e-3) / 1e12, "gemm_flop": fl_gemm, "attention_flop": fl_enc,
+                     "attention_share_of_time": float(ms_enc) / ms_l,
+                     "projected_32_layer_prefill_s": 32 * ms_l * 1e-3,
+                     "note": "hidden 4096, MLP 14336, 32 q / 8 kv heads, bf16; 131072 context tokens as 64 x 2048; the four "
+                             "projections are rocBLAS GEMMs"}
+        del xl, yl, kcl, vcl, ws_l, wts
 
     batch_res = None
     if args.prefill_batch > 0:
@@ -389,6 +427,8 @@ def main():
         line["rope_write_cache"] = rope_res
     if batch_res is not None:
         line["prefill_batch"] = batch_res
+    if layer_res is not None:
+        line["layer_encode"] = layer_res
     print(json.dumps(line))
 
 
