@@ -89,6 +89,14 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     return p;
 }
 
+// Split plan of the query prefill: one workgroup per CU on the matrix-core path.
+QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) {
+    const int rows = q_len * si.group;
+    const long units = (long)batch * q_len * si.hq;
+    const int base = si.mfma ? batch * si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
+    return plan_query(base, max_ctx, 256, si.mfma ? 256 : 1024);
+}
+
 // Splits of the tree entry point: the contexts of every node that holds contexts are cut into
 // runs of `len` tokens; `len` is what the flat entry points would use for the same sizes, so a
 // one-node tree runs exactly like them.  max_splits bounds the splits in use from sizes only:
@@ -102,11 +110,7 @@ struct TreePlan {
 TreePlan plan_tree(const ShapeInfo& si, long total_ctx, int n_nodes, int q_len) {
     QueryPlan qp;
     if (q_len == 1) qp = plan_query(si.mfma ? si.hkv : si.hq, total_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
-    else {
-        const int rows = q_len * si.group;
-        const int base = si.mfma ? si.hkv * ceil_div(rows, flash_block_rows(rows)) : q_len * si.hq;
-        qp = plan_query(base, total_ctx, 256, si.mfma ? 256 : 1024);
-    }
+    else qp = prefill_plan(si, 1, q_len, total_ctx);
     TreePlan p;
     p.len = qp.ctx_split_len;
     p.max_splits = ceil_div(total_ctx > 0 ? total_ctx : 1, p.len) + n_nodes;
@@ -194,8 +198,10 @@ size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_
     if (op == APE_OP_DECODE) q_len = 1;
     else if (op != APE_OP_PREFILL) return 0;
     if (batch < 1 || q_len < 1) return 0;
-    // worst case over every context length: kMaxSplits context splits + 1
-    return partial_bytes((long)batch * q_len * si.hq, kMaxSplits + 1, si.d);
+    // worst case over every context length: as many context splits as the planner can ask for, + 1
+    int n_max = kMaxSplits;
+    if (op == APE_OP_PREFILL) n_max = prefill_plan(si, batch, q_len, (long)kMaxSplits * (1 << 20)).n_ctx_splits;
+    return partial_bytes((long)batch * q_len * si.hq, n_max + 1, si.d);
 }
 
 int ape_encode_chunks(const ape_shape* shape,
@@ -267,9 +273,7 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         const int base = si.mfma ? batch * si.hkv : (int)units;
         plan = plan_query(base, max_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
     } else {
-        const int rows = q_len * si.group;
-        const int base = si.mfma ? batch * si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
-        plan = plan_query(base, max_ctx, si.mfma ? 256 : 256, si.mfma ? 256 : 1024);
+        plan = prefill_plan(si, batch, q_len, max_ctx);
     }
     const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
     if (!workspace || workspace_bytes < need)

@@ -42,7 +42,8 @@ def test_workspace_bytes():
     assert d % 256 == 0 and p % 256 == 0
     # decode ignores q_len; a batched prefill needs room for every request
     assert B.workspace_bytes(B.APE_OP_DECODE, sh, 32, 77) == d
-    assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 4, 256) == 4 * p
+    p4 = B.workspace_bytes(B.APE_OP_PREFILL, sh, 4, 256)
+    assert p < p4 <= 4 * p                                 # more requests, fewer context splits each
     bad = B.make_shape(32, 7, 128, B.APE_BF16)
     assert B.workspace_bytes(B.APE_OP_DECODE, bad, 1, 1) == 0
     assert B.workspace_bytes(99, sh, 1, 1) == 0
@@ -172,9 +173,9 @@ def test_tree_limits_and_workspace_size():
     assert B.tree_workspace_bytes(sh, 131072, 0, 256) == 0
     assert B.tree_workspace_bytes(sh, 131072, B.APE_TREE_MAX_NODES + 1, 1) == 0
     assert B.tree_workspace_bytes(sh, -1, 4, 1) == 0
-    # a one-node tree needs about what the flat entry point needs
+    # a one-node tree needs what the flat entry point needs plus one spare split and the plan
     flat = B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256)
-    assert B.tree_workspace_bytes(sh, 131072, 1, 256) <= flat
+    assert flat <= B.tree_workspace_bytes(sh, 131072, 1, 256) <= flat * 10 // 9 + 65536
     assert B.tree_workspace_bytes(sh, 200, 1, 8) < (1 << 22)
     assert _tree([(0.9, 0, 4, 1)], ws=FAKE * 256, ws_bytes=B.tree_workspace_bytes(sh, 200, 1, 8) - 1) == B.APE_ERR_WORKSPACE
 
