@@ -134,7 +134,7 @@ struct Tally { int cases = 0, failed = 0, fast = 0, bodies = 0; };
 template <typename MakeStream>
 static void run_case(Tally& t, const char* what, MakeStream make, const std::vector<std::pair<const char*, const char*>>& valid,
                      const std::vector<int>& vis_los, int expect_rows) {
-    for (int ring : {5, 6}) {
+    for (int ring : {5, 6, 8}) {
         int barriers = -1;
         for (int vis_lo : vis_los) {
             Sim sim; sim.valid = valid;
@@ -142,7 +142,7 @@ static void run_case(Tally& t, const char* what, MakeStream make, const std::vec
             walk(ld, sim);
             int rows = 0; for (int d : sim.ref_desc) rows += desc_n(d);
             if (rows != expect_rows) sim.fail("stream delivers " + std::to_string(rows) + " rows, expected " + std::to_string(expect_rows));
-            if (ring == 5) run<5>(sim, ld, vis_lo); else run<6>(sim, ld, vis_lo);
+            if (ring == 5) run<5>(sim, ld, vis_lo); else if (ring == 6) run<6>(sim, ld, vis_lo); else run<8>(sim, ld, vis_lo);
             if (sim.err.empty() && barriers >= 0 && sim.barriers != barriers) sim.fail("wavefronts with different causal limits execute different numbers of barriers");
             barriers = sim.barriers;
             ++t.cases; t.fast += sim.fast; t.bodies += sim.bodies;
