@@ -308,3 +308,27 @@ def test_paged_cache_is_a_chunk_table_of_pages():
         torch.cuda.synchronize()
         ref, _ = H.oracle_tree(h, q_len, sl, r.temperature, W.tree_per_context(4, 0.85))
         H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, "bf16", "pages under one node per context, q_len %d" % q_len)
+
+
+# ------------------------------------------------------------------ the ends of the paper's hyper-parameter grid
+@pytest.mark.parametrize("T,S", [(0.1, 0.1), (0.1, 1.0), (1.0, 0.1), (0.5, 0.5)])
+def test_hyperparameter_grid_corners(T, S):
+    """The paper searches T and S over [0.1, 1.0] (end of Section 4.4).  T = 0.1 multiplies the
+    context scores by ten (standard deviation ~10 here: probabilities spanning e^60 within a row),
+    S = 0.1 all but removes the context mass.  Prefill, decode and the tree entry point, bf16
+    matrix-core path and fp32 path."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(512, 300, 1, 700), q_len=40, decode_steps=4, k_scale=1.0, temperature=T, scale=S)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_query(spec, r, h, spec.q_len, spec.q_len, what="bf16 T=%g S=%g" % (T, S))
+    _check_decode(spec, r, h, spec.self_len_max, what="bf16 T=%g S=%g" % (T, S))
+    out, _ = H.run_tree(spec, r, W.tree_per_context(4, S), spec.q_len, spec.q_len)
+    ref, _ = H.oracle_tree(h, spec.q_len, spec.q_len, T, W.tree_per_context(4, S))
+    H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, "bf16", "tree T=%g S=%g" % (T, S))
+    # fp32: a score of magnitude |s| carries an absolute rounding error of a few |s| * 6e-8, which is the
+    # relative error of its probability; N(0,1) inputs at T = 0.1 give |s| up to ~40, still inside 1e-5
+    spec1 = W.CONFIGS[1].replace(temperature=T, scale=S, rope_base=None)
+    r1 = W.make_request(spec1, DEV)
+    h1 = H.HostArrays(r1)
+    _check_query(spec1, r1, h1, spec1.q_len, spec1.q_len, what="fp32 T=%g S=%g" % (T, S))
+    _check_decode(spec1, r1, h1, spec1.self_len_max, what="fp32 T=%g S=%g" % (T, S))
