@@ -332,3 +332,22 @@ def test_hyperparameter_grid_corners(T, S):
     h1 = H.HostArrays(r1)
     _check_query(spec1, r1, h1, spec1.q_len, spec1.q_len, what="fp32 T=%g S=%g" % (T, S))
     _check_decode(spec1, r1, h1, spec1.self_len_max, what="fp32 T=%g S=%g" % (T, S))
+
+
+# ------------------------------------------------------------------ short chunks
+@pytest.mark.parametrize("kw", [
+    dict(chunk_lens=(256,) * 5, prefix_len=32),                                   # the many-shot shape
+    dict(chunk_lens=(256, 1, 33, 64, 255, 129, 200, 97), prefix_len=7),           # ragged, partial last blocks
+    dict(chunk_lens=(288, 40, 65), prefix_len=0),                                 # no prefix: nine chunk blocks
+    dict(chunk_lens=(224, 100), prefix_len=64),                                   # two prefix blocks
+    dict(chunk_lens=(250, 130), prefix_len=32, n_q_heads=8, n_kv_heads=8),        # G = 1
+    dict(chunk_lens=(250, 130), prefix_len=32, n_q_heads=16, n_kv_heads=8),       # G = 2
+    dict(chunk_lens=(250, 60), prefix_len=5, n_q_heads=16, n_kv_heads=2),         # G = 8
+], ids=lambda kw: "x".join(str(v) for v in kw["chunk_lens"][:3]) + "_p%d" % kw["prefix_len"])
+def test_bf16_encode_short_chunks(kw):
+    """Many-shot shapes: streams of two to ten blocks per query tile, where every body is a generic
+    one (block tails, the causal diagonal) and the ring never wraps."""
+    spec = W.CONFIGS[2].replace(q_len=8, decode_steps=0, **kw)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, what="short chunks %s" % (kw,))
