@@ -1,0 +1,119 @@
+"""Randomised checks of the host-side logic of the C-ABI library (no GPU): the tree validator
+against an independent Python statement of the numbering rules, and the workspace sizes against
+what the calls themselves demand."""
+import ctypes
+import random
+
+import pytest
+
+from paper_2502_05431_amd import binding as B
+from paper_2502_05431_amd import workloads as W
+
+FAKE = 0x1000
+
+
+def _valid_tree(nodes, n_chunks):
+    """The numbering rules of ape_tree_node, restated: breadth-first child ranges, every context
+    owned exactly once, at most APE_TREE_MAX_DEPTH levels."""
+    if not nodes or len(nodes) > B.APE_TREE_MAX_NODES or not 1 <= n_chunks <= B.APE_TREE_MAX_CONTEXTS:
+        return False
+    owned, nxt = [0] * n_chunks, 1
+    for s, first, count, leaf in nodes:
+        if not (s > 0 and s != float("inf")) or count < 1:
+            return False
+        if leaf:
+            if first < 0 or first + count > n_chunks:
+                return False
+            for c in range(first, first + count):
+                owned[c] += 1
+        else:
+            if first != nxt:
+                return False
+            nxt += count
+            if nxt > len(nodes):
+                return False
+    if nxt != len(nodes) or any(o != 1 for o in owned):
+        return False
+    level, depth = [0], 1
+    while True:
+        kids = [c for n in level if not nodes[n][3] for c in range(nodes[n][1], nodes[n][1] + nodes[n][2])]
+        if not kids:
+            return depth <= B.APE_TREE_MAX_DEPTH
+        level, depth = kids, depth + 1
+
+
+def _call_tree(nodes, n_chunks, total_ctx=4096, q_len=4):
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    arr = (B.ApeTreeNode * max(len(nodes), 1))(*[B.ApeTreeNode(float(s), f, c, 1 if leaf else 0) for s, f, c, leaf in nodes])
+    r = B.ApeRequest()
+    r.k_prefix = FAKE; r.v_prefix = FAKE; r.prefix_len = 4; r.n_chunks = n_chunks
+    r.k_chunks = FAKE; r.v_chunks = FAKE; r.cu_chunk_lens = FAKE; r.total_ctx_len = total_ctx
+    r.self_len = q_len; r.k_self = FAKE; r.v_self = FAKE; r.temperature = 0.9; r.scale = 0.9
+    # no workspace: a valid tree gets as far as the workspace check and nothing is ever launched
+    return B.load().ape_attention_tree(ctypes.byref(sh), ctypes.byref(r), ctypes.cast(arr, ctypes.c_void_p), FAKE, len(nodes),
+                                       FAKE, q_len, FAKE, None, None, 0, None)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_tree_validator_agrees_with_the_rules(seed):
+    rng = random.Random(seed)
+    n_chunks = rng.randint(1, 40)
+    nodes = W.tree_random(n_chunks, seed, max_children=rng.randint(2, 6))
+    assert _valid_tree(nodes, n_chunks)
+    assert _call_tree(nodes, n_chunks) == B.APE_ERR_WORKSPACE
+    # one random mutation: still judged the same way by both
+    for _ in range(12):
+        m = [list(n) for n in nodes]
+        i = rng.randrange(len(m))
+        field = rng.choice(["scale", "first", "count", "leaf", "drop", "dup"])
+        if field == "scale":
+            m[i][0] = rng.choice([0.0, -1.0, 0.5, float("inf")])
+        elif field == "first":
+            m[i][1] += rng.choice([-1, 1, 2])
+        elif field == "count":
+            m[i][2] += rng.choice([-1, 1])
+        elif field == "leaf":
+            m[i][3] = not m[i][3]
+        elif field == "drop" and len(m) > 1:
+            del m[i]
+        else:
+            m.append(list(m[i]))
+        mt = [tuple(n) for n in m]
+        expect_ok = _valid_tree(mt, n_chunks)
+        rc = _call_tree(mt, n_chunks)
+        assert (rc == B.APE_ERR_WORKSPACE) == expect_ok, (mt, rc)
+        assert rc in (B.APE_ERR_WORKSPACE, B.APE_ERR_INVALID_ARG, B.APE_ERR_UNSUPPORTED)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_workspace_sizes_are_what_the_calls_demand(seed):
+    """A call with one byte less than ape_*_workspace_bytes reports is refused for the workspace;
+    sizes grow with the tree and the batch."""
+    rng = random.Random(100 + seed)
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    n_chunks = rng.randint(1, 64)
+    total = rng.randint(n_chunks, 200000)
+    q_len = rng.choice([1, 7, 64, 256])
+    nodes = W.tree_random(n_chunks, seed)
+    need = B.tree_workspace_bytes(sh, total, len(nodes), q_len)
+    assert need > 0 and need % 256 == 0
+    assert B.tree_workspace_bytes(sh, total, len(nodes) + 5, q_len) > need
+    arr = (B.ApeTreeNode * len(nodes))(*[B.ApeTreeNode(float(s), f, c, 1 if leaf else 0) for s, f, c, leaf in nodes])
+    r = B.ApeRequest()
+    r.k_prefix = FAKE; r.v_prefix = FAKE; r.prefix_len = 4; r.n_chunks = n_chunks
+    r.k_chunks = FAKE; r.v_chunks = FAKE; r.cu_chunk_lens = FAKE; r.total_ctx_len = total
+    r.self_len = q_len; r.k_self = FAKE; r.v_self = FAKE; r.temperature = 0.9; r.scale = 0.9
+    rc = B.load().ape_attention_tree(ctypes.byref(sh), ctypes.byref(r), ctypes.cast(arr, ctypes.c_void_p), FAKE, len(nodes),
+                                     FAKE, q_len, FAKE, None, FAKE * 256, need - 1, None)
+    assert rc == B.APE_ERR_WORKSPACE
+    # flat entry points: the bound never shrinks with batch or rows
+    batch = rng.randint(1, 40)
+    d1 = B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1)
+    assert B.workspace_bytes(B.APE_OP_DECODE, sh, batch + 1, 1) > d1
+    assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, q_len) > 0           # (not monotone in q_len: more row tiles, fewer splits)
+    rq = B.ApeRequest()
+    for k in ("k_prefix", "v_prefix", "k_chunks", "v_chunks", "cu_chunk_lens", "k_self", "v_self"):
+        setattr(rq, k, FAKE)
+    rq.prefix_len = 4; rq.n_chunks = n_chunks; rq.total_ctx_len = total; rq.self_len = q_len; rq.temperature = 0.9; rq.scale = 0.9
+    rc = B.load().ape_attention_prefill(ctypes.byref(sh), ctypes.byref(rq), FAKE, q_len, FAKE, None, FAKE * 256, 1, None)
+    assert rc == B.APE_ERR_WORKSPACE
