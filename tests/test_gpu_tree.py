@@ -159,3 +159,24 @@ def test_cfg4_manyshot_two_level_tree_sampled():
     pairs = [(0, hd) for hd in range(spec.n_q_heads)]
     _check_sampled(spec, r, h, nodes, 1, sl, pairs, "cfg4 grouped decode")
     _check_sampled(spec, r, h, W.tree_per_context(512, r.scale), 1, sl, pairs, "cfg4 per-context decode")
+
+
+def test_contexts_that_are_all_empty():
+    """A chunk table whose contexts hold no token at all: plain causal attention over prefix + self,
+    through the flat and the tree entry points (a tree whose every node is empty has weight zero)."""
+    for dtype, cfg in (("bf16", 2), ("f32", 1)):
+        spec = W.CONFIGS[cfg].replace(chunk_lens=(0, 0, 0), q_len=12, decode_steps=2)
+        r = W.make_request(spec, DEV)
+        h = H.HostArrays(r)
+        ref, _, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale)
+        dummy = torch.zeros((1, spec.n_kv_heads, spec.head_dim), dtype=spec.torch_dtype, device=DEV)
+        req = B.Request(r.k_prefix, r.v_prefix, [dummy[:0]] * 3, [dummy[:0]] * 3, r.k_self, r.v_self, spec.q_len,
+                        r.temperature, r.scale)
+        out, _ = H.run_prefill(spec, r, spec.q_len, spec.q_len, req=req)
+        H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, dtype, "flat, empty contexts")
+        for nodes in (W.tree_pooled(3, 0.9), W.tree_per_context(3, 0.9)):
+            out, _ = H.run_tree(spec, r, nodes, spec.q_len, spec.q_len, req=req)
+            H.check_close(H.f64(out).reshape(-1, spec.head_dim), ref, dtype, "tree, empty contexts")
+            out, _ = H.run_tree(spec, r, nodes, 1, spec.q_len + 1, req=req)
+            refd, _, _ = H.oracle_prefill(h, 1, spec.q_len + 1, r.temperature, r.scale)
+            H.check_close(H.f64(out).reshape(-1, spec.head_dim), refd, dtype, "tree decode, empty contexts")
