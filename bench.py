@@ -48,8 +48,10 @@ def pair_counts(spec):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=25,
+                    help="untimed steps; the chip raises its clocks over the first ~100 ms of load (a 10-step run of "
+                         "the prefill measures 0.67 ms per call, a 1000-step run 0.55 ms), so keep this at 25 or more")
     ap.add_argument("--decode-steps", type=int, default=8, help="decode steps per step over the 128K cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the batched-decode (config 5) region")
@@ -91,6 +93,28 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B.load()
+
+    def timed(fn, iters, warm_ms=150.0):
+        """Average ms per call of fn over `iters` calls, after calling it untimed for at least warm_ms of
+        GPU time (the chip raises its clocks over the first ~100 ms of load; a region that follows host-side
+        set-up starts from low clocks again)."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        spent = 0.0
+        while spent < warm_ms:
+            e0.record()
+            for _ in range(4):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            spent += e0.elapsed_time(e1)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
 
     spec = W.CONFIGS[3].replace(decode_steps=args.decode_steps)
     r = W.make_request(spec, dev)
@@ -179,15 +203,7 @@ def main():
 
         def seq_encode():
             B.encode_chunks(shape, None, r.k_prefix, r.v_prefix, r.q_ctx, r.k_ctx, r.v_ctx, cu1, cu1_dev, None, o_ctx)
-        seq_encode()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
-            seq_encode()
-        e1.record()
-        torch.cuda.synchronize()
-        ms_seq = e0.elapsed_time(e1) / 3
+        ms_seq = timed(seq_encode, 3, warm_ms=100.0)
         fl_seq = 4.0 * d * hq * (m_tok * (m_tok + 1) // 2 + m_tok * spec.prefix_len)
         seq_cmp = {"ms": ms_seq, "tflops": fl_seq / (ms_seq * 1e-3) / 1e12,
                    "attention_time_ratio_vs_parallel_encode": ms_seq / ms_enc,
@@ -208,16 +224,7 @@ def main():
             res = {"nodes": len(nodes)}
             for kind, fn in (("prefill_ms", lambda: B.attention_tree(shape, req, tree, q, out, None, ws_t)),
                              ("decode_ms_per_token", lambda: B.attention_tree(shape, req, tree, qd1, od1, None, ws_t))):
-                for _ in range(3):
-                    fn()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(20):
-                    fn()
-                e1.record()
-                torch.cuda.synchronize()
-                res[kind] = e0.elapsed_time(e1) / 20
+                res[kind] = timed(fn, 50)
             res["prefill_tflops"] = fl_pre / (res["prefill_ms"] * 1e-3) / 1e12
             res["decode_gbs"] = (kv_row_bytes * (spec.prefix_len + spec.total_ctx_len + spec.q_len)) / (res["decode_ms_per_token"] * 1e-3) / 1e9
             tree_var[name] = res
@@ -243,15 +250,7 @@ def main():
 
         def layer_call():
             B.layer_encode(shape, lw, xl, r.k_prefix, r.v_prefix, cu, cu_dev, kcl, vcl, yl, ws_l)
-        layer_call()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
-            layer_call()
-        e1.record()
-        torch.cuda.synchronize()
-        ms_l = e0.elapsed_time(e1) / 3
+        ms_l = timed(layer_call, 5)
         fl_gemm = 2.0 * m_tok * hidden * ((hq + 2 * hkv) * d + hq * d + 3 * inter)
         layer_res = {"ms": ms_l, "tflops": (fl_gemm + fl_enc) / (ms_l * 1e-3) / 1e12, "gemm_flop": fl_gemm, "attention_flop": fl_enc,
                      "attention_share_of_time": float(ms_enc) / ms_l,
@@ -274,16 +273,7 @@ def main():
 
         def batch_call():
             B.attention_prefill_batch(shape, reqs_b, qb, ob, None, ws_b)
-        for _ in range(2):
-            batch_call()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            batch_call()
-        e1.record()
-        torch.cuda.synchronize()
-        ms_b = e0.elapsed_time(e1) / 10
+        ms_b = timed(batch_call, 20)
         batch_res = {"batch": nb, "ms": ms_b, "tflops": nb * fl_pre / (ms_b * 1e-3) / 1e12,
                      "frac_mfma_peak": nb * fl_pre / (ms_b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                      "note": "%d requests x 256 query rows, each over its own 128K cache (T, S per request)" % nb}
@@ -300,16 +290,7 @@ def main():
 
         def rope_call():
             B.rope_write_cache(shape, q_raw, k_raw, v_raw, cu, cu_dev, spec.prefix_len, 500000.0, q_rot, kt, vt)
-        for _ in range(2):
-            rope_call()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(10):
-            rope_call()
-        e1.record()
-        torch.cuda.synchronize()
-        ms_rope = e0.elapsed_time(e1) / 10
+        ms_rope = timed(rope_call, 30)
         by_rope = 2.0 * (q_raw.numel() + k_raw.numel() + v_raw.numel()) * 2          # every element read once, written once
         rope_res = {"ms": ms_rope, "gbs": by_rope / (ms_rope * 1e-3) / 1e9, "frac_hbm_peak": by_rope / (ms_rope * 1e-3) / 1e9 / PEAK_HBM_GBS,
                     "bytes": by_rope, "note": "131072 tokens x (32 q + 8 k + 8 v heads) x 128, bf16, read once and written once"}
@@ -324,16 +305,8 @@ def main():
             b_ = torch.zeros(n, n, dtype=torch.bfloat16, device=dev)
             if name == "random":
                 a_.normal_(); b_.normal_()
-            for _ in range(3):
-                torch.matmul(a_, b_)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(20):
-                torch.matmul(a_, b_)
-            e1.record()
-            torch.cuda.synchronize()
-            gemm_ref["torch_bf16_gemm_8192_tflops_" + name] = 2.0 * n ** 3 * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            ms_g = timed(lambda: torch.matmul(a_, b_), 20)
+            gemm_ref["torch_bf16_gemm_8192_tflops_" + name] = 2.0 * n ** 3 / (ms_g * 1e-3) / 1e12
             del a_, b_
 
     if args.calibrate_copy:
@@ -365,16 +338,7 @@ def main():
         def decode_pass():
             for fn, _ in calls5:
                 fn()
-        decode_pass()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 3
-        e0.record()
-        for _ in range(reps):
-            decode_pass()
-        e1.record()
-        torch.cuda.synchronize()
-        ms5 = e0.elapsed_time(e1) / reps
+        ms5 = timed(decode_pass, 5)
         tok5 = [spec5.batch * (spec5.prefix_len + spec5.total_ctx_len + s + 1) for s in range(spec5.decode_steps)]
         by5 = sum(kv_row_bytes * t + spec5.batch * 2 * hq * d * 2 for t in tok5)
         phases["decode_cfg5_batch32"] = {"ms_per_step": ms5 / spec5.decode_steps, "gbs": by5 / (ms5 * 1e-3) / 1e9,
