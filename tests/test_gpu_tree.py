@@ -180,3 +180,25 @@ def test_contexts_that_are_all_empty():
             out, _ = H.run_tree(spec, r, nodes, 1, spec.q_len + 1, req=req)
             refd, _, _ = H.oracle_prefill(h, 1, spec.q_len + 1, r.temperature, r.scale)
             H.check_close(H.f64(out).reshape(-1, spec.head_dim), refd, dtype, "tree decode, empty contexts")
+
+
+def test_tree_at_its_size_limits():
+    """The largest tree the entry point takes: 2048 nodes (a root over 2047 one-context nodes), and a
+    chain of the maximum depth above a node with 300 contexts."""
+    n = B.APE_TREE_MAX_NODES - 1
+    spec = W.CONFIGS[1].replace(chunk_lens=tuple(1 + i % 3 for i in range(n)), q_len=2, decode_steps=1)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    nodes = W.tree_per_context(n, 0.9)
+    assert len(nodes) == B.APE_TREE_MAX_NODES
+    _check_tree(spec, r, h, nodes, spec.q_len, spec.q_len, what="2048 nodes, fp32")
+    spec = W.CONFIGS[2].replace(chunk_lens=tuple(1 + i % 3 for i in range(n)), q_len=1, decode_steps=1, k_scale=1.0)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_tree(spec, r, h, nodes, 1, 2, what="2048 nodes, bf16 decode")
+    _check_tree(spec, r, h, nodes, 1, 1, what="2048 nodes, bf16 one row")
+    spec = W.CONFIGS[2].replace(chunk_lens=(40,) * 300, q_len=33, decode_steps=0)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    chain = [(0.97, i + 1, 1, False) for i in range(B.APE_TREE_MAX_DEPTH - 1)] + [(0.9, 0, 300, True)]
+    _check_tree(spec, r, h, chain, spec.q_len, spec.q_len, what="depth 16 over 300 contexts")
