@@ -176,6 +176,12 @@ def main():
         "prefill": {"ms": float(ms_pre), "tflops": fl_pre / (ms_pre * 1e-3) / 1e12, "frac_mfma_peak": fl_pre / (ms_pre * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                     "note": "flash kernel + merge kernel"},
     }
+    # the same prefill call looped on its own (inside the step it follows the encode, under which the
+    # chip runs at lower clocks)
+    ms_pre_alone = timed(lambda: B.attention_prefill(shape, req, q, out, None, ws), 100)
+    phases["prefill_looped_alone"] = {"ms": ms_pre_alone, "tflops": fl_pre / (ms_pre_alone * 1e-3) / 1e12,
+                                      "frac_mfma_peak": fl_pre / (ms_pre_alone * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                      "note": "the prefill call of the step, 100 calls back to back"}
     if args.decode_steps:
         phases["decode_128k_batch1"] = {"ms_per_token": float(ms_dec) / args.decode_steps,
                                         "gbs": by_dec / (ms_dec * 1e-3) / 1e9, "frac_hbm_peak": by_dec / (ms_dec * 1e-3) / 1e9 / PEAK_HBM_GBS,
