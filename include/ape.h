@@ -276,8 +276,10 @@ size_t ape_layer_workspace_bytes(const ape_shape *shape, int32_t hidden, int32_t
  *   a = ape_encode_chunks attention (prefix KV + own context, causal);  x1 = x + a Wo^T;
  *   y = x1 + (SiLU(g) * u) Wd^T with [g, u] = RMSNorm(x1) Wgate_up^T.
  * The four matrix products are rocBLAS GEMMs with fp32 accumulation (this entry point alone makes
- * the library keep state: one rocBLAS handle per device, created at the first call); everything
- * between them runs in this library's kernels.  Intermediate tensors have the dtype of the shape.
+ * the library keep state: one rocBLAS handle per device, created at the first call and bound to the
+ * call's stream, so calls on one device must not overlap in time from different host threads);
+ * everything between them runs in this library's kernels.  Intermediate tensors have the dtype of
+ * the shape.
  *
  *   x, y               DEVICE packed [M, hidden], M = cu_chunk_lens_host[n_chunks]; y may not alias x
  *   k_prefix, v_prefix DEVICE [prefix_len, n_kv_heads, d]: THIS layer's cached prefix KV (rotated)
