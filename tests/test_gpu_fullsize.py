@@ -104,3 +104,21 @@ def test_cfg5_batched_decode_all_outputs():
             ref, ref_lse, _ = H.oracle_prefill(h, 1, sl, rs[b].temperature, rs[b].scale)
             H.check_close(H.f64(out[b]), ref, "bf16", "cfg5 request %d step %d" % (b, step))
             assert np.abs(H.f64(lse[b]) - ref_lse).max() <= H.lse_tol("bf16")
+
+
+def test_long_chunks_take_the_wide_tile_encode_sampled():
+    """Chunks beyond 4096 tokens (the shape of the sequential-encoding comparator: few, long causal
+    chunks) run on the wide query tile with long fast stretches; sampled rows at chunk starts and
+    ends, tile edges and deep inside."""
+    spec = W.CONFIGS[3].replace(chunk_lens=(6000, 4500, 33), q_len=8, decode_steps=0)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    rng = np.random.default_rng(7)
+    o_ctx, lse_ctx, _, _ = H.run_encode(spec, r, with_prefix_rows=False)
+    m = spec.total_ctx_len
+    must = [0, 1, 63, 64, 65, 4095, 4096, 5999, 6000, 6001, 6063, 6064, 10499, 10500, 10501, m - 1, 3000, 8200]
+    pairs = _pairs(rng, m, spec.n_q_heads, 320, must_rows=must)
+    ref, ref_lse = H.oracle_encode(h, pairs=pairs)
+    H.check_close(_gather(o_ctx, pairs), ref, "bf16", "long chunks encode")
+    assert np.abs(_gather(lse_ctx, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(o_ctx.float()).all()
