@@ -82,9 +82,18 @@ struct Stream {
         if (rem == 0) next_segment();
     }
     APE_RING_FN void next_segment() {
+        const int run_before = run;
         run = 0;
         if (cu != nullptr) {
-            if (t < t1) open_ctx();
+            if (t < t1) {
+                // A context that starts exactly where the rows handed out so far end (a packed cache, or
+                // neighbouring pages) continues the run of full blocks: same stride, no causal index, so
+                // the blocks on either side of the boundary are indistinguishable to the compute side.
+                // (After a partial block run_before is 0 already.)
+                const char *k_end = k, *v_end = v;
+                open_ctx();
+                if (rem > 0 && k == k_end && v == v_end) run = run_before;
+            }
         } else if (nc > 0) {
             k = kc; v = vc; rem = nc; nc = 0; j0 = 0; jstep = BLK;
         }

@@ -169,6 +169,9 @@ int main() {
     // context streams: ranges of the pooled contexts through a chunk table
     const std::vector<std::vector<int>> tables = {{64, 64}, {100, 1, 65, 300, 31}, {2048, 2048, 2048, 2048}, {257, 255}, {512, 512, 512}, {130},
                                                   {32, 0, 0, 64, 1, 0, 33}, {256, 256, 256, 256, 256, 256, 256, 256}, {1, 1, 1, 1, 1}};
+    // gap 0: the contexts lie back to back (a packed cache), where a run of full blocks continues
+    // across context boundaries; otherwise they are apart
+    for (long gap : {8192L, 0L})
     for (size_t v = 0; v < tables.size(); ++v) {
         const std::vector<int>& lens = tables[v];
         std::vector<int32_t> cu(1, 0);
@@ -176,7 +179,7 @@ int main() {
         std::vector<const void*> kc, vc;
         std::vector<std::pair<const char*, const char*>> valid;
         long off = 0;
-        for (int l : lens) { kc.push_back(base + off); vc.push_back(base + (1 << 25) + off); valid.push_back({base + off, base + off + (long)l * stride_b}); off += (long)l * stride_b + 8192; }
+        for (int l : lens) { kc.push_back(base + off); vc.push_back(base + (1 << 25) + off); valid.push_back({base + off, base + off + (long)l * stride_b}); off += (long)l * stride_b + gap; }
         const int total = cu.back();
         for (int split_len : {64, 128, 320, 1024, 8192})
             for (int t0 = 0; t0 < total; t0 += split_len) {
