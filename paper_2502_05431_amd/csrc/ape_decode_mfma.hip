@@ -143,7 +143,8 @@ struct Stream {
     const void* const* v_chunks;
     int n_chunks;
     int t, te, c0, c1;
-    int c;
+    int c, c_loaded;                   // c_loaded: the chunk whose base pointers kc, vc hold (-1: none)
+    const char *kc, *vc;
     const char *k0, *v0, *k1, *v1;    // plain segments
     int n0, n1;
     int seg, j;
@@ -153,6 +154,7 @@ struct Stream {
         cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
         t = (int)t_; te = (int)te_; stride_b = stride_b_; head_b = head_b_; c = 0; c0 = 0; c1 = 0;
         seg = 2; j = 0; n0 = n1 = 0; k0 = v0 = k1 = v1 = nullptr;
+        c_loaded = -1; kc = vc = nullptr;
         if (t < te) {
             int lo = 0, hi = n_chunks - 1;
             while (lo < hi) {
@@ -168,7 +170,7 @@ struct Stream {
         cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = 0; c = 0; c0 = c1 = 0;
         t = te = 0; stride_b = stride_b_; head_b = 0;
         k0 = k0_; v0 = v0_; n0 = n0_; k1 = k1_; v1 = v1_; n1 = n1_;
-        seg = 0; j = 0;
+        seg = 0; j = 0; c_loaded = -1; kc = vc = nullptr;
     }
     __device__ bool next(const char*& kb, const char*& vb, int& nv) {
         if (cu) {
@@ -179,8 +181,13 @@ struct Stream {
             }
             const int e = c1 < te ? c1 : te;
             nv = e - t < BT ? e - t : BT;
-            kb = (const char*)scalar_load_ptr(k_chunks + c) + (long)(t - c0) * stride_b + head_b;
-            vb = (const char*)scalar_load_ptr(v_chunks + c) + (long)(t - c0) * stride_b + head_b;
+            if (c != c_loaded) {                                    // the table is read once per chunk, not per tile
+                kc = (const char*)scalar_load_ptr(k_chunks + c) + head_b;
+                vc = (const char*)scalar_load_ptr(v_chunks + c) + head_b;
+                c_loaded = c;
+            }
+            kb = kc + (long)(t - c0) * stride_b;
+            vb = vc + (long)(t - c0) * stride_b;
             t += nv;
             return true;
         }
