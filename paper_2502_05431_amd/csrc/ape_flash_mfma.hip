@@ -29,6 +29,7 @@
 #define APE_RING_FN __device__ __forceinline__
 #define ape_ring_load_i32 ::ape::scalar_load_i32
 #define ape_ring_load_ptr ::ape::scalar_load_ptr
+#define ape_ring_load_chunk ::ape::scalar_load_chunk
 #include "ape_ring.h"
 
 #include <math.h>

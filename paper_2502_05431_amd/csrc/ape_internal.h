@@ -200,6 +200,17 @@ __device__ __forceinline__ void ctx_split_range(const QueryArgs& a, const KvView
     t1 = scalar_load_i32(a.split_ranges + 2 * split + 1);
 }
 
+// One chunk-table entry in a single round trip: cu[c + 1] and the K and V base pointers of chunk c
+// (three scalar loads issued back to back, one wait).
+__device__ __forceinline__ void scalar_load_chunk(const int32_t* cu_next, const void* const* kp, const void* const* vp,
+                                                  int32_t& c1, const void*& k, const void*& v) {
+    uint64_t kk, vv;
+    asm volatile("s_load_dword %0, %3, 0x0\n\ts_load_dwordx2 %1, %4, 0x0\n\ts_load_dwordx2 %2, %5, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(c1), "=&s"(kk), "=&s"(vv)
+                 : "s"(uniform_address(cu_next)), "s"(uniform_address(kp)), "s"(uniform_address(vp)) : "memory");
+    k = (const void*)kk; v = (const void*)vv;
+}
+
 template <typename Args>
 __device__ __forceinline__ KvView load_view(int rq) {
     auto ap = kernarg<Args>();

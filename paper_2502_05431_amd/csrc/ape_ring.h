@@ -7,7 +7,7 @@
 // body never meets a block that needs a mask.
 //
 // The includer defines APE_RING_FN (function qualifiers) and the two table readers
-// ape_ring_load_i32 / ape_ring_load_ptr (scalar loads on the GPU, plain reads on the host).
+// ape_ring_load_i32 / ape_ring_load_ptr / ape_ring_load_chunk (scalar loads on the GPU, plain reads on the host).
 #pragma once
 #include <stdint.h>
 
@@ -48,13 +48,18 @@ struct Stream {
 
     // Opens the segment that starts at pooled index t (t < t1).
     APE_RING_FN void open_ctx() {
-        while (t >= c1) {                                          // skip empty chunks
+        const void *kb = nullptr, *vb = nullptr;
+        bool have = false;
+        while (t >= c1) {                                          // the next chunk, skipping empty ones
             if (c + 1 >= n_chunks) return;                         // table shorter than total_ctx: stop, stay in bounds
-            ++c; c0 = c1; c1 = ape_ring_load_i32(cu + c + 1);
+            ++c; c0 = c1;
+            ape_ring_load_chunk(cu + c + 1, k_chunks + c, v_chunks + c, c1, kb, vb);   // one round trip per chunk
+            have = true;
         }
+        if (!have) { kb = ape_ring_load_ptr(k_chunks + c); vb = ape_ring_load_ptr(v_chunks + c); }
         const long off = (long)(t - c0) * stride_b + head_b;
-        k = (const char*)ape_ring_load_ptr(k_chunks + c) + off;
-        v = (const char*)ape_ring_load_ptr(v_chunks + c) + off;
+        k = (const char*)kb + off;
+        v = (const char*)vb + off;
         const int e = c1 < t1 ? c1 : t1;
         rem = e - t; t = e;
     }

@@ -20,6 +20,9 @@
 #define APE_RING_FN inline
 static inline int32_t ape_ring_load_i32(const int32_t* p) { return *p; }
 static inline const void* ape_ring_load_ptr(const void* const* p) { return *p; }
+static inline void ape_ring_load_chunk(const int32_t* cu_next, const void* const* kp, const void* const* vp, int32_t& c1, const void*& k, const void*& v) {
+    c1 = *cu_next; k = *kp; v = *vp;
+}
 #include "../paper_2502_05431_amd/csrc/ape_ring.h"
 
 using namespace ape;
