@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--tree-variants", action="store_true",
                     help="also time the query prefill and one decode step of the same 128K cache through the tree "
                          "entry point: one pooled node, a scaling factor per context, and a two-level tree")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time encode, query prefill and one decode step of the other bf16 configurations "
+                         "(2: RAG-shaped 20 x 512; 4: many-shot 512 x 256), each call looped on its own")
     ap.add_argument("--layer", action="store_true",
                     help="also time one whole Llama-3-8B-shaped layer (hidden 4096, MLP 14336, random weights) of the "
                          "context pre-caching pass over the same 64 x 2048 contexts")
@@ -238,6 +241,41 @@ def main():
                             "node are attended in splits of their own and the tree merge replaces the two-group merge" % ms_pre)
         del ws_t
 
+    cfg_res = None
+    if args.all_configs:
+        cfg_res = {}
+        for cfg in (2, 4):
+            sp = W.CONFIGS[cfg]
+            rr = W.make_request(sp, dev)
+            cu_c = [0]
+            for li in rr.chunk_lens:
+                cu_c.append(cu_c[-1] + li)
+            cu_c_dev = torch.tensor(cu_c, dtype=torch.int32, device=dev)
+            kc_, vc_ = rr.chunk_views()
+            rq = B.Request(rr.k_prefix, rr.v_prefix, kc_, vc_, rr.k_self, rr.v_self, sp.q_len, rr.temperature, rr.scale)
+            oc = torch.empty_like(rr.q_ctx)
+            qq = rr.q_self[:sp.q_len].contiguous()
+            oo = torch.empty_like(qq)
+            q1 = rr.q_self[sp.q_len:sp.q_len + 1].contiguous()
+            o1 = torch.empty_like(q1)
+            wsc = torch.empty(max(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, sp.q_len),
+                                  B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1)) // 4, dtype=torch.float32, device=dev)
+            fn_dec, arr_dec = B.decode_call(shape, [rq], q1, o1, None, wsc)
+            arr_dec[0].self_len = sp.q_len + 1
+            ms_e = timed(lambda: B.encode_chunks(shape, None, rr.k_prefix, rr.v_prefix, rr.q_ctx, rr.k_ctx, rr.v_ctx, cu_c, cu_c_dev, None, oc), 50)
+            ms_p = timed(lambda: B.attention_prefill(shape, rq, qq, oo, None, wsc), 100)
+            ms_d = timed(fn_dec, 200)
+            e_pairs, p_pairs = pair_counts(sp)
+            kv_tok = sp.prefix_len + sp.total_ctx_len + sp.q_len + 1
+            enc_bytes = 2.0 * (2 * rr.q_ctx.numel() + rr.k_ctx.numel() + rr.v_ctx.numel())       # Q read, O written, K and V read
+            cfg_res[sp.name] = {
+                "encode_ms": ms_e, "encode_tflops": 4.0 * d * hq * e_pairs / (ms_e * 1e-3) / 1e12,
+                "encode_hbm_gbs": enc_bytes / (ms_e * 1e-3) / 1e9,
+                "prefill_ms": ms_p, "prefill_tflops": 4.0 * d * hq * p_pairs / (ms_p * 1e-3) / 1e12,
+                "decode_ms_per_token": ms_d, "decode_gbs": (kv_row_bytes * kv_tok) / (ms_d * 1e-3) / 1e9,
+                "shape": "%d chunks x %d, prefix %d, %d query rows" % (len(sp.chunk_lens), sp.chunk_lens[0], sp.prefix_len, sp.q_len)}
+            del rr, rq, oc, wsc
+
     layer_res = None
     if args.layer:
         hidden, inter = 4096, 14336
@@ -399,6 +437,8 @@ def main():
         line["prefill_batch"] = batch_res
     if layer_res is not None:
         line["layer_encode"] = layer_res
+    if cfg_res is not None:
+        line["other_configs"] = cfg_res
     print(json.dumps(line))
 
 
