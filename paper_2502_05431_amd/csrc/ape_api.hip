@@ -93,8 +93,8 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
 QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) {
     const int rows = q_len * si.group;
     const long units = (long)batch * q_len * si.hq;
-    const int base = si.mfma ? batch * si.hkv * ceil_div(rows, flash_block_rows(rows)) : (int)units;
-    return plan_query(base, max_ctx, 256, si.mfma ? 256 : 1024);
+    const int base = si.mfma ? batch * si.hkv * ceil_div(rows, flash_prefill_block_rows(rows, max_ctx)) : (int)units;
+    return plan_query(base, max_ctx, 256, si.mfma ? flash_prefill_target_workgroups(max_ctx) : 1024);
 }
 
 // Splits of the tree entry point: the contexts of every node that holds contexts are cut into

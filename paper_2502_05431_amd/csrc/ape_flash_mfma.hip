@@ -852,10 +852,25 @@ hipError_t launch_encode_g(int group, const EncodeArgs& a, unsigned grid, int n_
 
 int flash_block_rows(int rows_per_kv_head) { return rows_per_kv_head > 128 ? 256 : 128; }
 
+// Query prefill: over a short context a workgroup's stream is a few dozen blocks, and what it spends
+// around them (descriptor and table reads, first loads, the partial results it writes and the merge
+// reads back) weighs as much as the blocks; the narrow tile then wins because two of its workgroups
+// share a CU and because half as many splits reach the same number of workgroups.  Measured with 256
+// query rows (64 tokens x 4 heads per KV head give the same picture): 2.5K context 0.047 against
+// 0.064 ms, 10K 0.078 / 0.089, 16K 0.102 / 0.113, 32K 0.160 / 0.168, 48K 0.229 / 0.232, 64K equal, 128K
+// 0.537 / 0.527.  Up to 12K tokens one narrow workgroup per CU is enough, beyond that two.
+int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx) {
+    if (max_ctx <= 40960) return 128;
+    return flash_block_rows(rows_per_kv_head);
+}
+int flash_prefill_target_workgroups(long max_ctx) { return max_ctx > 12288 && max_ctx <= 40960 ? 512 : 256; }
+
 hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
     const int rows = a.q_len * group;
-    const int bm = flash_block_rows(rows);
+    long max_ctx = 0;
+    for (int i = 0; i < a.n_req; ++i) max_ctx = a.req[i].total_ctx > max_ctx ? a.req[i].total_ctx : max_ctx;
+    const int bm = flash_prefill_block_rows(rows, max_ctx);
     const int n_qtiles = (rows + bm - 1) / bm;
     const int ctx_teams = a.n_ctx_splits * a.n_kv_heads;
     // x is a multiple of 8, so the workgroups of every request start on the same XCD phase

@@ -250,5 +250,9 @@ hipError_t launch_decode_mfma(const QueryArgs& a, hipStream_t s);       // bf16,
 
 // rows of (token, group-head) pairs one flash workgroup covers for a given amount of rows
 int flash_block_rows(int rows_per_kv_head);
+// the same for the query prefill, which also looks at the context length (see the definition), and
+// the number of workgroups its split plan aims at
+int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx);
+int flash_prefill_target_workgroups(long max_ctx);
 
 }  // namespace ape

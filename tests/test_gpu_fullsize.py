@@ -122,3 +122,26 @@ def test_long_chunks_take_the_wide_tile_encode_sampled():
     H.check_close(_gather(o_ctx, pairs), ref, "bf16", "long chunks encode")
     assert np.abs(_gather(lse_ctx, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
     assert torch.isfinite(o_ctx.float()).all()
+
+
+@pytest.mark.parametrize("chunk_lens, q_len, self_extra", [
+    ((20000, 1, 13000, 333, 9000, 64, 31), 50, 0),        # just above the switch; 200 ragged rows on one wide tile
+    ((12000, 0, 12000, 12000, 6999, 3), 130, 70),         # three wide tiles, the last ragged; long own span
+    ((40960,), 50, 0),                                    # the last context length on the narrow tile
+    ((40961,), 50, 0),                                    # the first one on the wide tile
+])
+def test_prefill_tile_switch_by_context_length_sampled(chunk_lens, q_len, self_extra):
+    """The query prefill takes the narrow query tile up to 40960 context tokens and the wide one
+    beyond (when a KV head has more than 128 query rows): ragged contexts on both sides of the
+    switch, sampled rows at tile edges."""
+    spec = W.CONFIGS[3].replace(chunk_lens=chunk_lens, q_len=q_len, prefix_len=7, decode_steps=self_extra, k_scale=1.0)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    rng = np.random.default_rng(11)
+    self_len = q_len + self_extra
+    out, lse = H.run_prefill(spec, r, q_len, self_len)
+    pairs = _pairs(rng, q_len, spec.n_q_heads, 192, must_rows=(31, 32, 33, 63, 64, 65, 127, 128))
+    ref, ref_lse, _ = H.oracle_prefill(h, q_len, self_len, r.temperature, r.scale, pairs=pairs)
+    H.check_close(_gather(out, pairs), ref, "bf16", "prefill %s" % (chunk_lens,))
+    assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(out.float()).all()
