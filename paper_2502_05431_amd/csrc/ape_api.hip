@@ -75,7 +75,7 @@ KvView to_view(const ape_request* r) {
 // Number of context splits: enough workgroups to fill 256 CUs a few times over, never more than
 // kMaxSplits, never splits shorter than `min_len` tokens.  Depends on sizes only.
 QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_workgroups) {
-    QueryPlan p;
+    QueryPlan p{};
     if (max_ctx <= 0) { p.n_ctx_splits = 0; p.ctx_split_len = 64; p.n_splits_total = 1; return p; }
     int want = ceil_div(target_workgroups, base_workgroups > 0 ? base_workgroups : 1);
     int cap = ceil_div(max_ctx, min_len);
@@ -93,8 +93,11 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
 QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) {
     const int rows = q_len * si.group;
     const long units = (long)batch * q_len * si.hq;
-    const int base = si.mfma ? batch * si.hkv * ceil_div(rows, flash_prefill_block_rows(rows, max_ctx)) : (int)units;
-    return plan_query(base, max_ctx, 256, si.mfma ? flash_prefill_target_workgroups(max_ctx) : 1024);
+    const int bm = si.mfma ? flash_prefill_block_rows(rows, max_ctx) : 0;
+    const int base = si.mfma ? batch * si.hkv * ceil_div(rows, bm) : (int)units;
+    QueryPlan p = plan_query(base, max_ctx, 256, si.mfma ? flash_prefill_target_workgroups(max_ctx) : 1024);
+    p.block_rows = bm;
+    return p;
 }
 
 // Splits of the tree entry point: the contexts of every node that holds contexts are cut into
@@ -104,6 +107,7 @@ QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) 
 struct TreePlan {
     int len;
     int max_splits;
+    int block_rows;        // query tile of the flash prefill (see QueryPlan)
     size_t partial_bytes, plan_bytes;
 };
 
@@ -113,6 +117,7 @@ TreePlan plan_tree(const ShapeInfo& si, long total_ctx, int n_nodes, int q_len) 
     else qp = prefill_plan(si, 1, q_len, total_ctx);
     TreePlan p;
     p.len = qp.ctx_split_len;
+    p.block_rows = qp.block_rows;
     p.max_splits = ceil_div(total_ctx > 0 ? total_ctx : 1, p.len) + n_nodes;
     const long units = (long)q_len * si.hq;
     p.partial_bytes = align_up((size_t)units * (p.max_splits + 1) * si.d * sizeof(float), kWsAlign) +
@@ -298,7 +303,7 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         a.n_ctx_splits = plan.n_ctx_splits; a.ctx_split_len = plan.ctx_split_len;
         a.units_total = (int)units; a.req_base = b0;
         hipError_t he;
-        if (si.mfma) he = decode ? launch_decode_mfma(a, st) : launch_flash_prefill(a, st);
+        if (si.mfma) he = decode ? launch_decode_mfma(a, st) : launch_flash_prefill(a, plan.block_rows, st);
         else he = launch_generic_query(a, si.dtype, st);
         if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
 
@@ -397,7 +402,7 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     a.n_ctx_splits = plan.max_splits; a.ctx_split_len = plan.len;
     a.split_ranges = plan_dev + TreePlanLayout{n_nodes, plan.max_splits}.ranges_at();
     a.units_total = (int)units; a.req_base = 0;
-    if (si.mfma) he = q_len == 1 ? launch_decode_mfma(a, st) : launch_flash_prefill(a, st);
+    if (si.mfma) he = q_len == 1 ? launch_decode_mfma(a, st) : launch_flash_prefill(a, plan.block_rows, st);
     else he = launch_generic_query(a, si.dtype, st);
     if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
 

@@ -865,12 +865,10 @@ int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx) {
 }
 int flash_prefill_target_workgroups(long max_ctx) { return max_ctx > 12288 && max_ctx <= 40960 ? 512 : 256; }
 
-hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s) {
+hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
     const int rows = a.q_len * group;
-    long max_ctx = 0;
-    for (int i = 0; i < a.n_req; ++i) max_ctx = a.req[i].total_ctx > max_ctx ? a.req[i].total_ctx : max_ctx;
-    const int bm = flash_prefill_block_rows(rows, max_ctx);
+    const int bm = block_rows == 256 ? 256 : 128;
     const int n_qtiles = (rows + bm - 1) / bm;
     const int ctx_teams = a.n_ctx_splits * a.n_kv_heads;
     // x is a multiple of 8, so the workgroups of every request start on the same XCD phase

@@ -230,6 +230,7 @@ struct QueryPlan {
     int n_ctx_splits;
     int ctx_split_len;
     int n_splits_total;
+    int block_rows;        // query tile of the flash prefill this plan was made for (0: not a flash prefill)
 };
 
 // ---- launchers (each returns hipGetLastError() of its launch) ------------------------------
@@ -244,7 +245,7 @@ int gemm_xwT(const void* x, long ldx, const void* w, const void* residual, void*
              int dtype, hipStream_t s);
 hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s);
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
-hipError_t launch_flash_prefill(const QueryArgs& a, hipStream_t s);     // bf16, d = 128
+hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t s);     // bf16, d = 128; block_rows from the plan
 hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s);     // bf16, d = 128
 hipError_t launch_decode_mfma(const QueryArgs& a, hipStream_t s);       // bf16, d = 128, q_len = 1
 
