@@ -203,9 +203,11 @@ __global__ __launch_bounds__(kWave) void generic_encode_kernel(const EncodeArgs 
 // then share out the splits, each accumulating its weighted rows with several loads in flight,
 // and are combined through LDS.  (A serial loop over 64 splits cost 61 us at batch 1.)
 constexpr int kMergeWaves = 4;
+constexpr int kMergeWavesFew = 16;
 
 // One group of splits [s0, s1): this wavefront's share of sum_s w_s o_s into acc (lane owns dims
 // lane + 64 r), with w_s = exp(lse_s - max); returns the group's max and sum of weights.
+template <int W>
 __device__ __forceinline__ void merge_group(const MergeArgs& a, long gunit, int s0, int s1, int wave, int lane,
                                             float (&acc)[kMaxDimRegs], float& m_out, float& z_out) {
     const int d = a.head_dim;
@@ -220,11 +222,11 @@ __device__ __forceinline__ void merge_group(const MergeArgs& a, long gunit, int 
             z += w_mine;
             const int cnt = min(kWave, s1 - c0);
             constexpr int UN = 4;                                       // rows in flight per wavefront
-            for (int i = wave; i < cnt; i += UN * kMergeWaves) {
+            for (int i = wave; i < cnt; i += UN * W) {
                 float w[UN], v[UN][kMaxDimRegs];
 #pragma unroll
                 for (int u = 0; u < UN; ++u) {
-                    const int ii = i + u * kMergeWaves;
+                    const int ii = i + u * W;
                     w[u] = ii < cnt ? __shfl(w_mine, min(ii, kWave - 1)) : 0.f;
                     const float* o = a.part_o + ((long)(c0 + min(ii, cnt - 1)) * a.units_total + gunit) * d;
 #pragma unroll
@@ -244,9 +246,13 @@ __device__ __forceinline__ void merge_group(const MergeArgs& a, long gunit, int 
     m_out = m; z_out = z;
 }
 
-template <typename T>
-__global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeArgs a) {
-    __shared__ float part[2][kMergeWaves][kWave * kMaxDimRegs];
+// W wavefronts per unit: kMergeWaves when there are many units (the launch is then bound by its
+// traffic), kMergeWavesFew for a few units with many splits each (decode of a long context at a small
+// batch: 32 units x 64 splits), where the time is a chain of round trips and W x 4 rows in flight
+// cover all splits in one of them.
+template <typename T, int W>
+__global__ __launch_bounds__(kWave * W) void merge_kernel(const MergeArgs a) {
+    __shared__ float part[2][W][kWave * kMaxDimRegs];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int unit = blockIdx.x;                                    // within this launch
     const int d = a.head_dim, hq = a.n_q_heads;
@@ -262,8 +268,8 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeA
     // batch leaves the trailing splits untouched)
     const int tc = kernarg<MergeArgs>()->total_ctx[rq];
     const int n_ctx = min(a.n_ctx_splits, (tc + a.ctx_split_len - 1) / a.ctx_split_len);
-    merge_group(a, gunit, 0, n_ctx, wave, lane, acc_c, mc, zc);
-    merge_group(a, gunit, a.n_ctx_splits, a.n_splits_total, wave, lane, acc_o, mo, zo);   // prefix + self: never empty
+    merge_group<W>(a, gunit, 0, n_ctx, wave, lane, acc_c, mc, zc);
+    merge_group<W>(a, gunit, a.n_ctx_splits, a.n_splits_total, wave, lane, acc_o, mo, zo);   // prefix + self: never empty
 #pragma unroll
     for (int r = 0; r < kMaxDimRegs; ++r) {
         part[0][wave][lane + kWave * r] = acc_c[r];
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void merge_kernel(const MergeA
     for (int r = 0; r < kMaxDimRegs; ++r) {
         acc_c[r] = 0.f; acc_o[r] = 0.f;
 #pragma unroll
-        for (int w = 0; w < kMergeWaves; ++w) { acc_c[r] += part[0][w][lane + kWave * r]; acc_o[r] += part[1][w][lane + kWave * r]; }
+        for (int w = 0; w < W; ++w) { acc_c[r] += part[0][w][lane + kWave * r]; acc_o[r] += part[1][w][lane + kWave * r]; }
     }
     const float lse_c = mc > -INFINITY ? mc + logf(zc) : -INFINITY;   // log Z_ctx
     const float inv_zc = zc > 0.f ? 1.f / zc : 0.f;
@@ -552,8 +558,14 @@ hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s) 
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
     dim3 grid((unsigned)(a.n_req * a.q_len * a.n_q_heads));
-    if (a.dtype == APE_F32) merge_kernel<float><<<grid, kWave * kMergeWaves, 0, s>>>(a);
-    else merge_kernel<__bf16><<<grid, kWave * kMergeWaves, 0, s>>>(a);
+    const bool few = a.n_ctx_splits >= 32 && (long)grid.x * a.n_splits_total <= 4096;
+    if (a.dtype == APE_F32) {
+        if (few) merge_kernel<float, kMergeWavesFew><<<grid, kWave * kMergeWavesFew, 0, s>>>(a);
+        else merge_kernel<float, kMergeWaves><<<grid, kWave * kMergeWaves, 0, s>>>(a);
+    } else {
+        if (few) merge_kernel<__bf16, kMergeWavesFew><<<grid, kWave * kMergeWavesFew, 0, s>>>(a);
+        else merge_kernel<__bf16, kMergeWaves><<<grid, kWave * kMergeWaves, 0, s>>>(a);
+    }
     return hipGetLastError();
 }
 

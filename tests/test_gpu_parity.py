@@ -81,6 +81,18 @@ def test_fp32_ragged_and_degenerate():
         _check_decode(spec, r, h, spec.self_len_max, what=what)
 
 
+def test_decode_of_a_long_context_at_batch_one_merges_many_splits():
+    """One request, one query row and thousands of context tokens: the planner cuts the context into
+    32 or more splits for a handful of (row, head) units, and the merge then runs its many-wavefront
+    variant (fp32 and bf16, ragged contexts so that the last split is short)."""
+    for cfg, generic in ((1, False), (2, True)):
+        spec = W.CONFIGS[cfg].replace(chunk_lens=(3000, 1, 2500, 2700, 37), q_len=1, decode_steps=3)
+        r = W.make_request(spec, DEV)
+        h = H.HostArrays(r)
+        for sl in (1, 4):
+            _check_decode(spec, r, h, sl, generic=generic, what="cfg%d many splits self_len %d" % (cfg, sl))
+
+
 # ------------------------------------------------------------------ bf16, generic kernels
 def test_bf16_generic_small():
     spec = W.CONFIGS[1].replace(dtype="bf16", chunk_lens=(33, 64, 7), q_len=20)
