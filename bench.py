@@ -174,11 +174,14 @@ def main():
     by_dec = sum(kv_row_bytes * t + 2 * hq * d * 2 for t in dec_tokens)
     value = (fl_enc + fl_pre + fl_dec) / (ms_step * 1e-3) / 1e12
 
+    ms_med, ms_min = np.median(ph, axis=0), ph.min(axis=0)
     phases = {
         "encode": {"ms": float(ms_enc), "tflops": fl_enc / (ms_enc * 1e-3) / 1e12, "frac_mfma_peak": fl_enc / (ms_enc * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         "prefill": {"ms": float(ms_pre), "tflops": fl_pre / (ms_pre * 1e-3) / 1e12, "frac_mfma_peak": fl_pre / (ms_pre * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                     "note": "flash kernel + merge kernel"},
     }
+    for i, name in enumerate(("encode", "prefill")):
+        phases[name]["ms_median"], phases[name]["ms_min"] = float(ms_med[i]), float(ms_min[i])
     # the same prefill call looped on its own (inside the step it follows the encode, under which the
     # chip runs at lower clocks)
     ms_pre_alone = timed(lambda: B.attention_prefill(shape, req, q, out, None, ws), 100)
@@ -188,6 +191,8 @@ def main():
     if args.decode_steps:
         phases["decode_128k_batch1"] = {"ms_per_token": float(ms_dec) / args.decode_steps,
                                         "gbs": by_dec / (ms_dec * 1e-3) / 1e9, "frac_hbm_peak": by_dec / (ms_dec * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                        "ms_per_token_median": float(ms_med[2]) / args.decode_steps,
+                                        "ms_per_token_min": float(ms_min[2]) / args.decode_steps,
                                         "note": "538 MB of KV per token, batch 1"}
 
     # the kernel that dominates the step
@@ -274,6 +279,29 @@ def main():
                 "prefill_ms": ms_p, "prefill_tflops": 4.0 * d * hq * p_pairs / (ms_p * 1e-3) / 1e12,
                 "decode_ms_per_token": ms_d, "decode_gbs": (kv_row_bytes * kv_tok) / (ms_d * 1e-3) / 1e9,
                 "shape": "%d chunks x %d, prefix %d, %d query rows" % (len(sp.chunk_lens), sp.chunk_lens[0], sp.prefix_len, sp.q_len)}
+            if kv_row_bytes * kv_tok < 128e6:
+                # a cache this small stays in the last-level cache when one call is looped: rotate over
+                # copies of the request that together exceed it (16 x 42 MB against 256 MB), so that
+                # every call reads its KV from HBM
+                n_rot = 16
+                rot = []
+                for i in range(n_rot):
+                    ri = W.make_request(sp, dev, run_index=i + 1)
+                    ki, vi = ri.chunk_views()
+                    rqi = B.Request(ri.k_prefix, ri.v_prefix, ki, vi, ri.k_self, ri.v_self, sp.q_len, ri.temperature, ri.scale)
+                    fi, ai = B.decode_call(shape, [rqi], q1, o1, None, wsc)
+                    ai[0].self_len = sp.q_len + 1
+                    rot.append((fi, ai, ri, rqi))
+
+                def rotated():
+                    for fi, _, _, _ in rot:
+                        fi()
+                ms_rot = timed(rotated, 20) / n_rot
+                cfg_res[sp.name]["decode_note"] = "one call looped: its %.0f MB of KV stay in the last-level cache" % (kv_row_bytes * kv_tok / 1e6)
+                cfg_res[sp.name]["decode_rotated_ms_per_token"] = ms_rot
+                cfg_res[sp.name]["decode_rotated_gbs"] = (kv_row_bytes * kv_tok) / (ms_rot * 1e-3) / 1e9
+                cfg_res[sp.name]["decode_rotated_note"] = "%d copies of the request in turn (%.0f MB): every call reads from HBM" % (n_rot, n_rot * kv_row_bytes * kv_tok / 1e6)
+                del rot
             del rr, rq, oc, wsc
 
     layer_res = None
