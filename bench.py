@@ -76,6 +76,10 @@ def main():
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time torch's bf16 GEMM (the vendor library) on zero and on random operands: context "
                          "for the MFMA roofline, which on this chip depends on the operand data (power limit)")
+    ap.add_argument("--sdpa-reference", action="store_true",
+                    help="also time torch's scaled_dot_product_attention (the vendor's fused attention) on the two "
+                         "contractions of config 3: causal attention over 64 sequences of 2048 tokens (the encode without "
+                         "its shared prefix) and 256 query rows over 131K keys (the context group of the prefill)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings in a --pmc run)")
@@ -381,6 +385,34 @@ def main():
             gemm_ref["torch_bf16_gemm_8192_tflops_" + name] = 2.0 * n ** 3 / (ms_g * 1e-3) / 1e12
             del a_, b_
 
+    sdpa_ref = None
+    if args.sdpa_reference:
+        import torch.nn.functional as F
+        from torch.nn.attention import SDPBackend, sdpa_kernel
+        sdpa_ref = {}
+        n_ch, l_ch = len(spec.chunk_lens), spec.chunk_lens[0]
+        g = hq // hkv
+        # K and V heads repeated for the query heads (torch's fused kernels take equal head counts)
+        qe = r.q_ctx.view(n_ch, l_ch, hq, d).transpose(1, 2).contiguous()
+        ke = r.k_ctx.view(n_ch, l_ch, hkv, d).transpose(1, 2).repeat_interleave(g, dim=1).contiguous()
+        ve = r.v_ctx.view(n_ch, l_ch, hkv, d).transpose(1, 2).repeat_interleave(g, dim=1).contiguous()
+        qp = q.view(1, spec.q_len, hq, d).transpose(1, 2).contiguous()
+        kp, vp = ke.transpose(0, 1).reshape(1, hq, n_ch * l_ch, d), ve.transpose(0, 1).reshape(1, hq, n_ch * l_ch, d)
+        cases = (("encode_like_causal_%dx%d" % (n_ch, l_ch), lambda: F.scaled_dot_product_attention(qe, ke, ve, is_causal=True),
+                  4.0 * d * hq * n_ch * l_ch * (l_ch + 1) / 2),
+                 ("prefill_like_%d_rows_over_%d_keys" % (spec.q_len, n_ch * l_ch), lambda: F.scaled_dot_product_attention(qp, kp, vp),
+                  4.0 * d * hq * spec.q_len * n_ch * l_ch))
+        for name, fn, flops in cases:
+            try:
+                with sdpa_kernel([SDPBackend.FLASH_ATTENTION, SDPBackend.EFFICIENT_ATTENTION]):
+                    ms_s = timed(fn, 20)
+                sdpa_ref[name] = {"ms": ms_s, "tflops": flops / (ms_s * 1e-3) / 1e12}
+            except Exception as exc:                      # no fused kernel for this shape on this build of torch
+                sdpa_ref[name] = {"error": str(exc)[:200]}
+        sdpa_ref["note"] = ("torch.nn.functional.scaled_dot_product_attention, fused backends only, K/V heads repeated to 32; "
+                            "same flop convention (unmasked pairs only)")
+        del qe, ke, ve, qp, kp, vp
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -455,6 +487,8 @@ def main():
     }
     if gemm_ref is not None:
         line["gemm_reference"] = gemm_ref
+    if sdpa_ref is not None:
+        line["sdpa_reference"] = sdpa_ref
     if seq_cmp is not None:
         line["sequential_comparator"] = seq_cmp
     if tree_var is not None:
