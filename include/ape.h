@@ -33,6 +33,11 @@
  *     the host before anything is launched and leave all outputs untouched.
  *     ape_last_error() gives a thread-local description of the last failure.
  *   - LogSumExp outputs are natural-log, fp32.
+ *   - Size limits of one call (APE_ERR_UNSUPPORTED beyond, nothing launched): query calls write at
+ *     most 2^24 (row, head) outputs (batch x q_len x n_q_heads); an encode on the matrix-core path
+ *     launches contexts x n_kv_heads x ceil(longest context x heads-per-KV-head / 128) workgroups and
+ *     takes fewer than 2^24 of them, on the other paths fewer than 2^26 (row, head) outputs.  Token
+ *     counts are 32-bit (a call covers fewer than 2^31 tokens); byte offsets are 64-bit throughout.
  */
 #ifndef APE_H
 #define APE_H
@@ -47,7 +52,8 @@ extern "C" {
 typedef enum {
     APE_OK = 0,
     APE_ERR_INVALID_ARG = -1,   /* null pointer, bad length, T or S not finite and > 0, ...      */
-    APE_ERR_UNSUPPORTED = -2,   /* head_dim / head ratio / dtype the kernels do not cover         */
+    APE_ERR_UNSUPPORTED = -2,   /* head_dim / head ratio / dtype the kernels do not cover, or a   */
+                                /* call beyond the size limits above                              */
     APE_ERR_WORKSPACE = -3,     /* workspace missing or smaller than ape_workspace_bytes says     */
     APE_ERR_DEVICE = -4         /* HIP reported a launch error                                    */
 } ape_status;

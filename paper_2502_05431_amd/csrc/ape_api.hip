@@ -60,6 +60,26 @@ int check_request(const ape_request* r, int q_len, int idx) {
     return APE_OK;
 }
 
+// Launch sizes: a grid times its workgroup size must stay below 2^32 work items and every count the
+// kernels index with fits an int.  Calls beyond that are refused here, before any size is narrowed.
+constexpr long kMaxUnits = 1L << 24;            // (row, head) outputs of one query call: one 256-thread workgroup each in the merge
+constexpr long kMaxEncodeBlocks = 1L << 24;     // workgroups of the matrix-core encode (256 threads each)
+constexpr long kMaxEncodeUnits = 1L << 26;      // (row, head) outputs of the generic encode: one wavefront each
+
+int check_encode_size(const ShapeInfo& si, int n_chunks, int max_len, long total_rows) {
+    if (si.mfma) {
+        // as launch_flash_encode sizes its grid, for the narrower of its two query tiles
+        const long n_qtiles = ((long)max_len * si.group + 127) / 128;
+        const long blocks = ((long)n_chunks * si.hkv + 7) / 8 * 8 * n_qtiles;
+        if (blocks >= kMaxEncodeBlocks)
+            return fail(APE_ERR_UNSUPPORTED, "encode of %d contexts of up to %d tokens needs %ld workgroups, fewer than %ld are supported "
+                        "(the grid is contexts x KV heads x query tiles of the longest context: split the call)", n_chunks, max_len, blocks, kMaxEncodeBlocks);
+    } else if (total_rows * si.hq >= kMaxEncodeUnits) {
+        return fail(APE_ERR_UNSUPPORTED, "encode of %ld rows x %d heads on the generic path, fewer than %ld outputs are supported", total_rows, si.hq, kMaxEncodeUnits);
+    }
+    return APE_OK;
+}
+
 KvView to_view(const ape_request* r) {
     KvView v;
     v.k_prefix = r->k_prefix; v.v_prefix = r->v_prefix;
@@ -235,6 +255,12 @@ int ape_encode_chunks(const ape_shape* shape,
         }
         total = cu_host[n_chunks];
         if (total > 0 && (!q_chunks || !k_chunks || !v_chunks || !o_chunks)) return fail(APE_ERR_INVALID_ARG, "chunk Q/K/V/O is NULL");
+        rc = check_encode_size(si, n_chunks, max_len, total);
+        if (rc) return rc;
+    }
+    if (q_prefix && prefix_len > 0) {
+        rc = check_encode_size(si, 1, prefix_len, prefix_len);
+        if (rc) return rc;
     }
     hipStream_t st = (hipStream_t)stream;
 
@@ -272,6 +298,8 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         if (m > max_ctx) max_ctx = m;
     }
     const long units = (long)batch * q_len * si.hq;
+    if (units > kMaxUnits)
+        return fail(APE_ERR_UNSUPPORTED, "%d requests x %d rows x %d heads = %ld outputs in one call, at most %ld are supported", batch, q_len, si.hq, units, kMaxUnits);
     QueryPlan plan;
     if (decode) {
         // one workgroup per (request, KV head, split) on the matrix-core path
@@ -371,6 +399,8 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
     rc = check_request(req, q_len, 0);
     if (rc) return rc;
+    if ((long)q_len * si.hq > kMaxUnits)
+        return fail(APE_ERR_UNSUPPORTED, "%d rows x %d heads = %ld outputs in one call, at most %ld are supported", q_len, si.hq, (long)q_len * si.hq, kMaxUnits);
     TreeMergeArgs m{};
     rc = check_tree(nodes_host, n_nodes, req->n_chunks, &m.n_levels, m.level_start);
     if (rc) return rc;
@@ -512,6 +542,8 @@ int ape_layer_encode(const ape_shape* shape, const ape_layer_weights* w, const v
     const long rows = cu_host[n_chunks];
     if (rows == 0) return APE_OK;
     if (!x || !y || !k_cache || !v_cache) return fail(APE_ERR_INVALID_ARG, "x, y, k_cache and v_cache must not be NULL");
+    rc = check_encode_size(si, n_chunks, max_len, rows);
+    if (rc) return rc;
     const LayerPlan p = plan_layer(si, w->hidden, w->intermediate, rows);
     if (!workspace || workspace_bytes < p.total)
         return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_layer_workspace_bytes gives the size)", workspace_bytes, p.total);

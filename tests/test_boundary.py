@@ -1,6 +1,8 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
 public header declares, sizes workspaces, and rejects bad arguments before launching anything."""
 import ctypes
+
+import numpy as np
 import os
 import re
 
@@ -118,6 +120,33 @@ def test_decode_and_encode_argument_errors():
     assert enc(ctypes.cast(cu2, ctypes.c_void_p), None) == B.APE_ERR_INVALID_ARG       # no device copy
     assert enc(ctypes.cast(cu2, ctypes.c_void_p), FAKE, q_prefix=FAKE) == B.APE_ERR_INVALID_ARG   # q_prefix without o_prefix
     assert enc(ctypes.cast(cu2, ctypes.c_void_p), FAKE, prefix_len=-2) == B.APE_ERR_INVALID_ARG
+
+
+def test_size_limits_are_refused_before_any_launch():
+    """Calls whose grids would pass 2^32 work items, or whose counts would not fit the kernels' 32-bit
+    indices, return APE_ERR_UNSUPPORTED with a message that names the limit."""
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    # query prefill: 2^24 (row, head) outputs pass the check (and stop at the missing workspace), one row more does not
+    rows_ok = (1 << 24) // 32
+    assert _prefill(sh, _req(self_len=rows_ok), q_len=rows_ok) == B.APE_ERR_WORKSPACE
+    assert _prefill(sh, _req(self_len=rows_ok + 1), q_len=rows_ok + 1) == B.APE_ERR_UNSUPPORTED
+    assert b"outputs in one call" in lib.ape_last_error()
+    assert _tree([(0.9, 0, 4, 1)], req=_req(n_chunks=4, total_ctx_len=200, self_len=rows_ok + 1), q_len=rows_ok + 1) == B.APE_ERR_UNSUPPORTED
+    # encode on the matrix-core path: contexts x KV heads x query tiles of the longest context
+    n = 4096
+    lens = [1 << 17] + [1] * (n - 1)                      # one long context makes every context's share of the grid long
+    cu = (ctypes.c_int32 * (n + 1))(*np.concatenate([[0], np.cumsum(lens)]).tolist())
+    enc = lambda shape: lib.ape_encode_chunks(ctypes.byref(shape), None, FAKE, FAKE, 4, FAKE, FAKE, FAKE,
+                                              ctypes.cast(cu, ctypes.c_void_p), FAKE, n, None, FAKE, None, None, None, 0, None)
+    assert enc(sh) == B.APE_ERR_UNSUPPORTED
+    assert b"workgroups" in lib.ape_last_error()
+    # the generic path counts (row, head) outputs instead
+    cu2 = (ctypes.c_int32 * 2)(0, 1 << 22)
+    enc1 = lambda shape: lib.ape_encode_chunks(ctypes.byref(shape), None, FAKE, FAKE, 4, FAKE, FAKE, FAKE,
+                                               ctypes.cast(cu2, ctypes.c_void_p), FAKE, 1, None, FAKE, None, None, None, 0, None)
+    assert enc1(B.make_shape(32, 8, 128, B.APE_F32)) == B.APE_ERR_UNSUPPORTED
+    assert b"generic path" in lib.ape_last_error()
 
 
 def _tree(nodes, req=None, nodes_dev=FAKE, n_nodes=None, ws=None, ws_bytes=0, q_len=8):
