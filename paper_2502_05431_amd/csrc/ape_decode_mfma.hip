@@ -18,6 +18,11 @@
 // tile being computed; the four wavefronts of a workgroup combine their states in LDS at the end.
 #include "ape_internal.h"
 
+#define APE_STREAM_FN __device__ __forceinline__
+#define ape_stream_load_i32 ::ape::scalar_load_i32
+#define ape_stream_load_ptr ::ape::scalar_load_ptr
+#include "ape_decode_stream.h"
+
 #include <math.h>
 
 namespace ape {
@@ -31,7 +36,8 @@ constexpr int D = 128;
 constexpr int ROWB = D * 2;
 constexpr int NT = 256;
 constexpr int NW = NT / 64;
-constexpr int BT = 32;                         // tokens per wavefront tile
+static_assert(NW == kDecodeWaves, "the stream bookkeeping deals a split to four wavefronts");
+constexpr int BT = kDecodeTile;                // tokens per wavefront tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -134,78 +140,9 @@ __device__ __forceinline__ void accumulate_pv(const uint32_t (&v)[32], bf16x8 p,
     }
 }
 
-// One wavefront's token stream: up to two plain segments, or a range of the pooled contexts
-// walked through the chunk table.  next() yields tiles of <= 32 tokens that never straddle a
-// segment or chunk end.
-struct Stream {
-    const int32_t* cu;                 // non-NULL: context range [t, te) through the chunk table (scalar loads)
-    const void* const* k_chunks;
-    const void* const* v_chunks;
-    int n_chunks;
-    int t, te, c0, c1;
-    int c, c_loaded;                   // c_loaded: the chunk whose base pointers kc, vc hold (-1: none)
-    const char *kc, *vc;
-    const char *k0, *v0, *k1, *v1;    // plain segments
-    int n0, n1;
-    int seg, j;
-    long stride_b, head_b;
-
-    __device__ void init_ctx(const KvView& kv, long t_, long te_, long stride_b_, long head_b_) {
-        cu = kv.cu; k_chunks = kv.k_chunks; v_chunks = kv.v_chunks; n_chunks = kv.n_chunks;
-        t = (int)t_; te = (int)te_; stride_b = stride_b_; head_b = head_b_; c = 0; c0 = 0; c1 = 0;
-        seg = 2; j = 0; n0 = n1 = 0; k0 = v0 = k1 = v1 = nullptr;
-        c_loaded = -1; kc = vc = nullptr;
-        if (t < te) {
-            int lo = 0, hi = n_chunks - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (scalar_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
-            }
-            c = lo; c0 = scalar_load_i32(cu + c); c1 = scalar_load_i32(cu + c + 1);
-        } else {
-            te = t;
-        }
-    }
-    __device__ void init_plain(const char* k0_, const char* v0_, int n0_, const char* k1_, const char* v1_, int n1_, long stride_b_) {
-        cu = nullptr; k_chunks = v_chunks = nullptr; n_chunks = 0; c = 0; c0 = c1 = 0;
-        t = te = 0; stride_b = stride_b_; head_b = 0;
-        k0 = k0_; v0 = v0_; n0 = n0_; k1 = k1_; v1 = v1_; n1 = n1_;
-        seg = 0; j = 0; c_loaded = -1; kc = vc = nullptr;
-    }
-    __device__ bool next(const char*& kb, const char*& vb, int& nv) {
-        if (cu) {
-            if (t >= te) return false;
-            while (t >= c1) {
-                if (c + 1 >= n_chunks) { t = te; return false; }   // table shorter than total_ctx: stay in bounds
-                ++c; c0 = c1; c1 = scalar_load_i32(cu + c + 1);
-            }
-            const int e = c1 < te ? c1 : te;
-            nv = e - t < BT ? e - t : BT;
-            if (c != c_loaded) {                                    // the table is read once per chunk, not per tile
-                kc = (const char*)scalar_load_ptr(k_chunks + c) + head_b;
-                vc = (const char*)scalar_load_ptr(v_chunks + c) + head_b;
-                c_loaded = c;
-            }
-            kb = kc + (long)(t - c0) * stride_b;
-            vb = vc + (long)(t - c0) * stride_b;
-            t += nv;
-            return true;
-        }
-        if (seg == 0 && j >= n0) { seg = 1; j = 0; }
-        if (seg == 1 && j >= n1) seg = 2;
-        if (seg >= 2) return false;
-        const int n = seg == 0 ? n0 : n1;
-        nv = n - j < BT ? n - j : BT;
-        kb = (seg == 0 ? k0 : k1) + (long)j * stride_b;
-        vb = (seg == 0 ? v0 : v1) + (long)j * stride_b;
-        j += nv;
-        return true;
-    }
-};
-
 // Software pipeline of one wavefront: the K registers are refilled for the next tile as soon as
 // the score MFMAs have consumed them, the V registers as soon as the PV MFMAs have.
-__device__ __forceinline__ void run_stream(Stream& sm, long stride_b, const bf16x8 (&qf)[4], float sc2, WaveState& st) {
+__device__ __forceinline__ void run_stream(DecodeStream& sm, long stride_b, const bf16x8 (&qf)[4], float sc2, WaveState& st) {
     const char *kb, *vb, *kn, *vn;
     int nv, nn;
     if (!sm.next(kb, vb, nv)) return;
@@ -269,23 +206,17 @@ __global__ __launch_bounds__(NT, 2) void decode_kernel(const QueryArgs a, const 
     for (int i = 0; i < 8; ++i) st.o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     const float inv_sqrt_d = 0.08838834764831845f;
 
-    Stream sm;
+    DecodeStream sm;
     if (split < a.n_ctx_splits) {
-        long t0, t1;
+        long t0, t1, lo, hi;
         ctx_split_range(a, kv, split, t0, t1);
-        // this wavefront's share: a multiple of 32 tokens
-        const long per = t0 < t1 ? ((t1 - t0 + NW - 1) / NW + BT - 1) / BT * BT : 0;
-        const long t = t0 + wave * per;
-        sm.init_ctx(kv, t, min(t1, t + per), stride_b, head_b);
+        decode_wave_share(t0, t1, wave, lo, hi);
+        sm.init_ctx(kv, lo, hi, stride_b, head_b);
         run_stream(sm, stride_b, qf, inv_sqrt_d / kv.temperature * LOG2E, st);
     } else {
-        // prefix + self (one query row sees all self_len tokens); wavefronts take contiguous
-        // shares, the prefix dealt from wavefront 0 upwards and the self KV from the last one down
-        const int np = kv.prefix_len, ns = kv.self_len;
-        const int perp = ((np + NW - 1) / NW + BT - 1) / BT * BT;
-        const int pers = ((ns + NW - 1) / NW + BT - 1) / BT * BT;
-        const int pb = min(np, wave * perp), pe = min(np, pb + perp);
-        const int sb = min(ns, (NW - 1 - wave) * pers), se = min(ns, sb + pers);
+        // prefix + self (one query row sees all self_len tokens)
+        int pb, pe, sb, se;
+        decode_plain_shares(kv.prefix_len, kv.self_len, wave, pb, pe, sb, se);
         sm.init_plain((const char*)kv.k_prefix + (long)pb * stride_b + head_b, (const char*)kv.v_prefix + (long)pb * stride_b + head_b, pe - pb,
                       (const char*)kv.k_self + (long)sb * stride_b + head_b, (const char*)kv.v_self + (long)sb * stride_b + head_b, se - sb,
                       stride_b);
