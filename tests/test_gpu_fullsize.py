@@ -146,3 +146,29 @@ def test_prefill_tile_switch_by_context_length_sampled(chunk_lens, q_len, self_e
     H.check_close(_gather(out, pairs), ref, "bf16", "prefill %s" % (chunk_lens,))
     assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
     assert torch.isfinite(out.float()).all()
+
+
+@pytest.mark.parametrize("hq, hkv", [(8, 8), (16, 8), (16, 2)])
+def test_wide_tile_with_other_head_ratios_sampled(hq, hkv):
+    """The wide query tile (prefill beyond 40960 context tokens, encode of chunks beyond 4096 tokens)
+    for 1, 2 and 8 query heads per KV head; ragged rows and contexts, sampled outputs."""
+    g = hq // hkv
+    q_len = 300 // g + 3                                  # more than one wide tile of (token, head) rows, the last ragged
+    spec = W.CONFIGS[3].replace(n_q_heads=hq, n_kv_heads=hkv, chunk_lens=(30000, 5000, 1, 6037), q_len=q_len,
+                                prefix_len=19, decode_steps=5, k_scale=1.0)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    rng = np.random.default_rng(100 + g)
+    self_len = q_len + 5
+    out, lse = H.run_prefill(spec, r, q_len, self_len)
+    pairs = _pairs(rng, q_len, hq, 160, must_rows=(256 // g - 1, 256 // g, 128 // g, 64 // g))
+    ref, ref_lse, _ = H.oracle_prefill(h, q_len, self_len, r.temperature, r.scale, pairs=pairs)
+    H.check_close(_gather(out, pairs), ref, "bf16", "wide prefill G=%d" % g)
+    assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    o_ctx, lse_ctx, _, _ = H.run_encode(spec, r, with_prefix_rows=False)
+    m = spec.total_ctx_len
+    pairs = _pairs(rng, m, hq, 200, must_rows=(0, 63, 64, 4095, 4096, 29999, 30000, 30001, 34999, 35000, 35001, m - 1))
+    ref, ref_lse = H.oracle_encode(h, pairs=pairs)
+    H.check_close(_gather(o_ctx, pairs), ref, "bf16", "wide encode G=%d" % g)
+    assert np.abs(_gather(lse_ctx, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(out.float()).all() and torch.isfinite(o_ctx.float()).all()
