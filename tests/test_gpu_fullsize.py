@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2502_05431_amd import binding as B
 from paper_2502_05431_amd import workloads as W
 
 import helpers as H
@@ -172,3 +173,30 @@ def test_wide_tile_with_other_head_ratios_sampled(hq, hkv):
     H.check_close(_gather(o_ctx, pairs), ref, "bf16", "wide encode G=%d" % g)
     assert np.abs(_gather(lse_ctx, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
     assert torch.isfinite(out.float()).all() and torch.isfinite(o_ctx.float()).all()
+
+
+def test_batched_prefill_on_the_wide_tile_sampled():
+    """Three requests in one batched prefill whose longest context (45 000 tokens) puts the call on the
+    wide query tile: the short and the empty context leave most of their splits untouched."""
+    base = W.CONFIGS[3].replace(temperature=None, scale=None, decode_steps=30, k_scale=1.0)
+    q_len = 48                                            # 192 (token, head) rows per KV head: one ragged wide tile
+    specs = [base.replace(chunk_lens=(20000, 25000), q_len=q_len), base.replace(chunk_lens=(300,), q_len=q_len, prefix_len=7),
+             base.replace(chunk_lens=(), q_len=q_len)]
+    self_lens = [48, 61, 78]
+    rs = [W.make_request(sp, DEV, request=b) for b, sp in enumerate(specs)]
+    shape = B.make_shape(base.n_q_heads, base.n_kv_heads, base.head_dim, base.torch_dtype)
+    reqs = [H.make_binding_request(r, sl) for r, sl in zip(rs, self_lens)]
+    q = torch.stack([r.q_self[sl - q_len:sl] for r, sl in zip(rs, self_lens)]).contiguous()
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((len(rs), base.n_q_heads, q_len), float("nan"), dtype=torch.float32, device=DEV)
+    ws = H.poisoned_workspace(B.workspace_bytes(B.APE_OP_PREFILL, shape, len(rs), q_len), DEV)
+    B.attention_prefill_batch(shape, reqs, q, out, lse, ws, self_lens=self_lens)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(21)
+    for b, (r, sl) in enumerate(zip(rs, self_lens)):
+        h = H.HostArrays(r)
+        pairs = _pairs(rng, q_len, base.n_q_heads, 128, must_rows=(31, 32, 33))
+        ref, ref_lse, _ = H.oracle_prefill(h, q_len, sl, r.temperature, r.scale, pairs=pairs)
+        H.check_close(_gather(out[b], pairs), ref, "bf16", "request %d" % b)
+        assert np.abs(_gather(lse[b], pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(out.float()).all()
