@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <vector>
 
 namespace ape {
@@ -102,6 +103,7 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     int n = want < 1 ? 1 : want;
     if (n > cap) n = cap;
     if (n > kMaxSplits) n = kMaxSplits;
+    p.n_bound = n;                                     // rounding the length up to whole tiles can only lower the count
     long len = (max_ctx + n - 1) / n;
     len = (len + 63) / 64 * 64;                        // tiles never straddle a split
     n = ceil_div(max_ctx, len);
@@ -223,9 +225,17 @@ size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_
     if (op == APE_OP_DECODE) q_len = 1;
     else if (op != APE_OP_PREFILL) return 0;
     if (batch < 1 || q_len < 1) return 0;
-    // worst case over every context length: as many context splits as the planner can ask for, + 1
+    // worst case over every context length: as many context splits as the planner can ask for, + 1.
+    // The prefill plan changes its query tile and its workgroup target with the context length; within
+    // each of the three ranges the count before rounding only grows with the length, so their upper ends decide.
     int n_max = kMaxSplits;
-    if (op == APE_OP_PREFILL) n_max = prefill_plan(si, batch, q_len, (long)kMaxSplits * (1 << 20)).n_ctx_splits;
+    if (op == APE_OP_PREFILL) {
+        n_max = 0;
+        for (long ctx : {kPrefillOneWorkgroupPerCuMaxCtx, kPrefillNarrowTileMaxCtx, (long)kMaxSplits * (1 << 20)}) {
+            const int n = prefill_plan(si, batch, q_len, ctx).n_bound;
+            if (n > n_max) n_max = n;
+        }
+    }
     return partial_bytes((long)batch * q_len * si.hq, n_max + 1, si.d);
 }
 

@@ -860,10 +860,12 @@ int flash_block_rows(int rows_per_kv_head) { return rows_per_kv_head > 128 ? 256
 // 0.064 ms, 10K 0.078 / 0.089, 16K 0.102 / 0.113, 32K 0.160 / 0.168, 48K 0.229 / 0.232, 64K equal, 128K
 // 0.537 / 0.527.  Up to 12K tokens one narrow workgroup per CU is enough, beyond that two.
 int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx) {
-    if (max_ctx <= 40960) return 128;
+    if (max_ctx <= kPrefillNarrowTileMaxCtx) return 128;
     return flash_block_rows(rows_per_kv_head);
 }
-int flash_prefill_target_workgroups(long max_ctx) { return max_ctx > 12288 && max_ctx <= 40960 ? 512 : 256; }
+int flash_prefill_target_workgroups(long max_ctx) {
+    return max_ctx > kPrefillOneWorkgroupPerCuMaxCtx && max_ctx <= kPrefillNarrowTileMaxCtx ? 512 : 256;
+}
 
 hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;

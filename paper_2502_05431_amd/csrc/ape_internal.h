@@ -230,6 +230,7 @@ struct QueryPlan {
     int n_ctx_splits;
     int ctx_split_len;
     int n_splits_total;
+    int n_bound;           // >= n_ctx_splits of this plan and of the plan for any shorter context with the same base and target
     int block_rows;        // query tile of the flash prefill this plan was made for (0: not a flash prefill)
 };
 
@@ -255,5 +256,8 @@ int flash_block_rows(int rows_per_kv_head);
 // the number of workgroups its split plan aims at
 int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx);
 int flash_prefill_target_workgroups(long max_ctx);
+// the context lengths at which those two change their answer (each holds up to and including its value)
+constexpr long kPrefillOneWorkgroupPerCuMaxCtx = 12288;
+constexpr long kPrefillNarrowTileMaxCtx = 40960;
 
 }  // namespace ape

@@ -129,6 +129,8 @@ def test_long_chunks_take_the_wide_tile_encode_sampled():
 @pytest.mark.parametrize("chunk_lens, q_len, self_extra", [
     ((20000, 1, 13000, 333, 9000, 64, 31), 50, 0),        # just above the switch; 200 ragged rows on one wide tile
     ((12000, 0, 12000, 12000, 6999, 3), 130, 70),         # three wide tiles, the last ragged; long own span
+    ((9000, 9000, 2000), 8, 0),                           # few rows, 20K context: twice the workgroups per row tile
+    ((30000, 10959), 32, 3),                              # 128 rows per KV head just below the switch: the most splits of any plan
     ((40960,), 50, 0),                                    # the last context length on the narrow tile
     ((40961,), 50, 0),                                    # the first one on the wide tile
 ])

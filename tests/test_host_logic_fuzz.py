@@ -117,3 +117,65 @@ def test_workspace_sizes_are_what_the_calls_demand(seed):
     rq.prefix_len = 4; rq.n_chunks = n_chunks; rq.total_ctx_len = total; rq.self_len = q_len; rq.temperature = 0.9; rq.scale = 0.9
     rc = B.load().ape_attention_prefill(ctypes.byref(sh), ctypes.byref(rq), FAKE, q_len, FAKE, None, FAKE * 256, 1, None)
     assert rc == B.APE_ERR_WORKSPACE
+
+
+def _needed(call):
+    """Workspace a call demands, read from the message of its refusal (the call gets 1 byte and launches nothing)."""
+    assert call() == B.APE_ERR_WORKSPACE
+    msg = B.load().ape_last_error().decode()
+    return int(msg.split(" bytes given, ")[1].split(" needed")[0])
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_workspace_bound_covers_every_context_length(seed):
+    """ape_workspace_bytes knows batch and rows only; whatever the context length makes of the split
+    plan (the query tile and the workgroup target change at 12 288 and 40 960 context tokens), the
+    demand stays within it."""
+    rng = random.Random(500 + seed)
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16) if seed % 2 == 0 else B.make_shape(rng.choice([8, 16, 64]), 8, 128, B.APE_BF16)
+    edges = [0, 1, 63, 64, 65, 255, 256, 257, 4096, 12287, 12288, 12289, 16384, 40959, 40960, 40961, 65536, 131072, 1 << 20, (1 << 31) - 1]
+    for _ in range(60):
+        batch = rng.choice([1, 1, 2, 4, 7, 32, 33])
+        q_len = rng.choice([1, 2, 31, 32, 33, 64, 100, 128, 256, 1000])
+        ctx = rng.choice(edges + [rng.randint(1, 300000)])
+        arr = (B.ApeRequest * batch)()
+        for b in range(batch):
+            r = arr[b]
+            for k in ("k_prefix", "v_prefix", "k_chunks", "v_chunks", "cu_chunk_lens", "k_self", "v_self"):
+                setattr(r, k, FAKE)
+            r.prefix_len = 4; r.n_chunks = 3 if ctx else 0
+            r.total_ctx_len = ctx if b == 0 else rng.randint(0, ctx) if ctx else 0      # request 0 holds the longest context
+            if r.total_ctx_len == 0:
+                r.n_chunks = 0
+            r.self_len = q_len; r.temperature = 0.9; r.scale = 0.9
+        bound_p = B.workspace_bytes(B.APE_OP_PREFILL, sh, batch, q_len)
+        need_p = _needed(lambda: lib.ape_attention_prefill_batch(ctypes.byref(sh), arr, batch, FAKE, q_len, FAKE, None, FAKE * 256, 1, None))
+        assert need_p <= bound_p, (batch, q_len, ctx, need_p, bound_p)
+        for b in range(batch):
+            arr[b].self_len = max(1, arr[b].self_len)
+        bound_d = B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1)
+        need_d = _needed(lambda: lib.ape_attention_decode(ctypes.byref(sh), arr, batch, FAKE, FAKE, None, FAKE * 256, 1, None))
+        assert need_d <= bound_d, (batch, ctx, need_d, bound_d)
+
+
+@pytest.mark.parametrize("hq, q_len, batch", [(32, 1, 1), (32, 32, 1), (32, 33, 1), (32, 256, 1), (8, 100, 3), (64, 5, 2)])
+def test_prefill_workspace_bound_over_a_sweep_of_context_lengths(hq, q_len, batch):
+    """Every context length in a fine sweep up to 70 000 tokens (both changes of the plan lie inside),
+    then coarser up to 3 M: the demand never passes ape_workspace_bytes."""
+    lib = B.load()
+    sh = B.make_shape(hq, 8, 128, B.APE_BF16)
+    bound = B.workspace_bytes(B.APE_OP_PREFILL, sh, batch, q_len)
+    arr = (B.ApeRequest * batch)()
+    for b in range(batch):
+        for k in ("k_prefix", "v_prefix", "k_chunks", "v_chunks", "cu_chunk_lens", "k_self", "v_self"):
+            setattr(arr[b], k, FAKE)
+        arr[b].prefix_len = 4; arr[b].n_chunks = 2; arr[b].self_len = q_len; arr[b].temperature = 0.9; arr[b].scale = 0.9
+    worst = 0
+    for ctx in list(range(1, 70000, 5)) + list(range(70000, 3000000, 9973)):
+        for b in range(batch):
+            arr[b].total_ctx_len = ctx
+        need = _needed(lambda: lib.ape_attention_prefill_batch(ctypes.byref(sh), arr, batch, FAKE, q_len, FAKE, None, FAKE * 256, 1, None))
+        assert need <= bound, (ctx, need, bound)
+        worst = max(worst, need)
+    assert worst > bound // 2                              # and the bound is not idle: some length comes within a factor of two
