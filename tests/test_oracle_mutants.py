@@ -55,22 +55,32 @@ MUTANTS = [
     ("rope: positions do not restart in every context",
      "const double pos = (double)(position_offset + (t - cu_chunk_lens[i]));", "const double pos = (double)(position_offset + t);", "test_oracle_rope_pins.py"),
 ]
+# the layer around the attention (numpy): (name, text in oracle/layer_oracle.py, replacement)
+LAYER_MUTANTS = [
+    ("layer: epsilon outside the root", "x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)", "x / (np.sqrt(np.mean(x * x, axis=-1, keepdims=True)) + eps)"),
+    ("layer: first residual dropped", "x1 = x[sel] + a @ f(w[\"wo\"]).T", "x1 = a @ f(w[\"wo\"]).T"),
+    ("layer: second residual dropped", "y = x1 + (silu(g) * u) @ f(w[\"wd\"]).T", "y = (silu(g) * u) @ f(w[\"wd\"]).T"),
+    ("layer: activation on the wrong branch", "(silu(g) * u)", "(g * silu(u))"),
+    ("layer: the MLP reads the un-normalised stream", "g, u = h2 @ f(w[\"wg\"]).T, h2 @ f(w[\"wu\"]).T", "g, u = x1 @ f(w[\"wg\"]).T, x1 @ f(w[\"wu\"]).T"),
+    ("layer: keys are not rotated", "    k = rope_f64(k, chunk_lens, lp, rope_base)\n", ""),
+    ("layer: positions start at zero instead of behind the prefix", "q = rope_f64(q, chunk_lens, lp, rope_base)", "q = rope_f64(q, chunk_lens, 0, rope_base)"),
+]
 # every query head reads its KV head: planted in all four functions at once
 GQA = ("wrong map from query heads to KV heads", "const int hk = h / G;", "const int hk = h % n_kv_heads;", "test_oracle_pins.py")
 
 
-def _copy_tree(tmp_path, old=None, new=None, every=False):
+def _copy_tree(tmp_path, old=None, new=None, every=False, target="ape_oracle.c"):
     root = tmp_path / "copy"
     (root / "oracle").mkdir(parents=True)
     (root / "tests").mkdir()
     for name in os.listdir(os.path.join(ROOT, "oracle")):
         if name.endswith((".py", ".c")):
             shutil.copy(os.path.join(ROOT, "oracle", name), root / "oracle" / name)
-    for name in ("conftest.py", "test_oracle_pins.py", "test_oracle_tree_pins.py", "test_oracle_rope_pins.py"):
+    for name in ("conftest.py", "test_oracle_pins.py", "test_oracle_tree_pins.py", "test_oracle_rope_pins.py", "test_oracle_layer_pins.py"):
         shutil.copy(os.path.join(HERE, name), root / "tests" / name)
     shutil.copytree(os.path.join(HERE, "golden"), root / "tests" / "golden")
     if old is not None:
-        path = root / "oracle" / "ape_oracle.c"
+        path = root / "oracle" / target
         src = path.read_text()
         assert src.count(old) >= 1 if every else src.count(old) == 1, "mutation site not found exactly once: %r" % old
         path.write_text(src.replace(old, new))
@@ -88,7 +98,7 @@ def _run_pins(root, pin_file):
 @pytest.mark.skipif(shutil.which("gcc") is None, reason="needs gcc")
 def test_the_untouched_copy_passes_every_pin(tmp_path):
     root = _copy_tree(tmp_path)
-    for pin_file in ("test_oracle_pins.py", "test_oracle_tree_pins.py", "test_oracle_rope_pins.py"):
+    for pin_file in ("test_oracle_pins.py", "test_oracle_tree_pins.py", "test_oracle_rope_pins.py", "test_oracle_layer_pins.py"):
         run = _run_pins(root, pin_file)
         assert run.returncode == 0, (pin_file, run.stdout[-3000:], run.stderr[-2000:])
         assert str(root) in run.stdout or "passed" in run.stdout
@@ -101,3 +111,12 @@ def test_a_planted_mistake_fails_a_pin(tmp_path, name, old, new, pin_file):
     run = _run_pins(root, pin_file)
     assert run.returncode == 1, "the pins did not notice: %s\n%s\n%s" % (name, run.stdout[-3000:], run.stderr[-2000:])
     assert "failed" in run.stdout and "error" not in run.stdout.splitlines()[-1], run.stdout[-2000:]      # a pin failed; nothing broke on the way
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="needs gcc")
+@pytest.mark.parametrize("name, old, new", LAYER_MUTANTS, ids=[m[0] for m in LAYER_MUTANTS])
+def test_a_planted_mistake_in_the_layer_fails_a_pin(tmp_path, name, old, new):
+    root = _copy_tree(tmp_path, old, new, target="layer_oracle.py")
+    run = _run_pins(root, "test_oracle_layer_pins.py")
+    assert run.returncode == 1, "the pins did not notice: %s\n%s\n%s" % (name, run.stdout[-3000:], run.stderr[-2000:])
+    assert "failed" in run.stdout and "error" not in run.stdout.splitlines()[-1], run.stdout[-2000:]
