@@ -111,7 +111,15 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     return p;
 }
 
-// Split plan of the query prefill: one workgroup per CU on the matrix-core path.
+// Split plan of a decode step: one workgroup per (request, KV head, split) on the matrix-core path,
+// about 2048 of them, splits of at least 512 tokens.
+QueryPlan decode_plan(const ShapeInfo& si, int batch, long max_ctx) {
+    const int base = si.mfma ? batch * si.hkv : batch * si.hq;
+    return plan_query(base, max_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
+}
+
+// Split plan of the query prefill.  Matrix-core path: about one workgroup per CU (two of the narrow
+// tile for contexts of middle length), the query tile chosen by flash_prefill_block_rows.
 QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) {
     const int rows = q_len * si.group;
     const long units = (long)batch * q_len * si.hq;
@@ -135,7 +143,7 @@ struct TreePlan {
 
 TreePlan plan_tree(const ShapeInfo& si, long total_ctx, int n_nodes, int q_len) {
     QueryPlan qp;
-    if (q_len == 1) qp = plan_query(si.mfma ? si.hkv : si.hq, total_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
+    if (q_len == 1) qp = decode_plan(si, 1, total_ctx);
     else qp = prefill_plan(si, 1, q_len, total_ctx);
     TreePlan p;
     p.len = qp.ctx_split_len;
@@ -225,6 +233,7 @@ size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_
     if (op == APE_OP_DECODE) q_len = 1;
     else if (op != APE_OP_PREFILL) return 0;
     if (batch < 1 || q_len < 1) return 0;
+    if ((long)batch * q_len * si.hq > kMaxUnits) return 0;     // the entry points refuse such a call
     // worst case over every context length: as many context splits as the planner can ask for, + 1.
     // The prefill plan changes its query tile and its workgroup target with the context length; within
     // each of the three ranges the count before rounding only grows with the length, so their upper ends decide.
@@ -312,9 +321,7 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         return fail(APE_ERR_UNSUPPORTED, "%d requests x %d rows x %d heads = %ld outputs in one call, at most %ld are supported", batch, q_len, si.hq, units, kMaxUnits);
     QueryPlan plan;
     if (decode) {
-        // one workgroup per (request, KV head, split) on the matrix-core path
-        const int base = si.mfma ? batch * si.hkv : (int)units;
-        plan = plan_query(base, max_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
+        plan = decode_plan(si, batch, max_ctx);
     } else {
         plan = prefill_plan(si, batch, q_len, max_ctx);
     }
