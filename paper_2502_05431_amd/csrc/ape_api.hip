@@ -7,7 +7,6 @@
 #include <cstdio>
 #include <cstring>
 #include <initializer_list>
-#include <vector>
 
 namespace ape {
 namespace {
@@ -163,7 +162,7 @@ int check_tree(const ape_tree_node* nodes, int n_nodes, int n_chunks, int* n_lev
     if (n_nodes > APE_TREE_MAX_NODES) return fail(APE_ERR_UNSUPPORTED, "%d tree nodes, at most %d are supported", n_nodes, APE_TREE_MAX_NODES);
     if (n_chunks < 1) return fail(APE_ERR_INVALID_ARG, "a tree needs at least one context");
     if (n_chunks > APE_TREE_MAX_CONTEXTS) return fail(APE_ERR_UNSUPPORTED, "%d contexts, at most %d are supported under a tree", n_chunks, APE_TREE_MAX_CONTEXTS);
-    std::vector<char> owned((size_t)n_chunks, 0);
+    bool owned[APE_TREE_MAX_CONTEXTS] = {};            // on the stack: the call allocates nothing, on the host either
     long next_child = 1;
     for (int n = 0; n < n_nodes; ++n) {
         const ape_tree_node& t = nodes[n];
