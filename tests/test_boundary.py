@@ -284,3 +284,36 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="missing"):
         B.load()
+
+
+def test_binding_structs_have_the_layout_of_the_header(tmp_path):
+    """The ctypes mirrors of the C structs against the compiler's view of include/ape.h: size and the
+    offset of every field (a drifted binding would hand the library shifted arguments)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    structs = {"ape_shape": B.ApeShape, "ape_request": B.ApeRequest, "ape_tree_node": B.ApeTreeNode,
+               "ape_layer_weights": B.ApeLayerWeights}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "ape.h"', 'int main(void) {']
+    for cname, cls in structs.items():
+        lines.append('printf("%s size %%zu\\n", sizeof(%s));' % (cname, cname))
+        for fname, _ in cls._fields_:
+            lines.append('printf("%s %s %%zu\\n", offsetof(%s, %s));' % (cname, fname, cname, fname))
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = str(tmp_path / "layout")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-I", inc, "-o", exe, str(src)])
+    out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split("\n")
+    seen = 0
+    for line in filter(None, out):
+        cname, fname, value = line.split()
+        cls = structs[cname]
+        if fname == "size":
+            assert ctypes.sizeof(cls) == int(value), line
+        else:
+            assert getattr(cls, fname).offset == int(value), line
+        seen += 1
+    assert seen == sum(len(c._fields_) + 1 for c in structs.values())
