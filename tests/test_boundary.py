@@ -317,3 +317,43 @@ def test_binding_structs_have_the_layout_of_the_header(tmp_path):
             assert getattr(cls, fname).offset == int(value), line
         seen += 1
     assert seen == sum(len(c._fields_) + 1 for c in structs.values())
+
+
+def test_a_plain_c_program_links_and_calls_the_library(tmp_path):
+    """The boundary is a C ABI: a C11 program that includes ape.h links against the library and calls
+    the entry points that need no GPU (sizes, status strings, an argument error)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    B.load()                                              # fails loudly if the library has not been built
+    src = tmp_path / "consumer.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "ape.h"
+int main(void) {
+    ape_shape sh = {32, 8, 128, APE_BF16};
+    size_t ws = ape_workspace_bytes(APE_OP_DECODE, &sh, 32, 1);
+    if (ws == 0 || ws % 256) return 1;
+    if (ape_workspace_bytes(APE_OP_ENCODE, &sh, 1, 1) != 0) return 2;
+    if (strlen(ape_status_string(APE_ERR_WORKSPACE)) == 0) return 3;
+    ape_request r;
+    memset(&r, 0, sizeof r);
+    r.temperature = 0.f;                                  /* invalid: refused on the host, nothing is launched */
+    int rc = ape_attention_prefill(&sh, &r, (const void*)256, 1, (void*)256, NULL, NULL, 0, NULL);
+    if (rc != APE_ERR_INVALID_ARG || strlen(ape_last_error()) == 0) return 4;
+    printf("%s %zu\n", ape_version(), ws);
+    return 0;
+}
+''')
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    exe = str(tmp_path / "consumer")
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(root, "include"), "-o", exe, str(src),
+                           "-L", lib_dir, "-lape_hip", "-Wl,-rpath," + lib_dir, "-Wl,-rpath-link,/opt/rocm/lib"])
+    env = dict(os.environ)
+    env["LD_LIBRARY_PATH"] = lib_dir + os.pathsep + "/opt/rocm/lib" + os.pathsep + env.get("LD_LIBRARY_PATH", "")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0, (run.returncode, run.stdout, run.stderr)
+    assert run.stdout.split()[1].isdigit()
