@@ -22,6 +22,10 @@
  *   - Every data pointer marked DEVICE points to GPU memory owned by the caller;
  *     the library never allocates, frees or copies device memory and keeps no
  *     state between calls.  Pointers marked HOST are read during the call only.
+ *   - Every data pointer is 16-byte aligned (rows of head_dim elements then are too: the kernels
+ *     use 16-byte accesses); that holds for the pointers inside device tables (k_chunks[i], the
+ *     caches of ape_rope_write_cache) as well, which the host cannot check.  Tables themselves are
+ *     aligned to their element size.
  *   - Tensors are row-major [tokens, heads, head_dim]; K/V have n_kv_heads heads,
  *     Q/O have n_q_heads heads; query head h reads KV head h / (n_q_heads/n_kv_heads).
  *     Q and K arrive already position-rotated.

@@ -22,6 +22,16 @@ int fail(int code, const char* fmt, ...) {
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// The kernels read and write rows with 16-byte vector accesses: every data pointer the host can
+// see is checked (NULL passes: presence is checked where it matters).
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+#define APE_CHECK_ALIGNED(...)                                                                              \
+    do {                                                                                                    \
+        const void* ptrs_[] = {__VA_ARGS__};                                                                \
+        for (const void* p_ : ptrs_)                                                                        \
+            if (misaligned(p_)) return fail(APE_ERR_INVALID_ARG, "data pointer %p is not 16-byte aligned (%s)", p_, #__VA_ARGS__); \
+    } while (0)
 inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 
 struct ShapeInfo {
@@ -55,6 +65,9 @@ int check_request(const ape_request* r, int q_len, int idx) {
         return fail(APE_ERR_INVALID_ARG, "request %d: chunk table is NULL", idx);
     if (r->self_len < q_len || q_len < 1) return fail(APE_ERR_INVALID_ARG, "request %d: self_len %d < q_len %d (the query rows' own KV belongs to k_self)", idx, r->self_len, q_len);
     if (!r->k_self || !r->v_self) return fail(APE_ERR_INVALID_ARG, "request %d: self KV is NULL", idx);
+    APE_CHECK_ALIGNED(r->k_prefix, r->v_prefix, r->k_self, r->v_self);
+    if (((uintptr_t)r->k_chunks | (uintptr_t)r->v_chunks) & 7 || (uintptr_t)r->cu_chunk_lens & 3)
+        return fail(APE_ERR_INVALID_ARG, "request %d: the chunk tables are not aligned to their element size", idx);
     if (!(std::isfinite(r->temperature) && r->temperature > 0.f)) return fail(APE_ERR_INVALID_ARG, "request %d: temperature must be finite and > 0", idx);
     if (!(std::isfinite(r->scale) && r->scale > 0.f)) return fail(APE_ERR_INVALID_ARG, "request %d: scale must be finite and > 0", idx);
     return APE_OK;
@@ -261,6 +274,7 @@ int ape_encode_chunks(const ape_shape* shape,
     if (prefix_len > 0 && (!k_prefix || !v_prefix)) return fail(APE_ERR_INVALID_ARG, "prefix KV is NULL");
     if ((q_prefix == nullptr) != (o_prefix == nullptr)) return fail(APE_ERR_INVALID_ARG, "q_prefix and o_prefix must both be given or both be NULL");
     if (lse_prefix && !q_prefix) return fail(APE_ERR_INVALID_ARG, "lse_prefix given without q_prefix");
+    APE_CHECK_ALIGNED(q_prefix, k_prefix, v_prefix, q_chunks, k_chunks, v_chunks, o_prefix, o_chunks);
     long total = 0;
     int max_len = 0;
     if (n_chunks > 0) {
@@ -315,6 +329,7 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         const long m = reqs[b].n_chunks > 0 ? reqs[b].total_ctx_len : 0;
         if (m > max_ctx) max_ctx = m;
     }
+    APE_CHECK_ALIGNED(q, out);
     const long units = (long)batch * q_len * si.hq;
     if (units > kMaxUnits)
         return fail(APE_ERR_UNSUPPORTED, "%d requests x %d rows x %d heads = %ld outputs in one call, at most %ld are supported", batch, q_len, si.hq, units, kMaxUnits);
@@ -415,6 +430,7 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     if (q_len < 1) return fail(APE_ERR_INVALID_ARG, "q_len %d < 1", q_len);
     rc = check_request(req, q_len, 0);
     if (rc) return rc;
+    APE_CHECK_ALIGNED(q, out);
     if ((long)q_len * si.hq > kMaxUnits)
         return fail(APE_ERR_UNSUPPORTED, "%d rows x %d heads = %ld outputs in one call, at most %ld are supported", q_len, si.hq, (long)q_len * si.hq, kMaxUnits);
     TreeMergeArgs m{};
@@ -472,6 +488,7 @@ int ape_rope_write_cache(const ape_shape* shape,
     if (position_offset < 0) return fail(APE_ERR_INVALID_ARG, "position_offset %d < 0", position_offset);
     if (!(std::isfinite(rope_base) && rope_base > 0.f)) return fail(APE_ERR_INVALID_ARG, "rope_base must be finite and > 0");
     if ((q_raw == nullptr) != (q_rot == nullptr)) return fail(APE_ERR_INVALID_ARG, "q_raw and q_rot must both be given or both be NULL");
+    APE_CHECK_ALIGNED(q_raw, k_raw, v_raw, q_rot);
     if ((k_raw == nullptr) != (k_cache == nullptr)) return fail(APE_ERR_INVALID_ARG, "k_raw and k_cache must both be given or both be NULL");
     if ((v_raw == nullptr) != (v_cache == nullptr)) return fail(APE_ERR_INVALID_ARG, "v_raw and v_cache must both be given or both be NULL");
     if (n_chunks == 0) return APE_OK;
@@ -558,6 +575,7 @@ int ape_layer_encode(const ape_shape* shape, const ape_layer_weights* w, const v
     const long rows = cu_host[n_chunks];
     if (rows == 0) return APE_OK;
     if (!x || !y || !k_cache || !v_cache) return fail(APE_ERR_INVALID_ARG, "x, y, k_cache and v_cache must not be NULL");
+    APE_CHECK_ALIGNED(x, y, k_cache, v_cache, k_prefix, v_prefix, w->attn_norm, w->w_qkv, w->w_o, w->mlp_norm, w->w_gate_up, w->w_down);
     rc = check_encode_size(si, n_chunks, max_len, rows);
     if (rc) return rc;
     const LayerPlan p = plan_layer(si, w->hidden, w->intermediate, rows);

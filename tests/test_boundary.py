@@ -89,6 +89,22 @@ def test_prefill_argument_errors(kw, code):
     assert B.load().ape_last_error()
 
 
+def test_misaligned_data_pointers_are_refused():
+    """The kernels use 16-byte accesses; pointers the host can see are checked before any launch."""
+    lib = B.load()
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    for kw in (dict(k_self=FAKE + 2), dict(v_prefix=FAKE + 8), dict(k_chunks=FAKE + 4), dict(cu_chunk_lens=FAKE + 2)):
+        assert _prefill(sh, _req(**kw)) == B.APE_ERR_INVALID_ARG, kw
+        assert b"aligned" in lib.ape_last_error()
+    assert _prefill(sh, _req(), q=FAKE + 8) == B.APE_ERR_INVALID_ARG
+    assert _prefill(sh, _req(), out=FAKE + 4) == B.APE_ERR_INVALID_ARG
+    assert _prefill(sh, _req(k_chunks=FAKE + 8)) == B.APE_ERR_WORKSPACE          # a table may start at any of its elements
+    cu = (ctypes.c_int32 * 2)(0, 64)
+    rc = lib.ape_encode_chunks(ctypes.byref(sh), None, FAKE, FAKE, 4, FAKE + 6, FAKE, FAKE, ctypes.cast(cu, ctypes.c_void_p), FAKE, 1,
+                               None, FAKE, None, None, None, 0, None)
+    assert rc == B.APE_ERR_INVALID_ARG and b"aligned" in lib.ape_last_error()
+
+
 def test_shape_errors():
     r = _req()
     assert _prefill(B.make_shape(32, 7, 128, B.APE_BF16), r) == B.APE_ERR_INVALID_ARG
