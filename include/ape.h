@@ -178,6 +178,26 @@ int ape_attention_decode(const ape_shape *shape, const ape_request *reqs, int32_
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ape_attention_decode for callers that cannot allocate device memory or pass a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same decode
+ * step, same kernels and same results, with the partial results of the context splits kept in a
+ * fixed buffer of APE_STATIC_SCRATCH_BYTES that the library holds in the memory of every GPU it is
+ * loaded on, until the process ends.  The call allocates and frees nothing.
+ *
+ *   reqs, batch, q, out, lse_out, stream   as for ape_attention_decode
+ * A call whose partial results do not fit (about batch x n_q_heads x (splits + 1) x (head_dim + 1) x
+ * 4 bytes; the Llama-3-8B shape fits 32 requests of 16K context tokens or one of 128K several times
+ * over) returns APE_ERR_UNSUPPORTED with nothing launched.  All calls on one GPU share the one
+ * buffer, which keeps the last call's contents: calls that overlap in time on the same GPU (two
+ * streams, two host threads) race and must be serialised by the caller.  Nothing in it needs
+ * clearing between calls.  The first call on a device looks the buffer's address up once (do it
+ * outside a graph capture); the current device must be the stream's.
+ */
+#define APE_STATIC_SCRATCH_BYTES (8u << 20)
+int ape_attention_decode_static(const ape_shape *shape, const ape_request *reqs, int32_t batch,
+                                const void *q, void *out, float *lse_out, void *stream);
+
+/*
  * One node of a tree of contexts (Appendix C.5: a cache whose contexts form a hierarchy).
  * Appendix C.2 is applied at every node: a node merges its children by a softmax over their
  * LogSumExp values A, and its own value is A_n = scale * LogSumExp(A_children).  The children

@@ -24,11 +24,12 @@ APE_DTYPE_FLAG_GENERIC = 0x100
 APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
 
 EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
-           "ape_attention_prefill_batch",
+           "ape_attention_prefill_batch", "ape_attention_decode_static",
            "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
            "ape_layer_workspace_bytes", "ape_layer_encode",
            "ape_status_string", "ape_last_error", "ape_version")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
+APE_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class ApeShape(ctypes.Structure):
@@ -90,6 +91,8 @@ def load() -> ctypes.CDLL:
         lib.ape_attention_decode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), i32, vp, vp, vp,
                                              vp, sz, vp]
         lib.ape_attention_decode.restype = ctypes.c_int
+        lib.ape_attention_decode_static.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), i32, vp, vp, vp, vp]
+        lib.ape_attention_decode_static.restype = ctypes.c_int
         lib.ape_tree_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32]
         lib.ape_tree_workspace_bytes.restype = sz
         lib.ape_attention_tree.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeRequest), vp, vp, i32,
@@ -239,6 +242,16 @@ def attention_decode(shape: ApeShape, reqs: Sequence[Request], q: torch.Tensor, 
     arr = (ApeRequest * n)(*[r.as_struct(None if self_lens is None else self_lens[i]) for i, r in enumerate(reqs)])
     rc = load().ape_attention_decode(ctypes.byref(shape), arr, n, _ptr(q), _ptr(out), _ptr(lse_out),
                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc)
+
+
+def attention_decode_static(shape: ApeShape, reqs: Sequence[Request], q: torch.Tensor, out: torch.Tensor,
+                            lse_out: Optional[torch.Tensor], stream=None, self_lens: Optional[Sequence[int]] = None):
+    """``ape_attention_decode_static``: the decode step with the library's own fixed buffer for the
+    partial results (no workspace argument, no allocation)."""
+    n = len(reqs)
+    arr = (ApeRequest * n)(*[r.as_struct(None if self_lens is None else self_lens[i]) for i, r in enumerate(reqs)])
+    rc = load().ape_attention_decode_static(ctypes.byref(shape), arr, n, _ptr(q), _ptr(out), _ptr(lse_out), _stream(stream))
     _check(rc)
 
 

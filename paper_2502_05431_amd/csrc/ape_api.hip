@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <initializer_list>
+#include <mutex>
 
 namespace ape {
 namespace {
@@ -320,8 +321,11 @@ int ape_encode_chunks(const ape_shape* shape,
     return APE_OK;
 }
 
+// `static_limit`: the workspace is the library's own fixed array, so a call that needs more is one
+// the entry point does not support (rather than a caller's buffer being too small).
 static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, int q_len, bool decode,
-                     const void* q, void* out, float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t st) {
+                     const void* q, void* out, float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t st,
+                     bool static_limit = false) {
     long max_ctx = 0;
     for (int b = 0; b < batch; ++b) {
         int rc = check_request(&reqs[b], q_len, b);
@@ -340,6 +344,9 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         plan = prefill_plan(si, batch, q_len, max_ctx);
     }
     const size_t need = partial_bytes(units, plan.n_splits_total, si.d);
+    if (static_limit && workspace_bytes < need)
+        return fail(APE_ERR_UNSUPPORTED, "%d requests x %d heads over up to %ld context tokens need %zu bytes of partial results; the "
+                    "built-in buffer holds %zu (use ape_attention_decode with a workspace of the caller's)", batch, si.hq, max_ctx, need, workspace_bytes);
     if (!workspace || workspace_bytes < need)
         return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_workspace_bytes gives the bound)", workspace_bytes, need);
     if ((uintptr_t)workspace % kWsAlign) return fail(APE_ERR_WORKSPACE, "workspace must be %d-byte aligned", kWsAlign);
@@ -408,6 +415,50 @@ int ape_attention_decode(const ape_shape* shape, const ape_request* reqs, int32_
     if (!reqs || !q || !out) return fail(APE_ERR_INVALID_ARG, "reqs, q and out must not be NULL");
     if (batch < 1) return fail(APE_ERR_INVALID_ARG, "batch %d < 1", batch);
     return run_query(si, reqs, batch, 1, true, q, out, lse_out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+// ---- decode with the partial results in a buffer of the library's own -----------------------
+// The array lives in every GPU's memory from the moment the library is loaded there until the
+// process ends.  In host code its name is only a handle: the address a kernel can use comes from
+// hipGetSymbolAddress, once per device (each GPU has its own copy at its own address).
+static __device__ __align__(256) unsigned char scratch[APE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (resolved at the first call there).
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t he = hipGetDevice(&dev);
+    if (he != hipSuccess) return fail(APE_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(he));
+    if (dev < 0 || dev >= kMaxDevices) return fail(APE_ERR_UNSUPPORTED, "device index %d, at most %d devices are supported", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        he = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (he != hipSuccess || !p) return fail(APE_ERR_DEVICE, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(he));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return APE_OK;
+}
+}  // namespace
+
+int ape_attention_decode_static(const ape_shape* shape, const ape_request* reqs, int32_t batch,
+                                const void* q, void* out, float* lse_out, void* stream) {
+    ShapeInfo si;
+    int rc = check_shape(shape, &si);
+    if (rc) return rc;
+    if (!reqs || !q || !out) return fail(APE_ERR_INVALID_ARG, "reqs, q and out must not be NULL");
+    if (batch < 1) return fail(APE_ERR_INVALID_ARG, "batch %d < 1", batch);
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    // Nothing in the buffer has to start at zero: every partial result the merge reads is written
+    // by the attention kernel of the same call (the merge stops at each request's last split).
+    return run_query(si, reqs, batch, 1, true, q, out, lse_out, ws, (size_t)APE_STATIC_SCRATCH_BYTES, (hipStream_t)stream, true);
 }
 
 size_t ape_tree_workspace_bytes(const ape_shape* shape, int32_t total_ctx_len, int32_t n_nodes, int32_t q_len) {
