@@ -30,11 +30,16 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0          # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
-# same counters' reading for a copy kernel of known size; see profiles/.  None = not measured.
+# HBM traffic per launch.  Hardware counters cannot be read from inside this process: the figures
+# come from two rocprofv3 --pmc runs of THIS script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch),
+# each scaled by the same counter's reading for the 1 GiB device copy of --calibrate-copy in the same
+# run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  TRAFFIC_SOURCE names the summary that holds the commands
+# and the raw readings; the line printed below carries it next to the number.
 MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": (790432 * 2 + 1048610) * 1024,     # 2.693 GB
                           "flash_prefill_kernel": (272131 * 2 + 37786) * 1024,     # 0.596 GB
                           "decode_kernel": (262890 * 2 + 1056) * 1024}             # 0.539 GB
+TRAFFIC_SOURCE = "profiles/bench_cfg3_hbm_traffic_pmc.md"
+WARM_MS = 150.0                    # GPU time of untimed load in front of every timed region
 
 
 def pair_counts(spec):
@@ -50,8 +55,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=25,
-                    help="untimed steps; the chip raises its clocks over the first ~100 ms of load (a 10-step run of "
-                         "the prefill measures 0.67 ms per call, a 1000-step run 0.55 ms), so keep this at 25 or more")
+                    help="untimed steps.  The chip raises its clocks over the first ~100 ms of load (a 10-step run of "
+                         "the prefill measures 0.67 ms per call, a 1000-step run 0.55 ms), so whatever this says the "
+                         "untimed steps go on until 150 ms of GPU time have passed (the count used is printed as warm_steps)")
     ap.add_argument("--decode-steps", type=int, default=8, help="decode steps per step over the 128K cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the batched-decode (config 5) region")
@@ -62,9 +68,12 @@ def main():
     ap.add_argument("--tree-variants", action="store_true",
                     help="also time the query prefill and one decode step of the same 128K cache through the tree "
                          "entry point: one pooled node, a scaling factor per context, and a two-level tree")
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time encode, query prefill and one decode step of the other bf16 configurations "
+    ap.add_argument("--all-configs", action="store_true", help="(default now; kept so that old command lines still parse)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip encode, query prefill and one decode step of the other bf16 configurations "
                          "(2: RAG-shaped 20 x 512; 4: many-shot 512 x 256), each call looped on its own")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="also time a stack of this many Llama-3-8B-shaped layers (ape_layers_encode) over the same contexts")
     ap.add_argument("--layer", action="store_true",
                     help="also time one whole Llama-3-8B-shaped layer (hidden 4096, MLP 14336, random weights) of the "
                          "context pre-caching pass over the same 64 x 2048 contexts")
@@ -101,7 +110,7 @@ def main():
     torch.cuda.set_device(0)
     B.load()
 
-    def timed(fn, iters, warm_ms=150.0):
+    def timed(fn, iters, warm_ms=WARM_MS):
         """Average ms per call of fn over `iters` calls, after calling it untimed for at least warm_ms of
         GPU time (the chip raises its clocks over the first ~100 ms of load; a region that follows host-side
         set-up starts from low clocks again)."""
@@ -136,8 +145,8 @@ def main():
     o_ctx = torch.empty_like(r.q_ctx)
     q = r.q_self[:spec.q_len].contiguous()
     out = torch.empty_like(q)
-    ws = torch.empty(max(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, spec.q_len),
-                         B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1)) // 4, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, spec.q_len, spec.total_ctx_len),
+                         B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1, spec.total_ctx_len)) // 4, dtype=torch.float32, device=dev)
     qd = [r.q_self[spec.q_len + i:spec.q_len + i + 1].contiguous() for i in range(args.decode_steps)]
     outd = torch.empty_like(qd[0]) if qd else None
     # decode calls marshalled once (argument marshalling only; the request's self_len grows by one per token)
@@ -157,9 +166,16 @@ def main():
             fn()
         if ev: ev[3].record()
 
-    for _ in range(args.warmup):
+    # untimed steps: the requested count, then on until WARM_MS of GPU time have been spent under load
+    warm_ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    warm_steps, warm_spent = 0, 0.0
+    while warm_steps < args.warmup or warm_spent < WARM_MS:
+        warm_ev[0].record()
         step()
-    torch.cuda.synchronize()
+        warm_ev[1].record()
+        torch.cuda.synchronize()
+        warm_spent += warm_ev[0].elapsed_time(warm_ev[1])
+        warm_steps += 1
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -211,6 +227,7 @@ def main():
                 "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(roof["kernel"])
+    roof["traffic_source"] = TRAFFIC_SOURCE
     roof["launch_ms"] = float({"flash_encode_kernel": ms_enc, "flash_prefill_kernel": ms_pre, "decode_kernel": ms_dec / max(1, args.decode_steps)}[roof["kernel"]])
 
     seq_cmp = None
@@ -251,7 +268,7 @@ def main():
         del ws_t
 
     cfg_res = None
-    if args.all_configs:
+    if not args.no_other_configs:
         cfg_res = {}
         for cfg in (2, 4):
             sp = W.CONFIGS[cfg]
@@ -267,8 +284,8 @@ def main():
             oo = torch.empty_like(qq)
             q1 = rr.q_self[sp.q_len:sp.q_len + 1].contiguous()
             o1 = torch.empty_like(q1)
-            wsc = torch.empty(max(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, sp.q_len),
-                                  B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1)) // 4, dtype=torch.float32, device=dev)
+            wsc = torch.empty(max(B.workspace_bytes(B.APE_OP_PREFILL, shape, 1, sp.q_len, sp.total_ctx_len),
+                                  B.workspace_bytes(B.APE_OP_DECODE, shape, 1, 1, sp.total_ctx_len)) // 4, dtype=torch.float32, device=dev)
             fn_dec, arr_dec = B.decode_call(shape, [rq], q1, o1, None, wsc)
             arr_dec[0].self_len = sp.q_len + 1
             ms_e = timed(lambda: B.encode_chunks(shape, None, rr.k_prefix, rr.v_prefix, rr.q_ctx, rr.k_ctx, rr.v_ctx, cu_c, cu_c_dev, None, oc), 50)
@@ -279,9 +296,12 @@ def main():
             enc_bytes = 2.0 * (2 * rr.q_ctx.numel() + rr.k_ctx.numel() + rr.v_ctx.numel())       # Q read, O written, K and V read
             cfg_res[sp.name] = {
                 "encode_ms": ms_e, "encode_tflops": 4.0 * d * hq * e_pairs / (ms_e * 1e-3) / 1e12,
-                "encode_hbm_gbs": enc_bytes / (ms_e * 1e-3) / 1e9,
+                "encode_frac_mfma_peak": 4.0 * d * hq * e_pairs / (ms_e * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "encode_hbm_gbs": enc_bytes / (ms_e * 1e-3) / 1e9, "encode_frac_hbm_peak": enc_bytes / (ms_e * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "prefill_ms": ms_p, "prefill_tflops": 4.0 * d * hq * p_pairs / (ms_p * 1e-3) / 1e12,
+                "prefill_frac_mfma_peak": 4.0 * d * hq * p_pairs / (ms_p * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                 "decode_ms_per_token": ms_d, "decode_gbs": (kv_row_bytes * kv_tok) / (ms_d * 1e-3) / 1e9,
+                "decode_frac_hbm_peak": (kv_row_bytes * kv_tok) / (ms_d * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "shape": "%d chunks x %d, prefix %d, %d query rows" % (len(sp.chunk_lens), sp.chunk_lens[0], sp.prefix_len, sp.q_len)}
             if kv_row_bytes * kv_tok < 128e6:
                 # a cache this small stays in the last-level cache when one call is looped: rotate over
@@ -304,6 +324,7 @@ def main():
                 cfg_res[sp.name]["decode_note"] = "one call looped: its %.0f MB of KV stay in the last-level cache" % (kv_row_bytes * kv_tok / 1e6)
                 cfg_res[sp.name]["decode_rotated_ms_per_token"] = ms_rot
                 cfg_res[sp.name]["decode_rotated_gbs"] = (kv_row_bytes * kv_tok) / (ms_rot * 1e-3) / 1e9
+                cfg_res[sp.name]["decode_rotated_frac_hbm_peak"] = (kv_row_bytes * kv_tok) / (ms_rot * 1e-3) / 1e9 / PEAK_HBM_GBS
                 cfg_res[sp.name]["decode_rotated_note"] = "%d copies of the request in turn (%.0f MB): every call reads from HBM" % (n_rot, n_rot * kv_row_bytes * kv_tok / 1e6)
                 del rot
             del rr, rq, oc, wsc
@@ -335,6 +356,32 @@ def main():
                              "projections are rocBLAS GEMMs"}
         del xl, yl, kcl, vcl, ws_l, wts
 
+    layers_res = None
+    if args.layers > 0:
+        hidden, inter, nl = 4096, 14336, args.layers
+        gw = torch.Generator(device=dev)
+        gw.manual_seed(r.seed + 9)
+        rn = lambda *sh, scale=1.0: (torch.randn(sh, generator=gw, device=dev, dtype=torch.float32) * scale).to(torch.bfloat16)
+        keep, lws = [], []
+        for _ in range(nl):
+            wts = dict(attn_norm=torch.ones(hidden, dtype=torch.bfloat16, device=dev), w_qkv=rn((hq + 2 * hkv) * d, hidden, scale=hidden ** -0.5),
+                       w_o=rn(hidden, hq * d, scale=(hq * d) ** -0.5), mlp_norm=torch.ones(hidden, dtype=torch.bfloat16, device=dev),
+                       w_gate_up=rn(2 * inter, hidden, scale=hidden ** -0.5), w_down=rn(hidden, inter, scale=inter ** -0.5))
+            keep.append(wts)
+            lws.append(B.layer_weights(hidden, inter, 1e-5, 500000.0, **wts))
+        m_tok = spec.total_ctx_len
+        xl = rn(m_tok, hidden)
+        yl = torch.empty_like(xl)
+        kcs = [torch.empty_like(r.k_ctx) for _ in range(nl)]
+        vcs = [torch.empty_like(r.v_ctx) for _ in range(nl)]
+        kps, vps = [r.k_prefix] * nl, [r.v_prefix] * nl
+        ws_l = torch.empty(B.layer_workspace_bytes(shape, hidden, inter, m_tok, n_layers=nl) // 4, dtype=torch.float32, device=dev)
+        ms_ls = timed(lambda: B.layers_encode(shape, lws, xl, kps, vps, cu, cu_dev, kcs, vcs, yl, ws_l), 2)
+        layers_res = {"layers": nl, "ms": ms_ls, "ms_per_layer": ms_ls / nl,
+                      "note": "ape_layers_encode: %d Llama-3-8B-shaped layers (random weights), 131072 context tokens as 64 x 2048, "
+                              "every layer writing its own KV cache" % nl}
+        del xl, yl, kcs, vcs, ws_l, keep
+
     batch_res = None
     if args.prefill_batch > 0:
         nb = args.prefill_batch
@@ -345,7 +392,7 @@ def main():
             reqs_b.append(B.Request(rr.k_prefix, rr.v_prefix, kb_, vb_, rr.k_self, rr.v_self, spec.q_len, rr.temperature, rr.scale))
         qb = torch.stack([rr.q_self[:spec.q_len] for rr in rb]).contiguous()
         ob = torch.empty_like(qb)
-        ws_b = torch.empty(B.workspace_bytes(B.APE_OP_PREFILL, shape, nb, spec.q_len) // 4, dtype=torch.float32, device=dev)
+        ws_b = torch.empty(B.workspace_bytes(B.APE_OP_PREFILL, shape, nb, spec.q_len, spec.total_ctx_len) // 4, dtype=torch.float32, device=dev)
 
         def batch_call():
             B.attention_prefill_batch(shape, reqs_b, qb, ob, None, ws_b)
@@ -430,7 +477,7 @@ def main():
             reqs.append(B.Request(rr.k_prefix, rr.v_prefix, k5, v5, rr.k_self, rr.v_self, 1, rr.temperature, rr.scale))
         q5 = torch.stack([rr.q_self for rr in rs], dim=1).contiguous()          # [steps, batch, Hq, d]
         o5 = torch.empty_like(q5[0])
-        ws5 = torch.empty(B.workspace_bytes(B.APE_OP_DECODE, shape, spec5.batch, 1) // 4, dtype=torch.float32, device=dev)
+        ws5 = torch.empty(B.workspace_bytes(B.APE_OP_DECODE, shape, spec5.batch, 1, spec5.total_ctx_len) // 4, dtype=torch.float32, device=dev)
 
         calls5 = []
         for s in range(spec5.decode_steps):
@@ -476,6 +523,7 @@ def main():
     line = {
         "metric": "APE attn TFLOP/s (query prefill over 128K cached KV) + decode HBM GB/s",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "warm_steps": warm_steps, "warm_ms": warm_spent,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config 3: 128K context (64 chunks x 2048 + prefix 32), Llama-3-8B heads (32q/8kv, d=128), "
@@ -499,6 +547,8 @@ def main():
         line["prefill_batch"] = batch_res
     if layer_res is not None:
         line["layer_encode"] = layer_res
+    if layers_res is not None:
+        line["layers_encode"] = layers_res
     if cfg_res is not None:
         line["other_configs"] = cfg_res
     print(json.dumps(line))

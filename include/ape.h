@@ -13,8 +13,6 @@
  *                          the pooled context partition sum is raised to S.
  *   ape_rope_write_cache   rotary embedding with positions re-used across contexts
  *                          (Section 1) fused with the KV-cache write, in front of the above.
- *   ape_layer_encode       one whole layer (projections and MLP as library GEMMs) around the
- *                          encode attention, for a per-layer prefill latency (Section 5.4).
  *   ape_attention_tree     the same over a tree of contexts with a scaling factor per
  *                          node (Appendix C.2 and C.5); S per context is one such tree.
  *
@@ -22,6 +20,9 @@
  *   - Every data pointer marked DEVICE points to GPU memory owned by the caller;
  *     the library never allocates, frees or copies device memory and keeps no
  *     state between calls.  Pointers marked HOST are read during the call only.
+ *     (The library depends on the HIP runtime alone.  Whole transformer layers around the
+ *     attention, which need a GEMM library and its handle, are a separate shared object with a
+ *     header of its own, ape_layer.h.)
  *   - Every data pointer is 16-byte aligned (rows of head_dim elements then are too: the kernels
  *     use 16-byte accesses); that holds for the pointers inside device tables (k_chunks[i], the
  *     caches of ape_rope_write_cache) as well, which the host cannot check.  Tables themselves are
@@ -37,8 +38,9 @@
  *     the host before anything is launched and leave all outputs untouched.
  *     ape_last_error() gives a thread-local description of the last failure.
  *   - LogSumExp outputs are natural-log, fp32.
- *   - Size limits of one call (APE_ERR_UNSUPPORTED beyond, nothing launched): query calls write at
- *     most 2^24 (row, head) outputs (batch x q_len x n_q_heads); an encode on the matrix-core path
+ *   - Size limits of one call (APE_ERR_UNSUPPORTED beyond, nothing launched): query calls write
+ *     fewer than 2^24 (row, head) outputs (batch x q_len x n_q_heads); the attention launch of a tree
+ *     call (split slots x KV heads x query tiles) has fewer than 2^24 workgroups; an encode on the matrix-core path
  *     launches contexts x n_kv_heads x ceil(longest context x heads-per-KV-head / 128) workgroups and
  *     takes fewer than 2^24 of them, on the other paths fewer than 2^26 (row, head) outputs.  Token
  *     counts are 32-bit (a call covers fewer than 2^31 tokens); byte offsets are 64-bit throughout.
@@ -91,7 +93,9 @@ typedef struct {
     const void *const *k_chunks;       /* DEVICE array [n_chunks] of DEVICE pointers, chunk i: [l_i, n_kv_heads, d] */
     const void *const *v_chunks;       /* DEVICE array [n_chunks] of DEVICE pointers                                */
     const int32_t *cu_chunk_lens;      /* DEVICE [n_chunks + 1]: 0, l_1, l_1+l_2, ..., total_ctx_len                */
-    int32_t total_ctx_len;             /* HOST copy of cu_chunk_lens[n_chunks]; the caller keeps the two equal      */
+    int32_t total_ctx_len;             /* HOST copy of cu_chunk_lens[n_chunks]; the caller keeps the two equal.     */
+                                       /* Token counts are 32-bit: one request holds fewer than 2^31 context tokens */
+                                       /* (4 TB of K at the Llama-3-8B shape, beyond any one GPU's memory)          */
     int32_t self_len;                  /* tokens in k_self/v_self INCLUDING the rows being queried; >= q_len >= 1   */
     const void *k_self;                /* DEVICE [self_len, n_kv_heads, head_dim]: query + generated tokens         */
     const void *v_self;                /* DEVICE                                                                     */
@@ -102,12 +106,15 @@ typedef struct {
 /*
  * Bytes of caller-provided DEVICE workspace an operation needs (0 is possible).
  * An upper bound that depends only on the arguments given, never on the data.
- *   op       ape_op
- *   batch    requests (decode, batched prefill); 1 for ape_attention_prefill; ignored for encode
- *   q_len    query rows per request (prefill); 1 for decode; ignored for encode
+ *   op            ape_op
+ *   batch         requests (decode, batched prefill); 1 for ape_attention_prefill; ignored for encode
+ *   q_len         query rows per request (prefill); 1 for decode; ignored for encode
+ *   max_total_kv  the largest total_ctx_len of any request the workspace will serve; the result
+ *                 covers every call whose contexts are no longer than that.  Negative: no limit known,
+ *                 the result then covers every context length (the most splits the planner ever uses).
  * Returns 0 on invalid arguments as well; the entry points re-validate.
  */
-size_t ape_workspace_bytes(int op, const ape_shape *shape, int32_t batch, int32_t q_len);
+size_t ape_workspace_bytes(int op, const ape_shape *shape, int32_t batch, int32_t q_len, int64_t max_total_kv);
 
 /*
  * Pre-caching attention of Section 2.2 with the shared prefix of Section 4.1.
@@ -143,7 +150,7 @@ int ape_encode_chunks(const ape_shape *shape,
  *             own KV: row r sees self tokens 0 .. self_len - q_len + r.
  *   q, out    DEVICE [q_len, n_q_heads, d]
  *   lse_out   DEVICE fp32 [n_q_heads, q_len] or NULL: log(Z_prefix + Z_ctx^S + Z_self)
- *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_PREFILL, shape, 1, q_len), 256-byte aligned
+ *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_PREFILL, shape, 1, q_len, req->total_ctx_len), 256-byte aligned
  */
 int ape_attention_prefill(const ape_shape *shape, const ape_request *req,
                           const void *q, int32_t q_len, void *out, float *lse_out,
@@ -157,7 +164,7 @@ int ape_attention_prefill(const ape_shape *shape, const ape_request *req,
  *   reqs      HOST array [batch]
  *   q, out    DEVICE [batch, q_len, n_q_heads, d]
  *   lse_out   DEVICE fp32 [batch, n_q_heads, q_len] or NULL
- *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_PREFILL, shape, batch, q_len), 256-byte aligned
+ *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_PREFILL, shape, batch, q_len, longest context), 256-byte aligned
  */
 int ape_attention_prefill_batch(const ape_shape *shape, const ape_request *reqs, int32_t batch,
                                 const void *q, int32_t q_len, void *out, float *lse_out,
@@ -171,7 +178,7 @@ int ape_attention_prefill_batch(const ape_shape *shape, const ape_request *reqs,
  *   reqs      HOST array [batch]
  *   q, out    DEVICE [batch, n_q_heads, d]
  *   lse_out   DEVICE fp32 [batch, n_q_heads] or NULL
- *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_DECODE, shape, batch, 1), 256-byte aligned
+ *   workspace DEVICE, >= ape_workspace_bytes(APE_OP_DECODE, shape, batch, 1, longest context), 256-byte aligned
  */
 int ape_attention_decode(const ape_shape *shape, const ape_request *reqs, int32_t batch,
                          const void *q, void *out, float *lse_out,
@@ -277,50 +284,6 @@ int ape_rope_write_cache(const ape_shape *shape,
                          const int32_t *cu_chunk_lens_host, const int32_t *cu_chunk_lens_dev, int32_t n_chunks,
                          int32_t position_offset, float rope_base,
                          void *q_rot, void *const *k_cache, void *const *v_cache, void *stream);
-
-/*
- * Weights of one transformer layer (the published Llama layer of the models the paper evaluates;
- * Section 5.4 measures their prefill).  All DEVICE, dtype of the shape, [out_features, in_features]
- * row-major.
- */
-typedef struct {
-    int32_t hidden;             /* model width, multiple of 8                                        */
-    int32_t intermediate;       /* MLP width, multiple of 8                                          */
-    float rms_eps;              /* RMSNorm epsilon                                                   */
-    float rope_base;            /* rotary base                                                       */
-    const void *attn_norm;      /* [hidden]                                                          */
-    const void *w_qkv;          /* [(n_q_heads + 2 n_kv_heads) d, hidden]: Q rows, then K, then V    */
-    const void *w_o;            /* [hidden, n_q_heads d]                                             */
-    const void *mlp_norm;       /* [hidden]                                                          */
-    const void *w_gate_up;      /* [2 intermediate, hidden]: gate rows, then up rows                 */
-    const void *w_down;         /* [hidden, intermediate]                                            */
-} ape_layer_weights;
-
-/* Bytes of DEVICE workspace ape_layer_encode needs for total_rows packed context tokens. */
-size_t ape_layer_workspace_bytes(const ape_shape *shape, int32_t hidden, int32_t intermediate, int32_t total_rows);
-
-/*
- * One layer of the context pre-caching pass (Section 2.2) over the packed contexts:
- *   h = RMSNorm(x);  q, k, v = h Wqkv^T;  q, k rotated with positions re-used across contexts
- *   (token j of every context at prefix_len + j);  k, v written to the cache;
- *   a = ape_encode_chunks attention (prefix KV + own context, causal);  x1 = x + a Wo^T;
- *   y = x1 + (SiLU(g) * u) Wd^T with [g, u] = RMSNorm(x1) Wgate_up^T.
- * The four matrix products are rocBLAS GEMMs with fp32 accumulation (this entry point alone makes
- * the library keep state: one rocBLAS handle per device, created at the first call and bound to the
- * call's stream, so calls on one device must not overlap in time from different host threads);
- * everything between them runs in this library's kernels.  Intermediate tensors have the dtype of
- * the shape.
- *
- *   x, y               DEVICE packed [M, hidden], M = cu_chunk_lens_host[n_chunks]; y may not alias x
- *   k_prefix, v_prefix DEVICE [prefix_len, n_kv_heads, d]: THIS layer's cached prefix KV (rotated)
- *   k_cache, v_cache   DEVICE packed [M, n_kv_heads, d]: receive this layer's context KV
- *   workspace          DEVICE, >= ape_layer_workspace_bytes(shape, hidden, intermediate, M)
- */
-int ape_layer_encode(const ape_shape *shape, const ape_layer_weights *weights, const void *x,
-                     const void *k_prefix, const void *v_prefix, int32_t prefix_len,
-                     const int32_t *cu_chunk_lens_host, const int32_t *cu_chunk_lens_dev, int32_t n_chunks,
-                     void *k_cache, void *v_cache, void *y,
-                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* Text for a status code (static storage). */
 const char *ape_status_string(int status);

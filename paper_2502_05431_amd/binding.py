@@ -16,6 +16,7 @@ import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libape_hip.so")
+LAYER_LIB_PATH = os.path.join(_PKG, "libape_layer.so")
 
 APE_OK = 0
 APE_ERR_INVALID_ARG, APE_ERR_UNSUPPORTED, APE_ERR_WORKSPACE, APE_ERR_DEVICE = -1, -2, -3, -4
@@ -26,8 +27,8 @@ APE_OP_ENCODE, APE_OP_PREFILL, APE_OP_DECODE = 0, 1, 2
 EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", "ape_attention_decode",
            "ape_attention_prefill_batch", "ape_attention_decode_static",
            "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
-           "ape_layer_workspace_bytes", "ape_layer_encode",
            "ape_status_string", "ape_last_error", "ape_version")
+LAYER_EXPORTS = ("ape_layer_workspace_bytes", "ape_layers_workspace_bytes", "ape_layer_encode", "ape_layers_encode")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
 APE_STATIC_SCRATCH_BYTES = 8 << 20
 
@@ -59,6 +60,10 @@ class ApeLayerWeights(ctypes.Structure):
                 ("w_down", ctypes.c_void_p)]
 
 
+class ApeLayerTaps(ctypes.Structure):
+    _fields_ = [("q_rot", ctypes.c_void_p), ("attn", ctypes.c_void_p)]
+
+
 class ApeError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__("ape status %d: %s" % (status, message))
@@ -77,7 +82,7 @@ def load() -> ctypes.CDLL:
                                "(there is no fallback path)" % LIB_PATH)
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
-        lib.ape_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(ApeShape), i32, i32]
+        lib.ape_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(ApeShape), i32, i32, ctypes.c_int64]
         lib.ape_workspace_bytes.restype = sz
         lib.ape_encode_chunks.argtypes = [ctypes.POINTER(ApeShape), vp, vp, vp, i32, vp, vp, vp, vp, vp, i32,
                                           vp, vp, vp, vp, vp, sz, vp]
@@ -101,17 +106,38 @@ def load() -> ctypes.CDLL:
         lib.ape_rope_write_cache.argtypes = [ctypes.POINTER(ApeShape), vp, vp, vp, vp, vp, i32, i32, ctypes.c_float,
                                              vp, vp, vp, vp]
         lib.ape_rope_write_cache.restype = ctypes.c_int
-        lib.ape_layer_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32]
-        lib.ape_layer_workspace_bytes.restype = sz
-        lib.ape_layer_encode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeLayerWeights), vp, vp, vp, i32,
-                                         vp, vp, i32, vp, vp, vp, vp, sz, vp]
-        lib.ape_layer_encode.restype = ctypes.c_int
         lib.ape_status_string.argtypes = [ctypes.c_int]
         lib.ape_status_string.restype = ctypes.c_char_p
         lib.ape_last_error.restype = ctypes.c_char_p
         lib.ape_version.restype = ctypes.c_char_p
         _lib = lib
     return _lib
+
+
+_layer_lib = None
+
+
+def load_layer() -> ctypes.CDLL:
+    """Load the layer library (rocBLAS-backed layers around the attention); raises if it has not been built."""
+    global _layer_lib
+    if _layer_lib is None:
+        load()                                         # the attention library first: the layer library links against it
+        if not os.path.exists(LAYER_LIB_PATH):
+            raise RuntimeError("%s is missing: build it with `python -m paper_2502_05431_amd.build`" % LAYER_LIB_PATH)
+        lib = ctypes.CDLL(LAYER_LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        lib.ape_layer_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32]
+        lib.ape_layer_workspace_bytes.restype = sz
+        lib.ape_layers_workspace_bytes.argtypes = [ctypes.POINTER(ApeShape), i32, i32, i32, i32]
+        lib.ape_layers_workspace_bytes.restype = sz
+        lib.ape_layer_encode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeLayerWeights), vp, vp, vp, i32,
+                                         vp, vp, i32, vp, vp, vp, ctypes.POINTER(ApeLayerTaps), vp, sz, vp]
+        lib.ape_layer_encode.restype = ctypes.c_int
+        lib.ape_layers_encode.argtypes = [ctypes.POINTER(ApeShape), ctypes.POINTER(ApeLayerWeights), i32, vp, vp, vp, i32,
+                                          vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.ape_layers_encode.restype = ctypes.c_int
+        _layer_lib = lib
+    return _layer_lib
 
 
 def _check(rc: int):
@@ -140,8 +166,9 @@ def make_shape(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype, generic: b
     return ApeShape(n_q_heads, n_kv_heads, head_dim, code | (APE_DTYPE_FLAG_GENERIC if generic else 0))
 
 
-def workspace_bytes(op: int, shape: ApeShape, batch: int = 1, q_len: int = 1) -> int:
-    return int(load().ape_workspace_bytes(op, ctypes.byref(shape), batch, q_len))
+def workspace_bytes(op: int, shape: ApeShape, batch: int = 1, q_len: int = 1, max_total_kv: int = -1) -> int:
+    """``ape_workspace_bytes``; ``max_total_kv`` = longest context the workspace will serve (-1: any)."""
+    return int(load().ape_workspace_bytes(op, ctypes.byref(shape), batch, q_len, max_total_kv))
 
 
 @dataclass
@@ -308,21 +335,50 @@ def layer_weights(hidden: int, intermediate: int, rms_eps: float, rope_base: flo
                            mlp_norm.data_ptr(), w_gate_up.data_ptr(), w_down.data_ptr())
 
 
-def layer_workspace_bytes(shape: ApeShape, hidden: int, intermediate: int, total_rows: int) -> int:
-    return int(load().ape_layer_workspace_bytes(ctypes.byref(shape), hidden, intermediate, total_rows))
+def layer_workspace_bytes(shape: ApeShape, hidden: int, intermediate: int, total_rows: int, n_layers: int = 1) -> int:
+    if n_layers == 1:
+        return int(load_layer().ape_layer_workspace_bytes(ctypes.byref(shape), hidden, intermediate, total_rows))
+    return int(load_layer().ape_layers_workspace_bytes(ctypes.byref(shape), hidden, intermediate, total_rows, n_layers))
+
+
+def _cu_host(cu_chunk_lens):
+    n_chunks = len(cu_chunk_lens) - 1 if cu_chunk_lens is not None and len(cu_chunk_lens) else 0
+    cu_host = (ctypes.c_int32 * (n_chunks + 1))(*cu_chunk_lens) if n_chunks else None
+    return n_chunks, cu_host, (ctypes.cast(cu_host, ctypes.c_void_p) if cu_host is not None else None)
 
 
 def layer_encode(shape: ApeShape, weights: ApeLayerWeights, x, k_prefix, v_prefix, cu_chunk_lens: Sequence[int],
-                 cu_chunk_lens_dev, k_cache, v_cache, y, workspace, stream=None):
-    """``ape_layer_encode``: x/y [M, hidden]; k_cache/v_cache packed [M, Hkv, d]."""
-    n_chunks = len(cu_chunk_lens) - 1 if cu_chunk_lens is not None and len(cu_chunk_lens) else 0
-    cu_host = (ctypes.c_int32 * (n_chunks + 1))(*cu_chunk_lens) if n_chunks else None
+                 cu_chunk_lens_dev, k_cache, v_cache, y, workspace, stream=None, q_rot_tap=None, attn_tap=None):
+    """``ape_layer_encode``: x/y [M, hidden]; k_cache/v_cache packed [M, Hkv, d]; the taps, if given,
+    receive the rotated queries and the attention output [M, Hq, d]."""
+    n_chunks, _keep, cu_ptr = _cu_host(cu_chunk_lens)
     prefix_len = 0 if k_prefix is None else k_prefix.shape[0]
-    rc = load().ape_layer_encode(ctypes.byref(shape), ctypes.byref(weights), _ptr(x), _ptr(k_prefix), _ptr(v_prefix), prefix_len,
-                                 ctypes.cast(cu_host, ctypes.c_void_p) if cu_host is not None else None,
-                                 _ptr(cu_chunk_lens_dev), n_chunks, _ptr(k_cache), _ptr(v_cache), _ptr(y),
-                                 _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
-                                 _stream(stream))
+    taps = None
+    if q_rot_tap is not None or attn_tap is not None:
+        taps = ApeLayerTaps(None if q_rot_tap is None else q_rot_tap.data_ptr(), None if attn_tap is None else attn_tap.data_ptr())
+    rc = load_layer().ape_layer_encode(ctypes.byref(shape), ctypes.byref(weights), _ptr(x), _ptr(k_prefix), _ptr(v_prefix), prefix_len,
+                                       cu_ptr, _ptr(cu_chunk_lens_dev), n_chunks, _ptr(k_cache), _ptr(v_cache), _ptr(y),
+                                       ctypes.byref(taps) if taps is not None else None,
+                                       _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                       _stream(stream))
+    _check(rc)
+
+
+def layers_encode(shape: ApeShape, weights: Sequence[ApeLayerWeights], x, k_prefix: Optional[Sequence], v_prefix: Optional[Sequence],
+                  cu_chunk_lens: Sequence[int], cu_chunk_lens_dev, k_cache: Sequence, v_cache: Sequence, y, workspace, stream=None):
+    """``ape_layers_encode``: a stack of layers; per-layer lists of prefix KV (or None) and cache tensors."""
+    n_layers = len(weights)
+    n_chunks, _keep, cu_ptr = _cu_host(cu_chunk_lens)
+    warr = (ApeLayerWeights * n_layers)(*weights)
+    table = lambda ts: (ctypes.c_void_p * n_layers)(*[t.data_ptr() for t in ts])
+    prefix_len = 0 if not k_prefix else k_prefix[0].shape[0]
+    kp = table(k_prefix) if prefix_len else None
+    vp = table(v_prefix) if prefix_len else None
+    kc, vc = table(k_cache), table(v_cache)
+    rc = load_layer().ape_layers_encode(ctypes.byref(shape), warr, n_layers, _ptr(x), kp, vp, prefix_len,
+                                        cu_ptr, _ptr(cu_chunk_lens_dev), n_chunks, kc, vc, _ptr(y),
+                                        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                        _stream(stream))
     _check(rc)
 
 

@@ -1,4 +1,5 @@
-"""Builds ``libape_hip.so`` (the C-ABI HIP library) for gfx950 with hipcc.
+"""Builds ``libape_hip.so`` (the C-ABI attention library; depends on the HIP runtime only) and
+``libape_layer.so`` (whole layers around it; links rocBLAS and libape_hip.so) for gfx950 with hipcc.
 
 Usage: ``python -m paper_2502_05431_amd.build`` (cross-compiles without a GPU).
 """
@@ -15,12 +16,14 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libape_hip.so")
+LAYER_LIB = os.path.join(PKG, "libape_layer.so")
 RESOURCES = os.path.join(PKG, "_build", "kernel_resources.json")
 
 # -packed-fp32-ops off: packed fp32 VALU forms are not used on the test machines.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+               "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+               "-I", os.path.join(CSRC, "layer")]
 
 
 # Per-file flags.  The flash kernels keep every MFMA accumulator in the vector registers (the
@@ -34,6 +37,10 @@ EXTRA_FLAGS = {
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+
+
+def layer_sources():
+    return sorted(glob.glob(os.path.join(CSRC, "layer", "*.hip")))
 
 
 _REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|"
@@ -58,13 +65,14 @@ def parse_resources(compiler_output: str) -> dict:
 def build(verbose: bool = True, extra=()) -> str:
     objs = []
     procs = []
-    for src in sources():
+    layer_objs = []
+    for src in sources() + layer_sources():
         obj = os.path.join(PKG, "_build", os.path.basename(src) + ".o")
         os.makedirs(os.path.dirname(obj), exist_ok=True)
         cmd = ["hipcc", *[f for f in HIPCC_FLAGS if f != "-shared"], *EXTRA_FLAGS.get(os.path.basename(src), []),
                "-Rpass-analysis=kernel-resource-usage", *extra, "-c", src, "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-        objs.append(obj)
+        (layer_objs if os.path.dirname(src).endswith("layer") else objs).append(obj)
     failed = False
     resources = {}
     for src, p in procs:
@@ -79,8 +87,13 @@ def build(verbose: bool = True, extra=()) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     tmp = LIB + ".tmp%d" % os.getpid()
-    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs, "-lrocblas"])
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
     os.replace(tmp, LIB)
+    # the layer library finds the attention library next to itself ($ORIGIN)
+    tmp = LAYER_LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *layer_objs,
+                           "-L" + PKG, "-lape_hip", "-Wl,-rpath,$ORIGIN", "-lrocblas"])
+    os.replace(tmp, LAYER_LIB)
     with open(RESOURCES, "w") as f:
         json.dump(resources, f, indent=1, sort_keys=True)
     return LIB

@@ -11,8 +11,8 @@
 
 namespace ape {
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
 int fail(int code, const char* fmt, ...) {
     va_list ap;
@@ -21,6 +21,8 @@ int fail(int code, const char* fmt, ...) {
     va_end(ap);
     return code;
 }
+
+namespace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -35,11 +37,7 @@ inline bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
     } while (0)
 inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 
-struct ShapeInfo {
-    int hq, hkv, d, dtype, group;
-    bool force_generic;
-    bool mfma;                  // matrix-core kernels cover this shape
-};
+}  // namespace
 
 int check_shape(const ape_shape* s, ShapeInfo* o) {
     if (!s) return fail(APE_ERR_INVALID_ARG, "shape is NULL");
@@ -56,6 +54,8 @@ int check_shape(const ape_shape* s, ShapeInfo* o) {
               (o->group == 1 || o->group == 2 || o->group == 4 || o->group == 8);
     return APE_OK;
 }
+
+namespace {
 
 int check_request(const ape_request* r, int q_len, int idx) {
     if (r->prefix_len < 0) return fail(APE_ERR_INVALID_ARG, "request %d: prefix_len %d < 0", idx, r->prefix_len);
@@ -76,9 +76,11 @@ int check_request(const ape_request* r, int q_len, int idx) {
 
 // Launch sizes: a grid times its workgroup size must stay below 2^32 work items and every count the
 // kernels index with fits an int.  Calls beyond that are refused here, before any size is narrowed.
-constexpr long kMaxUnits = 1L << 24;            // (row, head) outputs of one query call: one 256-thread workgroup each in the merge
+constexpr long kMaxUnits = 1L << 24;            // a query call writes FEWER (row, head) outputs than this: one 256-thread workgroup each in the merge
+constexpr long kMaxTreeBlocks = 1L << 24;       // workgroups of the attention launch of a tree call (256 threads each)
 constexpr long kMaxEncodeBlocks = 1L << 24;     // workgroups of the matrix-core encode (256 threads each)
 constexpr long kMaxEncodeUnits = 1L << 26;      // (row, head) outputs of the generic encode: one wavefront each
+}  // namespace
 
 int check_encode_size(const ShapeInfo& si, int n_chunks, int max_len, long total_rows) {
     if (si.mfma) {
@@ -93,6 +95,8 @@ int check_encode_size(const ShapeInfo& si, int n_chunks, int max_len, long total
     }
     return APE_OK;
 }
+
+namespace {
 
 KvView to_view(const ape_request* r) {
     KvView v;
@@ -239,21 +243,27 @@ const char* ape_status_string(int status) {
 const char* ape_last_error(void) { return g_err; }
 const char* ape_version(void) { return "0.1.0"; }
 
-size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_t q_len) {
+size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_t q_len, int64_t max_total_kv) {
     ShapeInfo si;
     if (check_shape(shape, &si) != APE_OK) return 0;
     if (op == APE_OP_ENCODE) return 0;
     if (op == APE_OP_DECODE) q_len = 1;
     else if (op != APE_OP_PREFILL) return 0;
     if (batch < 1 || q_len < 1) return 0;
-    if ((long)batch * q_len * si.hq > kMaxUnits) return 0;     // the entry points refuse such a call
-    // worst case over every context length: as many context splits as the planner can ask for, + 1.
-    // The prefill plan changes its query tile and its workgroup target with the context length; within
-    // each of the three ranges the count before rounding only grows with the length, so their upper ends decide.
-    int n_max = kMaxSplits;
-    if (op == APE_OP_PREFILL) {
-        n_max = 0;
-        for (long ctx : {kPrefillOneWorkgroupPerCuMaxCtx, kPrefillNarrowTileMaxCtx, (long)kMaxSplits * (1 << 20)}) {
+    if ((long)batch * q_len * si.hq >= kMaxUnits) return 0;     // the entry points refuse such a call
+    // The most context splits any call can ask for whose longest context has at most max_total_kv
+    // tokens (negative: any length), + 1 for prefix + self.  Decode: the count only grows with the
+    // length.  Prefill: the plan changes its query tile and its workgroup target with the context
+    // length; within each of the three ranges the count before rounding only grows with the length,
+    // so the upper ends of the ranges below the cap, and the cap itself, decide.
+    const long any_len = (long)kMaxSplits * (1 << 20);
+    const long cap = max_total_kv < 0 || max_total_kv > any_len ? any_len : (long)max_total_kv;
+    int n_max = 0;
+    if (op == APE_OP_DECODE) {
+        n_max = decode_plan(si, batch, cap).n_bound;
+    } else {
+        for (long ctx : {kPrefillOneWorkgroupPerCuMaxCtx, kPrefillNarrowTileMaxCtx, cap}) {
+            if (ctx > cap) continue;
             const int n = prefill_plan(si, batch, q_len, ctx).n_bound;
             if (n > n_max) n_max = n;
         }
@@ -335,8 +345,8 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
     }
     APE_CHECK_ALIGNED(q, out);
     const long units = (long)batch * q_len * si.hq;
-    if (units > kMaxUnits)
-        return fail(APE_ERR_UNSUPPORTED, "%d requests x %d rows x %d heads = %ld outputs in one call, at most %ld are supported", batch, q_len, si.hq, units, kMaxUnits);
+    if (units >= kMaxUnits)
+        return fail(APE_ERR_UNSUPPORTED, "%d requests x %d rows x %d heads = %ld outputs in one call, fewer than %ld are supported", batch, q_len, si.hq, units, kMaxUnits);
     QueryPlan plan;
     if (decode) {
         plan = decode_plan(si, batch, max_ctx);
@@ -482,8 +492,8 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     rc = check_request(req, q_len, 0);
     if (rc) return rc;
     APE_CHECK_ALIGNED(q, out);
-    if ((long)q_len * si.hq > kMaxUnits)
-        return fail(APE_ERR_UNSUPPORTED, "%d rows x %d heads = %ld outputs in one call, at most %ld are supported", q_len, si.hq, (long)q_len * si.hq, kMaxUnits);
+    if ((long)q_len * si.hq >= kMaxUnits)
+        return fail(APE_ERR_UNSUPPORTED, "%d rows x %d heads = %ld outputs in one call, fewer than %ld are supported", q_len, si.hq, (long)q_len * si.hq, kMaxUnits);
     TreeMergeArgs m{};
     rc = check_tree(nodes_host, n_nodes, req->n_chunks, &m.n_levels, m.level_start);
     if (rc) return rc;
@@ -493,6 +503,24 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     if (plan.max_splits > kMaxTreeSplits)
         return fail(APE_ERR_UNSUPPORTED, "%d splits would be needed, at most %d are supported", plan.max_splits, kMaxTreeSplits);
     const long units = (long)q_len * si.hq;
+    // The attention grid is sized from the bound on the splits, not from the splits in use: one
+    // workgroup of 256 threads per (split slot, KV head[, query tile]); its work items must stay
+    // below 2^32.
+    {
+        const long slots = (long)plan.max_splits + 1;
+        long blocks;
+        if (si.mfma && q_len > 1) {
+            const long n_qtiles = ((long)q_len * si.group + plan.block_rows - 1) / plan.block_rows;
+            blocks = ((slots - 1) * si.hkv + 7) / 8 * 8 * n_qtiles + ((long)si.hkv + 7) / 8 * 8 * n_qtiles;
+        } else if (si.mfma) {
+            blocks = slots * si.hkv;
+        } else {
+            blocks = slots * units;
+        }
+        if (blocks >= kMaxTreeBlocks)
+            return fail(APE_ERR_UNSUPPORTED, "the tree call would launch %ld workgroups (%d split slots x heads x query tiles), fewer than %ld are "
+                        "supported: fewer nodes or fewer query rows per call", blocks, plan.max_splits + 1, kMaxTreeBlocks);
+    }
     const size_t need = plan.partial_bytes + plan.plan_bytes;
     if (!workspace || workspace_bytes < need)
         return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_tree_workspace_bytes gives the size)", workspace_bytes, need);
@@ -555,128 +583,6 @@ int ape_rope_write_cache(const ape_shape* shape,
     for (int c = 0; c < si.d / 2; ++c) a.inv_freq[c] = std::pow((double)rope_base, -2.0 * c / si.d);
     hipError_t he = launch_rope_write(a, si.dtype, (hipStream_t)stream);
     if (he != hipSuccess) return fail(APE_ERR_DEVICE, "rope kernel: %s", hipGetErrorString(he));
-    return APE_OK;
-}
-
-// ---- one layer around the encode attention -------------------------------------------------
-namespace {
-constexpr long kMlpSlabRows = 16384;           // rows of the MLP processed at a time (bounds the workspace)
-
-struct LayerPlan {
-    size_t h, qkv, q_rot, x1, gu, act, total;   // byte offsets into the workspace, and its size
-    long slab;
-};
-
-LayerPlan plan_layer(const ShapeInfo& si, int hidden, int inter, long rows) {
-    const size_t es = si.dtype == APE_F32 ? 4 : 2;
-    LayerPlan p;
-    p.slab = rows < kMlpSlabRows ? rows : kMlpSlabRows;
-    size_t off = 0;
-    auto take = [&](size_t elems) { const size_t at = off; off += align_up(elems * es, kWsAlign); return at; };
-    p.h = take((size_t)rows * hidden);
-    p.qkv = take((size_t)rows * (si.hq + 2 * si.hkv) * si.d);
-    p.q_rot = take((size_t)rows * si.hq * si.d);
-    p.x1 = take((size_t)rows * hidden);
-    p.gu = take((size_t)p.slab * 2 * inter);
-    p.act = take((size_t)p.slab * inter);
-    p.total = off;
-    return p;
-}
-
-int check_layer(const ape_layer_weights* w) {
-    if (!w) return fail(APE_ERR_INVALID_ARG, "layer weights are NULL");
-    if (w->hidden < 8 || w->hidden % 8 || w->intermediate < 8 || w->intermediate % 8)
-        return fail(APE_ERR_UNSUPPORTED, "hidden %d and intermediate %d must be positive multiples of 8", w->hidden, w->intermediate);
-    if (!(std::isfinite(w->rms_eps) && w->rms_eps >= 0.f)) return fail(APE_ERR_INVALID_ARG, "rms_eps must be finite and >= 0");
-    if (!(std::isfinite(w->rope_base) && w->rope_base > 0.f)) return fail(APE_ERR_INVALID_ARG, "rope_base must be finite and > 0");
-    if (!w->attn_norm || !w->w_qkv || !w->w_o || !w->mlp_norm || !w->w_gate_up || !w->w_down)
-        return fail(APE_ERR_INVALID_ARG, "a layer weight pointer is NULL");
-    return APE_OK;
-}
-}  // namespace
-
-size_t ape_layer_workspace_bytes(const ape_shape* shape, int32_t hidden, int32_t intermediate, int32_t total_rows) {
-    ShapeInfo si;
-    if (check_shape(shape, &si) != APE_OK) return 0;
-    if (hidden < 8 || hidden % 8 || intermediate < 8 || intermediate % 8 || total_rows < 0) return 0;
-    return plan_layer(si, hidden, intermediate, total_rows).total;
-}
-
-int ape_layer_encode(const ape_shape* shape, const ape_layer_weights* w, const void* x,
-                     const void* k_prefix, const void* v_prefix, int32_t prefix_len,
-                     const int32_t* cu_host, const int32_t* cu_dev, int32_t n_chunks,
-                     void* k_cache, void* v_cache, void* y,
-                     void* workspace, size_t workspace_bytes, void* stream) {
-    ShapeInfo si;
-    int rc = check_shape(shape, &si);
-    if (rc) return rc;
-    rc = check_layer(w);
-    if (rc) return rc;
-    if (prefix_len < 0 || n_chunks < 0) return fail(APE_ERR_INVALID_ARG, "prefix_len and n_chunks must be >= 0");
-    if (prefix_len > 0 && (!k_prefix || !v_prefix)) return fail(APE_ERR_INVALID_ARG, "prefix KV is NULL");
-    if (n_chunks == 0) return APE_OK;
-    if (!cu_host || !cu_dev) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens (host and device) are required");
-    if (cu_host[0] != 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens[0] must be 0");
-    int max_len = 0;
-    for (int i = 0; i < n_chunks; ++i) {
-        const long li = (long)cu_host[i + 1] - cu_host[i];
-        if (li < 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens is not non-decreasing at %d", i);
-        if (li > max_len) max_len = (int)li;
-    }
-    const long rows = cu_host[n_chunks];
-    if (rows == 0) return APE_OK;
-    if (!x || !y || !k_cache || !v_cache) return fail(APE_ERR_INVALID_ARG, "x, y, k_cache and v_cache must not be NULL");
-    APE_CHECK_ALIGNED(x, y, k_cache, v_cache, k_prefix, v_prefix, w->attn_norm, w->w_qkv, w->w_o, w->mlp_norm, w->w_gate_up, w->w_down);
-    rc = check_encode_size(si, n_chunks, max_len, rows);
-    if (rc) return rc;
-    const LayerPlan p = plan_layer(si, w->hidden, w->intermediate, rows);
-    if (!workspace || workspace_bytes < p.total)
-        return fail(APE_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed (ape_layer_workspace_bytes gives the size)", workspace_bytes, p.total);
-    if ((uintptr_t)workspace % kWsAlign) return fail(APE_ERR_WORKSPACE, "workspace must be %d-byte aligned", kWsAlign);
-    hipStream_t st = (hipStream_t)stream;
-    const size_t es = si.dtype == APE_F32 ? 4 : 2;
-    char* ws = (char*)workspace;
-    void *h = ws + p.h, *qkv = ws + p.qkv, *q_rot = ws + p.q_rot, *x1 = ws + p.x1, *gu = ws + p.gu, *act = ws + p.act;
-    const int hidden = w->hidden, inter = w->intermediate;
-    const int qd = si.hq * si.d, kvd = si.hkv * si.d, qkvd = qd + 2 * kvd;
-    auto dev_fail = [&](const char* what, hipError_t e) { return fail(APE_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e)); };
-
-    // attention half: norm -> QKV -> rotary embedding + cache write -> attention -> output projection + residual
-    hipError_t he = launch_rmsnorm(x, w->attn_norm, h, rows, hidden, w->rms_eps, si.dtype, st);
-    if (he != hipSuccess) return dev_fail("RMSNorm", he);
-    if (gemm_xwT(h, hidden, w->w_qkv, nullptr, qkv, qkvd, rows, qkvd, hidden, si.dtype, st)) return fail(APE_ERR_DEVICE, "QKV projection (rocBLAS) failed");
-    RopeArgs ra{};
-    ra.q_raw = qkv; ra.k_raw = (char*)qkv + (size_t)qd * es; ra.v_raw = (char*)qkv + (size_t)(qd + kvd) * es;
-    ra.q_rot = q_rot; ra.k_packed = k_cache; ra.v_packed = v_cache;
-    ra.q_stride = ra.k_stride = ra.v_stride = qkvd;
-    ra.cu = cu_dev; ra.n_chunks = n_chunks; ra.total_rows = (int)rows;
-    ra.n_q_heads = si.hq; ra.n_kv_heads = si.hkv; ra.head_dim = si.d; ra.position_offset = prefix_len;
-    for (int c = 0; c < si.d / 2; ++c) ra.inv_freq[c] = std::pow((double)w->rope_base, -2.0 * c / si.d);
-    he = launch_rope_write(ra, si.dtype, st);
-    if (he != hipSuccess) return dev_fail("rotary embedding", he);
-    void* attn = qkv;                                   // the raw projections are no longer needed
-    EncodeArgs e{};
-    e.q = q_rot; e.k = k_cache; e.v = v_cache; e.k_prefix = k_prefix; e.v_prefix = v_prefix;
-    e.cu = cu_dev; e.out = attn; e.lse = nullptr;
-    e.n_chunks = n_chunks; e.prefix_len = prefix_len; e.total_rows = (int)rows; e.max_chunk_len = max_len;
-    e.n_q_heads = si.hq; e.n_kv_heads = si.hkv; e.head_dim = si.d;
-    he = si.mfma ? launch_flash_encode(e, st) : launch_generic_encode(e, si.dtype, st);
-    if (he != hipSuccess) return dev_fail("encode attention", he);
-    if (gemm_xwT(attn, qd, w->w_o, x, x1, hidden, rows, hidden, qd, si.dtype, st)) return fail(APE_ERR_DEVICE, "output projection (rocBLAS) failed");
-
-    // MLP half, a slab of rows at a time: norm -> gate/up -> SiLU(gate) * up -> down projection + residual
-    he = launch_rmsnorm(x1, w->mlp_norm, h, rows, hidden, w->rms_eps, si.dtype, st);
-    if (he != hipSuccess) return dev_fail("RMSNorm", he);
-    for (long r0 = 0; r0 < rows; r0 += p.slab) {
-        const long nr = rows - r0 < p.slab ? rows - r0 : p.slab;
-        const char* hs = (const char*)h + (size_t)r0 * hidden * es;
-        const char* xs = (const char*)x1 + (size_t)r0 * hidden * es;
-        char* ys = (char*)y + (size_t)r0 * hidden * es;
-        if (gemm_xwT(hs, hidden, w->w_gate_up, nullptr, gu, 2 * inter, nr, 2 * inter, hidden, si.dtype, st)) return fail(APE_ERR_DEVICE, "gate/up projection (rocBLAS) failed");
-        he = launch_swiglu(gu, act, nr, inter, si.dtype, st);
-        if (he != hipSuccess) return dev_fail("SiLU * up", he);
-        if (gemm_xwT(act, inter, w->w_down, xs, ys, hidden, nr, hidden, inter, si.dtype, st)) return fail(APE_ERR_DEVICE, "down projection (rocBLAS) failed");
-    }
     return APE_OK;
 }
 

@@ -225,6 +225,19 @@ __device__ __forceinline__ KvView load_view(int rq) {
 }
 #endif
 
+// ---- host helpers of the entry points (defined in ape_api.hip; the layer library, a separate
+// shared object, links against them) --------------------------------------------------------
+struct ShapeInfo {
+    int hq, hkv, d, dtype, group;
+    bool force_generic;
+    bool mfma;                  // matrix-core kernels cover this shape
+};
+// records the text ape_last_error() returns on this thread, returns `code`
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int check_shape(const ape_shape* s, ShapeInfo* o);
+// size limits of an encode launch (see the header's general conventions)
+int check_encode_size(const ShapeInfo& si, int n_chunks, int max_len, long total_rows);
+
 // Split plan shared by ape_workspace_bytes and the launches.
 struct QueryPlan {
     int n_ctx_splits;
@@ -239,11 +252,6 @@ hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s);
 hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
 hipError_t launch_rope_write(const RopeArgs& a, int dtype, hipStream_t s);
-hipError_t launch_rmsnorm(const void* x, const void* w, void* y, long rows, int hidden, float eps, int dtype, hipStream_t s);
-hipError_t launch_swiglu(const void* gate_up, void* act, long rows, int inter, int dtype, hipStream_t s);
-// y[rows, n] = x[rows, k] W[n, k]^T (+ residual); 0 on success
-int gemm_xwT(const void* x, long ldx, const void* w, const void* residual, void* y, long ldy, long rows, int n, int k,
-             int dtype, hipStream_t s);
 hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s);
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
 hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t s);     // bf16, d = 128; block_rows from the plan

@@ -1,10 +1,11 @@
-// One transformer layer around the block-diagonal encode attention: the projections and the MLP
-// that turn the attention kernels into a per-layer prefill latency (arXiv 2502.05431, Section 5.4
-// measures whole-model prefill; the layer itself is the published Llama architecture).
+// Kernels and the rocBLAS wrapper of the layer library (libape_layer.so): the projections and the
+// MLP that turn the attention kernels into a per-layer prefill latency (arXiv 2502.05431, Section
+// 5.4 measures whole-model prefill; the layer itself is the published Llama architecture).
 // The four matrix products go to rocBLAS (plain GEMMs, fp32 accumulation, the residual added by
-// beta = 1); everything between them runs in this library's kernels: RMSNorm, the rotary
-// embedding + cache write, the attention, SiLU(gate) * up.
-#include "ape_internal.h"
+// beta = 1); RMSNorm and SiLU(gate) * up are the kernels below; the rotary embedding + cache write
+// and the attention are the attention library's (libape_hip.so, which this library links against
+// and which itself stays free of rocBLAS and of any state).
+#include "ape_layer_internal.h"
 
 #include <rocblas/rocblas.h>
 
@@ -119,8 +120,11 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gu, T
     }
 }
 
-// ---- rocBLAS: one handle per device for the life of the process
+// ---- rocBLAS: one handle per device for the life of the process.  The handle carries the stream
+// of the call that uses it, so a call holds g_blas_mutex from its first GEMM to its last (taken by
+// BlasCall, below): two host threads on one device are serialised instead of racing on the handle.
 std::mutex g_handle_mutex;
+std::recursive_mutex g_blas_mutex;
 rocblas_handle g_handles[64] = {};
 
 rocblas_handle blas_handle() {
@@ -132,6 +136,21 @@ rocblas_handle blas_handle() {
 }
 
 }  // namespace
+
+BlasCall::BlasCall() { g_blas_mutex.lock(); }
+BlasCall::~BlasCall() { g_blas_mutex.unlock(); }
+
+// Creating a handle allocates device memory: a caller that captures a HIP graph creates it first,
+// outside the capture, with a plain call on the same device.
+bool blas_ready_for(hipStream_t s) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) return false;
+    if (st == hipStreamCaptureStatusNone) return blas_handle() != nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(g_handle_mutex);
+    return g_handles[dev] != nullptr;                 // capturing: only an existing handle will do
+}
 
 hipError_t launch_rmsnorm(const void* x, const void* w, void* y, long rows, int hidden, float eps, int dtype, hipStream_t s) {
     if (rows == 0) return hipSuccess;

@@ -13,8 +13,8 @@ from paper_2502_05431_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "ape.h")).read()
+def header_functions(header="ape.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ape_[a-z_]+)\s*\(", text)))
 
@@ -26,6 +26,24 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert getattr(lib, n) is not None
     assert re.match(rb"\d+\.\d+\.\d+", lib.ape_version())
+
+
+def test_layer_library_exports_every_declared_symbol_and_the_attention_library_needs_no_gemm_library():
+    lib = B.load_layer()
+    names = header_functions("ape_layer.h")
+    assert set(names) == set(B.LAYER_EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    # the attention library depends on the HIP runtime alone; rocBLAS comes in with the layer library only
+    import subprocess
+    needed = lambda path: subprocess.run(["readelf", "-d", path], capture_output=True, text=True).stdout
+    assert "rocblas" not in needed(B.LIB_PATH)
+    assert "rocblas" in needed(B.LAYER_LIB_PATH) and "libape_hip.so" in needed(B.LAYER_LIB_PATH)
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    one = B.layer_workspace_bytes(sh, 4096, 14336, 1000)
+    assert one > 0 and one % 256 == 0
+    assert B.layer_workspace_bytes(sh, 4096, 14336, 1000, n_layers=4) == one + (1000 * 4096 * 2 + 255) // 256 * 256
+    assert B.layer_workspace_bytes(sh, 4095, 14336, 1000) == 0
 
 
 def test_status_strings():
@@ -49,6 +67,16 @@ def test_workspace_bytes():
     bad = B.make_shape(32, 7, 128, B.APE_BF16)
     assert B.workspace_bytes(B.APE_OP_DECODE, bad, 1, 1) == 0
     assert B.workspace_bytes(99, sh, 1, 1) == 0
+    # with the longest context stated, the bound is what calls up to that length need and no more:
+    # never above the any-length bound, growing with the length, one split (prefix + self) for none
+    unit = 516                                             # (head_dim + 1) fp32 per (row, head) and split
+    assert B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 0) < 2 * 32 * unit + 512
+    d128k = B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 131072)
+    d16k = B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 16384)
+    assert 0 < d16k < d128k <= B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, -1)
+    p128k = B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256, 131072)
+    assert 0 < p128k <= p and B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256, 1 << 40) == p
+    assert p128k < 12 * 8192 * unit                        # config 3: 8 context splits + 1, not the 65-split worst case
 
 
 FAKE = 0x1000  # never dereferenced: every call below fails validation before any launch
@@ -143,12 +171,20 @@ def test_size_limits_are_refused_before_any_launch():
     indices, return APE_ERR_UNSUPPORTED with a message that names the limit."""
     lib = B.load()
     sh = B.make_shape(32, 8, 128, B.APE_BF16)
-    # query prefill: 2^24 (row, head) outputs pass the check (and stop at the missing workspace), one row more does not
-    rows_ok = (1 << 24) // 32
+    # query prefill: fewer than 2^24 (row, head) outputs pass the check (and stop at the missing workspace);
+    # exactly 2^24 would be 2^32 work items in the merge launch and is refused
+    rows_ok = (1 << 24) // 32 - 1
     assert _prefill(sh, _req(self_len=rows_ok), q_len=rows_ok) == B.APE_ERR_WORKSPACE
     assert _prefill(sh, _req(self_len=rows_ok + 1), q_len=rows_ok + 1) == B.APE_ERR_UNSUPPORTED
     assert b"outputs in one call" in lib.ape_last_error()
+    assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, rows_ok) > 0 and B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, rows_ok + 1) == 0
     assert _tree([(0.9, 0, 4, 1)], req=_req(n_chunks=4, total_ctx_len=200, self_len=rows_ok + 1), q_len=rows_ok + 1) == B.APE_ERR_UNSUPPORTED
+    # a tree call sizes its attention grid from the bound on the splits: many nodes x many query rows
+    # pass 2^24 workgroups and are refused on the host (not by the launch)
+    n_ctx = 2000
+    big_tree = [(1.0, 1, n_ctx, 0)] + [(0.9, i, 1, 1) for i in range(n_ctx)]
+    assert _tree(big_tree, req=_req(n_chunks=n_ctx, total_ctx_len=n_ctx * 64, self_len=131072), q_len=131072) == B.APE_ERR_UNSUPPORTED
+    assert b"workgroups" in lib.ape_last_error()
     # encode on the matrix-core path: contexts x KV heads x query tiles of the longest context
     n = 4096
     lens = [1 << 17] + [1] * (n - 1)                      # one long context makes every context's share of the grid long
@@ -238,7 +274,7 @@ def test_batched_prefill_argument_errors():
 
 
 def test_layer_argument_errors():
-    lib = B.load()
+    lib = B.load_layer()
     sh = B.make_shape(32, 8, 128, B.APE_BF16)
     cu = (ctypes.c_int32 * 3)(0, 5, 9)
     cuh = ctypes.cast(cu, ctypes.c_void_p)
@@ -249,9 +285,9 @@ def test_layer_argument_errors():
             setattr(w, k, v)
         return w
 
-    def layer(w=None, x=FAKE, kp=FAKE, vp=FAKE, lp=4, cu_host=cuh, cu_dev=FAKE, n=2, kc=FAKE, vc=FAKE, y=FAKE, ws=None, wsb=0):
+    def layer(w=None, x=FAKE, kp=FAKE, vp=FAKE, lp=4, cu_host=cuh, cu_dev=FAKE, n=2, kc=FAKE, vc=FAKE, y=FAKE + 256, ws=None, wsb=0):
         w = w or weights()
-        return lib.ape_layer_encode(ctypes.byref(sh), ctypes.byref(w), x, kp, vp, lp, cu_host, cu_dev, n, kc, vc, y, ws, wsb, None)
+        return lib.ape_layer_encode(ctypes.byref(sh), ctypes.byref(w), x, kp, vp, lp, cu_host, cu_dev, n, kc, vc, y, None, ws, wsb, None)
     assert layer(w=weights(hidden=4095)) == B.APE_ERR_UNSUPPORTED
     assert layer(w=weights(intermediate=0)) == B.APE_ERR_UNSUPPORTED
     assert layer(w=weights(rms_eps=-1.0)) == B.APE_ERR_INVALID_ARG
@@ -265,6 +301,20 @@ def test_layer_argument_errors():
     assert layer() == B.APE_ERR_WORKSPACE
     assert layer(ws=FAKE + 8, wsb=1 << 40) == B.APE_ERR_WORKSPACE
     assert layer(n=0) == B.APE_OK                                  # nothing to do
+    assert layer(y=FAKE, x=FAKE + 0) == B.APE_ERR_INVALID_ARG      # y aliases x
+    assert b"alias" in B.load().ape_last_error()                   # (one error text for both libraries)
+
+    # a stack of layers: per-layer tables on the host
+    def stack(n_layers=2, ws=None, wsb=0, widths=(4096, 4096), kc_null=False, lp=4):
+        warr = (B.ApeLayerWeights * n_layers)(*[weights(hidden=widths[i % len(widths)]) for i in range(n_layers)])
+        tab = (ctypes.c_void_p * max(n_layers, 1))(*[FAKE] * n_layers)
+        kc = (ctypes.c_void_p * max(n_layers, 1))(*([FAKE] * (n_layers - 1) + [None if kc_null else FAKE])[:n_layers])
+        return lib.ape_layers_encode(ctypes.byref(sh), warr, n_layers, FAKE, tab, tab, lp, cuh, FAKE, 2, kc, tab, FAKE + 256, ws, wsb, None)
+    assert stack(n_layers=0) == B.APE_ERR_INVALID_ARG
+    assert stack(widths=(4096, 2048)) == B.APE_ERR_INVALID_ARG     # layers of different widths
+    assert stack(kc_null=True) == B.APE_ERR_INVALID_ARG
+    assert stack() == B.APE_ERR_WORKSPACE
+    assert stack(ws=FAKE * 256, wsb=B.layer_workspace_bytes(sh, 4096, 14336, 9, n_layers=2) - 1) == B.APE_ERR_WORKSPACE
     need = B.layer_workspace_bytes(sh, 4096, 14336, 131072)
     assert need % 256 == 0 and 4 * 2 ** 30 < need < 8 * 2 ** 30    # the MLP runs in slabs: a few GiB, not 16
     assert B.layer_workspace_bytes(sh, 4095, 14336, 10) == 0
@@ -310,8 +360,8 @@ def test_binding_structs_have_the_layout_of_the_header(tmp_path):
     if shutil.which("gcc") is None:
         pytest.skip("needs gcc")
     structs = {"ape_shape": B.ApeShape, "ape_request": B.ApeRequest, "ape_tree_node": B.ApeTreeNode,
-               "ape_layer_weights": B.ApeLayerWeights}
-    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "ape.h"', 'int main(void) {']
+               "ape_layer_weights": B.ApeLayerWeights, "ape_layer_taps": B.ApeLayerTaps}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "ape.h"', '#include "ape_layer.h"', 'int main(void) {']
     for cname, cls in structs.items():
         lines.append('printf("%s size %%zu\\n", sizeof(%s));' % (cname, cname))
         for fname, _ in cls._fields_:
@@ -350,9 +400,9 @@ def test_a_plain_c_program_links_and_calls_the_library(tmp_path):
 #include "ape.h"
 int main(void) {
     ape_shape sh = {32, 8, 128, APE_BF16};
-    size_t ws = ape_workspace_bytes(APE_OP_DECODE, &sh, 32, 1);
+    size_t ws = ape_workspace_bytes(APE_OP_DECODE, &sh, 32, 1, 16384);
     if (ws == 0 || ws % 256) return 1;
-    if (ape_workspace_bytes(APE_OP_ENCODE, &sh, 1, 1) != 0) return 2;
+    if (ape_workspace_bytes(APE_OP_ENCODE, &sh, 1, 1, -1) != 0) return 2;
     if (strlen(ape_status_string(APE_ERR_WORKSPACE)) == 0) return 3;
     ape_request r;
     memset(&r, 0, sizeof r);

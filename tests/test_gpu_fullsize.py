@@ -1,8 +1,9 @@
 """GPU parity at the full benchmark sizes (configs 3, 4, 5), in the launch configuration bench.py
-times.  The oracle computes sampled outputs one by one -- each sampled (row, head) pair exactly,
-over its full KV; 4096 pairs per output tensor (every output where there are no more than that)
--- always including first/last rows and heads and rows at tile and chunk boundaries;
-size-independent properties cover the rest."""
+times.  The oracle computes outputs one by one -- each (row, head) pair exactly, over its full KV:
+every output of the query prefills (8192 at config 3, 4096 at config 4) and of the batched decode;
+4096 distinct sampled rows of each encode (drawn without replacement) -- always including
+first/last rows and heads and rows at tile and chunk boundaries; size-independent properties cover
+the rest."""
 import numpy as np
 import pytest
 import torch
@@ -17,10 +18,22 @@ DEV = "cuda:0"
 
 
 def _pairs(rng, n_rows, n_heads, n, must_rows=()):
+    """n DISTINCT (row, head) pairs (all of them when there are no more than n): the required rows
+    with the first and last head, the rest drawn without replacement."""
+    total = n_rows * n_heads
+    if n >= total:
+        return [(r, h) for r in range(n_rows) for h in range(n_heads)]
     rows = {0, n_rows - 1, *[r for r in must_rows if 0 <= r < n_rows]}
-    pairs = [(r, h) for r in sorted(rows) for h in (0, n_heads - 1)]
-    while len(pairs) < n:
-        pairs.append((int(rng.integers(n_rows)), int(rng.integers(n_heads))))
+    pairs = [(r, h) for r in sorted(rows) for h in sorted({0, n_heads - 1})]
+    seen = set(pairs)
+    for idx in rng.permutation(total):
+        if len(pairs) >= n:
+            break
+        pr = (int(idx) // n_heads, int(idx) % n_heads)
+        if pr not in seen:
+            seen.add(pr)
+            pairs.append(pr)
+    assert len(set(pairs)) == len(pairs) == n
     return pairs
 
 
@@ -36,9 +49,10 @@ def test_cfg3_128k_encode_and_prefill_sampled():
     h = H.HostArrays(r)
     rng = np.random.default_rng(3)
 
-    # query prefill: 256 rows over the 131K cached KV
+    # query prefill: 256 rows over the 131K cached KV -- every one of the 8192 (row, head) outputs
     out, lse = H.run_prefill(spec, r, spec.q_len, spec.q_len)
-    pairs = _pairs(rng, spec.q_len, spec.n_q_heads, 4096, must_rows=(63, 64, 127, 128, 191, 192))
+    pairs = _pairs(rng, spec.q_len, spec.n_q_heads, spec.q_len * spec.n_q_heads)
+    assert len(pairs) == 8192
     ref, ref_lse, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, pairs=pairs)
     H.check_close(_gather(out, pairs), ref, "bf16", "cfg3 prefill")
     assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
@@ -78,7 +92,7 @@ def test_cfg4_manyshot_prefill_and_decode_sampled():
     ref, ref_lse, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, pairs=pairs)
     H.check_close(_gather(out, pairs), ref, "bf16", "cfg4 prefill")
     assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
-    for step in (0, 63):
+    for step in sorted({*range(0, 64, 4), 63}):           # 16 of the 64 decode steps spread over the run, and the last
         sl = spec.q_len + step + 1
         outd, lsed = H.run_decode(spec, [r], [sl])
         refd, refd_lse, _ = H.oracle_prefill(h, 1, sl, r.temperature, r.scale)

@@ -106,10 +106,12 @@ def test_workspace_sizes_are_what_the_calls_demand(seed):
     rc = B.load().ape_attention_tree(ctypes.byref(sh), ctypes.byref(r), ctypes.cast(arr, ctypes.c_void_p), FAKE, len(nodes),
                                      FAKE, q_len, FAKE, None, FAKE * 256, need - 1, None)
     assert rc == B.APE_ERR_WORKSPACE
-    # flat entry points: the bound never shrinks with batch or rows
+    # flat entry points: the bound grows with the batch at a fixed split count (more requests mean
+    # fewer splits each, so across split counts it need not)
     batch = rng.randint(1, 40)
     d1 = B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1)
-    assert B.workspace_bytes(B.APE_OP_DECODE, sh, batch + 1, 1) > d1
+    assert d1 >= batch * 32 * 2 * 516
+    assert B.workspace_bytes(B.APE_OP_DECODE, sh, batch + 1, 1, 600) > B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1, 600)
     assert B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, q_len) > 0           # (not monotone in q_len: more row tiles, fewer splits)
     rq = B.ApeRequest()
     for k in ("k_prefix", "v_prefix", "k_chunks", "v_chunks", "cu_chunk_lens", "k_self", "v_self"):
@@ -152,11 +154,18 @@ def test_workspace_bound_covers_every_context_length(seed):
         bound_p = B.workspace_bytes(B.APE_OP_PREFILL, sh, batch, q_len)
         need_p = _needed(lambda: lib.ape_attention_prefill_batch(ctypes.byref(sh), arr, batch, FAKE, q_len, FAKE, None, FAKE * 256, 1, None))
         assert need_p <= bound_p, (batch, q_len, ctx, need_p, bound_p)
+        # the bound for a stated longest context covers this call whenever its contexts are no longer
+        for cap in (ctx, ctx + rng.randint(0, 5000), 2 * ctx + 1):
+            capped = B.workspace_bytes(B.APE_OP_PREFILL, sh, batch, q_len, cap)
+            assert need_p <= capped <= bound_p, (batch, q_len, ctx, cap, need_p, capped, bound_p)
         for b in range(batch):
             arr[b].self_len = max(1, arr[b].self_len)
         bound_d = B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1)
         need_d = _needed(lambda: lib.ape_attention_decode(ctypes.byref(sh), arr, batch, FAKE, FAKE, None, FAKE * 256, 1, None))
         assert need_d <= bound_d, (batch, ctx, need_d, bound_d)
+        for cap in (ctx, ctx + rng.randint(0, 5000), 2 * ctx + 1):
+            capped = B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1, cap)
+            assert need_d <= capped <= bound_d, (batch, ctx, cap, need_d, capped, bound_d)
 
 
 @pytest.mark.parametrize("hq, q_len, batch", [(32, 1, 1), (32, 32, 1), (32, 33, 1), (32, 256, 1), (8, 100, 3), (64, 5, 2)])
@@ -177,5 +186,9 @@ def test_prefill_workspace_bound_over_a_sweep_of_context_lengths(hq, q_len, batc
             arr[b].total_ctx_len = ctx
         need = _needed(lambda: lib.ape_attention_prefill_batch(ctypes.byref(sh), arr, batch, FAKE, q_len, FAKE, None, FAKE * 256, 1, None))
         assert need <= bound, (ctx, need, bound)
+        if ctx % 7 == 0:                                   # ... nor the bound stated for a cap at or above this length
+            for cap in (ctx, ctx + 4097):
+                capped = B.workspace_bytes(B.APE_OP_PREFILL, sh, batch, q_len, cap)
+                assert need <= capped <= bound, (ctx, cap, need, capped, bound)
         worst = max(worst, need)
     assert worst > bound // 2                              # and the bound is not idle: some length comes within a factor of two

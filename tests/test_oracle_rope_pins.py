@@ -7,22 +7,26 @@ import pytest
 import torch
 
 from oracle import ape_oracle
-from paper_2502_05431_amd import workloads as W
 
 
 def _x(n, heads, d, seed=0):
     return np.random.default_rng(seed).standard_normal((n, heads, d)).astype(np.float32)
 
 
-def test_against_the_input_generator_rotation():
-    """workloads.rope_rotate (torch; angles in fp64, cos/sin rounded to fp32) is a separate
-    implementation of the same published rotation."""
+def test_against_complex_multiplication():
+    """The rotation of the plane (x_c, x_{c+d/2}) by the angle pos * base^(-2c/d) IS the complex
+    product (x_c + i x_{c+d/2}) * exp(i angle): numpy's complex arithmetic computes it with no
+    rotation formula written out here (and nothing of the product package is involved)."""
     lens, off, base = [5, 9, 1, 12], 8, 500000.0
-    x = _x(sum(lens), 3, 64, 1)
-    pos = torch.cat([off + torch.arange(l) for l in lens])
-    ref = W.rope_rotate(torch.from_numpy(x), pos, base).numpy()
+    d = 64
+    x = _x(sum(lens), 3, d, 1)
+    pos = np.concatenate([off + np.arange(l) for l in lens]).astype(np.float64)
+    freq = np.float64(base) ** (-np.arange(d // 2, dtype=np.float64) * 2.0 / d)
+    z = (x[..., :d // 2].astype(np.float64) + 1j * x[..., d // 2:].astype(np.float64)) * np.exp(1j * pos[:, None, None] * freq[None, None, :])
+    ref = np.concatenate([z.real, z.imag], axis=-1)
     got = ape_oracle.rope(x, lens, off, base)
-    np.testing.assert_allclose(got, ref, atol=2e-6)
+    np.testing.assert_allclose(got, ref, atol=1e-13)
+    assert torch.tensor(got).shape == (sum(lens), 3, d)
 
 
 def test_position_zero_is_identity_and_planes_keep_their_norm():
