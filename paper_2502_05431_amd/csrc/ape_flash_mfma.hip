@@ -275,6 +275,24 @@ __device__ __forceinline__ void softmax_slice(const f32x16 (&s)[RB], int rb, int
     p[rb][r >> 3][(r & 7) >> 1] = pk;
 }
 
+// The same slice cut in two, for bodies that spread the softmax over every MFMA slot: first the two
+// exponentials (their arguments are ready since the previous body), then, one MFMA later, the row
+// sums and the packed conversion.
+template <int RB>
+__device__ __forceinline__ void softmax_half_a(const f32x16 (&s)[RB], int rb, int k, float sc2, float m, float (&e)[2]) {
+    e[0] = __builtin_amdgcn_exp2f(fmaf(s[rb][2 * k], sc2, -m));
+    e[1] = __builtin_amdgcn_exp2f(fmaf(s[rb][2 * k + 1], sc2, -m));
+}
+template <int RB>
+__device__ __forceinline__ void softmax_half_b(const float (&e)[2], int rb, int k, float (&psum)[RB][2], u32x4 (&p)[RB][2]) {
+    const int r = 2 * k;
+    psum[rb][0] += e[0];
+    psum[rb][1] += e[1];
+    uint32_t pk;
+    asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(e[0]), "v"(e[1]), "v"(psum[rb][0]), "v"(psum[rb][1]));
+    p[rb][r >> 3][(r & 7) >> 1] = pk;
+}
+
 // O *= alpha (per query row).  The file is built with VGPR-form MFMAs (accumulators in the
 // vector registers), so this is a plain multiply; it is kept clear of the matrix-core writes.
 template <int RB>
@@ -502,6 +520,82 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
     for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
 }
 
+// The fast body once more, with the softmax spread evenly: the probabilities of block j are written
+// to p_out while the PV product still reads those of block j-1 from p_in (two register sets that
+// swap roles from one body to the next, like the scores), so a slice of the softmax no longer has to
+// wait for the MFMAs that read the registers it overwrites, and every one of the 16*RB MFMAs of the
+// body carries half a slice (two exponentials, or two adds and a conversion) in its shadow instead
+// of half of them carrying a whole one.
+template <int RB, int RING>
+__device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
+                                                   const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
+                                                   const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB],
+                                                   const u32x4 (&p_in)[RB][2], u32x4 (&p_out)[RB][2],
+                                                   bf16x8 (&vf)[8], RingPlan<RING>& plan) {
+    constexpr int NS = 8 * RB;
+    const char* slot_pv = lds + pv_off;
+    const char* slot_cur = lds + plan.o_cur;
+    const char* slot_nxt = lds + plan.o_nxt;
+    bf16x8 kf[8];
+    float psum[RB][2];
+    float e[2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) psum[rb][0] = psum[rb][1] = 0.f;
+    // slot t (0 .. 2*NS-1) carries half-slice t: slice t/2 = (row block (t/2)/8, register pair (t/2)%8)
+    auto half_slice = [&](int t) {
+        const int sl = t >> 1, rb = sl / 8, k = sl % 8;
+        if ((t & 1) == 0) softmax_half_a<RB>(s_in, rb, k, sc2, st.m[rb], e);
+        else softmax_half_b<RB>(e, rb, k, psum, p_out);
+    };
+    // ---- O += P V of block j-1
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int rb = n / 8, f = n % 8;
+        st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p_in[rb][f >> 2]),
+                                                                  st.o[rb][f & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n < 2) {
+            vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
+            vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+        }
+        if (RB == 2) {
+            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+        } else if (n == 4 || n == 5) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag(slot_nxt, lo, 4 * (n - 4) + q);
+        }
+        if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+        else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
+        half_slice(n);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- K Q^T of block j+1
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_out[rb][r] = 0.f;
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+        const int ks = n / RB, rb = n % RB;
+        s_out[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_out[rb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        half_slice(NS + n);
+        if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);             // for the next body's PV
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    bool bad = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        psum[rb][0] += psum[rb][1];
+        bad |= !(psum[rb][0] <= kPsumMax);
+    }
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(bad) != 0, 0)) set_reference<RB>(s_in, sc2, st, psum, p_out);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) st.l[rb] += psum[rb][0];
+}
+
 // The loads of the first blocks of a stream (blocks 0 .. RING-3), started before anything else in
 // the kernel -- the query fragments are fetched while they fly.
 template <int RING>
@@ -560,7 +654,7 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
     plan.piece(2);
     plan.piece(3);
     // body 0 has no block -1: its PV product runs on zero probabilities and block 0's (finite) values
-    u32x4 p[RB][2];
+    u32x4 p[RB][2], p2[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) p[rb][0] = p[rb][1] = u32x4{0, 0, 0, 0};
     bf16x8 vf[8];
@@ -574,12 +668,12 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             int next_pv_off = plan.o_cur;
-            pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, vf, plan);
+            pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, p2, vf, plan);
             pv_off = next_pv_off;
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             next_pv_off = plan.o_cur;
-            pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, plan);
+            pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p2, p, vf, plan);
             pv_off = next_pv_off;
         }
         if (n_fast & 1) {
@@ -790,15 +884,18 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
     init_state<RB>(st);
     run_blocks<RB>(rs, lds, qf, st, 0.08838834764831845f * LOG2E, lim);
 
+    // ---- output: the wavefront's rows go through LDS (the ring is idle now) so that they leave as
+    // whole 256-byte rows, 16 bytes per lane: the G heads of a token are neighbours in memory, and a
+    // store instruction then writes up to 1 KB of consecutive bytes instead of 64 scattered pieces.
+    ring_barrier();                                        // every wavefront is done with the last block's slot
+    char* stage = lds + (long)wave * (RB * 32 * ROWB);     // RB * 8 KB of this wavefront's own
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
         const int tok = R / G, g = R % G;
         const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
-        if (tok >= len) continue;
-        const float inv = 1.f / lt;                        // a row always sees itself
-        const int h = hk * G + g;
-        char* o = (char*)a.out + ((long)(c0 + tok) * hq + h) * ROWB;
+        const float inv = tok < len ? 1.f / lt : 0.f;      // a valid row always sees itself
+        char* row = stage + (rb * 32 + l32) * ROWB;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -806,9 +903,22 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
                 bf16x4 w;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = (__bf16)(st.o[rb][db][4 * q4 + e] * inv);
-                *(bf16x4*)(o + (32 * db + 8 * q4 + 4 * hi) * 2) = w;
+                // 16-byte chunk 4*db + q4 of the row, XOR-swizzled by the row; this lane's half of it
+                *(bf16x4*)(row + (((4 * db + q4) ^ (l32 & 15)) << 4) + 8 * hi) = w;
             }
-        if (a.lse && hi == 0) a.lse[(long)h * a.total_rows + c0 + tok] = (st.m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+        if (a.lse && hi == 0 && tok < len) a.lse[(long)(hk * G + g) * a.total_rows + c0 + tok] = (st.m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+    }
+    // (the staging area is the wavefront's own: no barrier, the LDS operations of one wavefront complete in order)
+    {
+        const int c16 = lane & 15, r4 = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < RB * 8; ++i) {
+            const int lr = 4 * i + r4;                     // row of the wavefront's RB * 32
+            const int R = qtile * BM + wave * 32 * RB + lr;
+            const int tok = R / G, g = R % G;
+            const u32x4 w = *(const u32x4*)(stage + lr * ROWB + ((c16 ^ (lr & 15)) << 4));
+            if (tok < len) *(u32x4*)((char*)a.out + ((long)(c0 + tok) * hq + hk * G + g) * ROWB + c16 * 16) = w;
+        }
     }
 }
 
