@@ -21,6 +21,7 @@
 #define APE_STREAM_FN __device__ __forceinline__
 #define ape_stream_load_i32 ::ape::scalar_load_i32
 #define ape_stream_load_ptr ::ape::scalar_load_ptr
+#define ape_stream_find_chunk ::ape::find_chunk
 #include "ape_decode_stream.h"
 
 #include <math.h>

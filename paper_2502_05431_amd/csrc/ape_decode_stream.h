@@ -6,8 +6,9 @@
 // 1..32 rows that stay inside one chunk and inside that chunk's rows.
 //
 // The includer defines APE_STREAM_FN (function qualifiers), the two table readers
-// ape_stream_load_i32 / ape_stream_load_ptr (scalar loads on the GPU, plain reads on the host) and
-// the view type: any struct with the fields cu, k_chunks, v_chunks, n_chunks.
+// ape_stream_load_i32 / ape_stream_load_ptr (scalar loads on the GPU, plain reads on the host),
+// ape_stream_find_chunk(cu, n_chunks, t) = the largest c with cu[c] <= t, and the view type: any
+// struct with the fields cu, k_chunks, v_chunks, n_chunks.
 #pragma once
 #include <stdint.h>
 
@@ -59,12 +60,8 @@ struct DecodeStream {
         seg = 2; j = 0; n0 = n1 = 0; k0 = v0 = k1 = v1 = nullptr;
         c_loaded = -1; kc = vc = nullptr;
         if (t < te) {
-            int lo = 0, hi = n_chunks - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (ape_stream_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
-            }
-            c = lo; c0 = ape_stream_load_i32(cu + c); c1 = ape_stream_load_i32(cu + c + 1);
+            c = ape_stream_find_chunk(cu, n_chunks, t);                // the largest c with cu[c] <= t
+            c0 = ape_stream_load_i32(cu + c); c1 = ape_stream_load_i32(cu + c + 1);
         } else {
             te = t;
         }

@@ -30,6 +30,7 @@
 #define ape_ring_load_i32 ::ape::scalar_load_i32
 #define ape_ring_load_ptr ::ape::scalar_load_ptr
 #define ape_ring_load_chunk ::ape::scalar_load_chunk
+#define ape_ring_find_chunk ::ape::find_chunk
 #include "ape_ring.h"
 
 #include <math.h>
@@ -668,12 +669,18 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             int next_pv_off = plan.o_cur;
-            pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, p2, vf, plan);
+            // Narrow tile: the evenly spread body (+1.7 % measured).  Wide tile: its second set of
+            // probability registers does not fit next to the 128 accumulators (the compiler parks 16
+            // more values in the accumulation registers and copies them in and out, 18 instructions per
+            // body), which eats the gain: it keeps the paired body.
+            if constexpr (RB == 1) pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, p2, vf, plan);
+            else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, vf, plan);
             pv_off = next_pv_off;
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             next_pv_off = plan.o_cur;
-            pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p2, p, vf, plan);
+            if constexpr (RB == 1) pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p2, p, vf, plan);
+            else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, plan);
             pv_off = next_pv_off;
         }
         if (n_fast & 1) {
@@ -884,40 +891,66 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
     init_state<RB>(st);
     run_blocks<RB>(rs, lds, qf, st, 0.08838834764831845f * LOG2E, lim);
 
-    // ---- output: the wavefront's rows go through LDS (the ring is idle now) so that they leave as
-    // whole 256-byte rows, 16 bytes per lane: the G heads of a token are neighbours in memory, and a
-    // store instruction then writes up to 1 KB of consecutive bytes instead of 64 scattered pieces.
-    ring_barrier();                                        // every wavefront is done with the last block's slot
-    char* stage = lds + (long)wave * (RB * 32 * ROWB);     // RB * 8 KB of this wavefront's own
+    if constexpr (RB == 2) {
+        // Wide tile (chunks beyond 4096 tokens: long streams, the output is a small part of a tile's
+        // time): every lane stores its 4-dim pieces directly.  (Staging through LDS as below makes the
+        // compiler park a hundred more values in the accumulation registers of this kernel.)
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
-        const int tok = R / G, g = R % G;
-        const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
-        const float inv = tok < len ? 1.f / lt : 0.f;      // a valid row always sees itself
-        char* row = stage + (rb * 32 + l32) * ROWB;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(st.o[rb][db][4 * q4 + e] * inv);
-                // 16-byte chunk 4*db + q4 of the row, XOR-swizzled by the row; this lane's half of it
-                *(bf16x4*)(row + (((4 * db + q4) ^ (l32 & 15)) << 4) + 8 * hi) = w;
-            }
-        if (a.lse && hi == 0 && tok < len) a.lse[(long)(hk * G + g) * a.total_rows + c0 + tok] = (st.m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
-    }
-    // (the staging area is the wavefront's own: no barrier, the LDS operations of one wavefront complete in order)
-    {
-        const int c16 = lane & 15, r4 = lane >> 4;
-#pragma unroll
-        for (int i = 0; i < RB * 8; ++i) {
-            const int lr = 4 * i + r4;                     // row of the wavefront's RB * 32
-            const int R = qtile * BM + wave * 32 * RB + lr;
+        for (int rb = 0; rb < RB; ++rb) {
+            const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
             const int tok = R / G, g = R % G;
-            const u32x4 w = *(const u32x4*)(stage + lr * ROWB + ((c16 ^ (lr & 15)) << 4));
-            if (tok < len) *(u32x4*)((char*)a.out + ((long)(c0 + tok) * hq + hk * G + g) * ROWB + c16 * 16) = w;
+            const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
+            if (tok >= len) continue;
+            const float inv = 1.f / lt;                        // a row always sees itself
+            const int h = hk * G + g;
+            char* o = (char*)a.out + ((long)(c0 + tok) * hq + h) * ROWB;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(st.o[rb][db][4 * q4 + e] * inv);
+                    *(bf16x4*)(o + (32 * db + 8 * q4 + 4 * hi) * 2) = w;
+                }
+            if (a.lse && hi == 0) a.lse[(long)h * a.total_rows + c0 + tok] = (st.m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+        }
+    } else {
+        // ---- output: the wavefront's rows go through LDS (the ring is idle now) so that they leave as
+        // whole 256-byte rows, 16 bytes per lane: the G heads of a token are neighbours in memory, and a
+        // store instruction then writes up to 1 KB of consecutive bytes instead of 64 scattered pieces.
+        ring_barrier();                                        // every wavefront is done with the last block's slot
+        char* stage = lds + (long)wave * (RB * 32 * ROWB);     // RB * 8 KB of this wavefront's own
+    #pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int R = qtile * BM + wave * 32 * RB + rb * 32 + l32;
+            const int tok = R / G, g = R % G;
+            const float lt = st.l[rb] + __shfl_xor(st.l[rb], 32);
+            const float inv = tok < len ? 1.f / lt : 0.f;      // a valid row always sees itself
+            char* row = stage + (rb * 32 + l32) * ROWB;
+    #pragma unroll
+            for (int db = 0; db < 4; ++db)
+    #pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    bf16x4 w;
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(st.o[rb][db][4 * q4 + e] * inv);
+                    // 16-byte chunk 4*db + q4 of the row, XOR-swizzled by the row; this lane's half of it
+                    *(bf16x4*)(row + (((4 * db + q4) ^ (l32 & 15)) << 4) + 8 * hi) = w;
+                }
+            if (a.lse && hi == 0 && tok < len) a.lse[(long)(hk * G + g) * a.total_rows + c0 + tok] = (st.m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+        }
+        // (the staging area is the wavefront's own: no barrier, the LDS operations of one wavefront complete in order)
+        {
+            const int c16 = lane & 15, r4 = lane >> 4;
+    #pragma unroll
+            for (int i = 0; i < RB * 8; ++i) {
+                const int lr = 4 * i + r4;                     // row of the wavefront's RB * 32
+                const int R = qtile * BM + wave * 32 * RB + lr;
+                const int tok = R / G, g = R % G;
+                const u32x4 w = *(const u32x4*)(stage + lr * ROWB + ((c16 ^ (lr & 15)) << 4));
+                if (tok < len) *(u32x4*)((char*)a.out + ((long)(c0 + tok) * hq + hk * G + g) * ROWB + c16 * 16) = w;
+            }
         }
     }
 }

@@ -188,6 +188,26 @@ __device__ __forceinline__ const void* scalar_load_ptr(const void* const* p) {
     return (const void*)v;
 }
 
+// The chunk that holds pooled context index t: the largest c in [0, n_chunks - 1] with cu[c] <= t
+// (cu non-decreasing, cu[0] = 0 <= t; n_chunks >= 1; t wavefront-uniform).  A binary search is a chain of
+// log2(n) dependent loads, ~0.5 us each, in front of a workgroup's first K/V load; here the 64 lanes
+// probe 64 evenly spaced entries at once and a ballot narrows the range 64-fold per round trip: one
+// round for up to 64 chunks, two for up to 4096.
+__device__ __forceinline__ int find_chunk(const int32_t* cu, int n_chunks, int t) {
+    const int lane = threadIdx.x & 63;
+    int lo = 0, hi = n_chunks - 1;                                     // cu[lo] <= t holds throughout; the answer is <= hi
+    while (lo < hi) {
+        const int step = (hi - lo + 63) >> 6;                          // >= 1; lane 63 probes hi
+        const int idx = min(lo + (lane + 1) * step, hi);               // non-decreasing over the lanes
+        const int cnt = __builtin_popcountll(__builtin_amdgcn_ballot_w64(cu[idx] <= t));   // true for a prefix of the lanes
+        if (cnt == 64) { lo = hi; break; }
+        const int first_false = min(lo + (cnt + 1) * step, hi);        // lane cnt's probe: the answer lies before it
+        if (cnt > 0) lo = min(lo + cnt * step, hi);                    // lane cnt-1's probe (a smaller index than lane cnt's)
+        hi = first_false - 1;
+    }
+    return __builtin_amdgcn_readfirstlane(lo);
+}
+
 // Context tokens [t0, t1) (indices into the pooled contexts) that split `split` of request view
 // `kv` covers; t0 >= t1 for an empty split.  `split` must be wavefront-uniform.
 __device__ __forceinline__ void ctx_split_range(const QueryArgs& a, const KvView& kv, int split, long& t0, long& t1) {

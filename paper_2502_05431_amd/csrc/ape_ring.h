@@ -6,8 +6,10 @@
 // bounds, into a free slot; every body finds its three blocks where it looks for them; a fast
 // body never meets a block that needs a mask.
 //
-// The includer defines APE_RING_FN (function qualifiers) and the two table readers
-// ape_ring_load_i32 / ape_ring_load_ptr / ape_ring_load_chunk (scalar loads on the GPU, plain reads on the host).
+// The includer defines APE_RING_FN (function qualifiers), the table readers ape_ring_load_i32 /
+// ape_ring_load_ptr / ape_ring_load_chunk (scalar loads on the GPU, plain reads on the host) and
+// ape_ring_find_chunk(cu, n_chunks, t) = the largest c with cu[c] <= t (a search across the lanes
+// on the GPU, a plain one on the host).
 #pragma once
 #include <stdint.h>
 
@@ -70,12 +72,8 @@ struct Stream {
         k = v = kc = vc = nullptr; nc = 0; rem = 0; run = 0; j0 = -1; jstep = 0;
         t = t0_; t1 = t1_; c = 0; c0 = c1 = 0;
         if (t < t1 && cu != nullptr && n_chunks > 0) {
-            int lo = 0, hi = n_chunks - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (ape_ring_load_i32(cu + mid) <= t) lo = mid; else hi = mid - 1;
-            }
-            c = lo; c0 = ape_ring_load_i32(cu + c); c1 = ape_ring_load_i32(cu + c + 1);
+            c = ape_ring_find_chunk(cu, n_chunks, t);              // the largest c with cu[c] <= t
+            c0 = ape_ring_load_i32(cu + c); c1 = ape_ring_load_i32(cu + c + 1);
             open_ctx();
         }
     }

@@ -15,6 +15,11 @@
 #define APE_STREAM_FN inline
 static inline int32_t ape_stream_load_i32(const int32_t* p) { return *p; }
 static inline const void* ape_stream_load_ptr(const void* const* p) { return *p; }
+static inline int ape_stream_find_chunk(const int32_t* cu, int n_chunks, int t) {
+    int lo = 0, hi = n_chunks - 1;
+    while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (cu[mid] <= t) lo = mid; else hi = mid - 1; }
+    return lo;
+}
 #include "../paper_2502_05431_amd/csrc/ape_decode_stream.h"
 
 using namespace ape;

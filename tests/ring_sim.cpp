@@ -23,6 +23,11 @@ static inline const void* ape_ring_load_ptr(const void* const* p) { return *p; }
 static inline void ape_ring_load_chunk(const int32_t* cu_next, const void* const* kp, const void* const* vp, int32_t& c1, const void*& k, const void*& v) {
     c1 = *cu_next; k = *kp; v = *vp;
 }
+static inline int ape_ring_find_chunk(const int32_t* cu, int n_chunks, int t) {
+    int lo = 0, hi = n_chunks - 1;
+    while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (cu[mid] <= t) lo = mid; else hi = mid - 1; }
+    return lo;
+}
 #include "../paper_2502_05431_amd/csrc/ape_ring.h"
 
 using namespace ape;
