@@ -287,7 +287,7 @@ int ape_encode_chunks(const ape_shape* shape,
     if (lse_prefix && !q_prefix) return fail(APE_ERR_INVALID_ARG, "lse_prefix given without q_prefix");
     APE_CHECK_ALIGNED(q_prefix, k_prefix, v_prefix, q_chunks, k_chunks, v_chunks, o_prefix, o_chunks);
     long total = 0;
-    int max_len = 0;
+    int max_len = 0, min_len = INT32_MAX;
     if (n_chunks > 0) {
         if (!cu_host || !cu_dev) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens (host and device) are required");
         if (cu_host[0] != 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens[0] must be 0");
@@ -295,6 +295,7 @@ int ape_encode_chunks(const ape_shape* shape,
             const long li = (long)cu_host[i + 1] - cu_host[i];
             if (li < 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens is not non-decreasing at %d", i);
             if (li > max_len) max_len = (int)li;
+            if (li < min_len) min_len = (int)li;
         }
         total = cu_host[n_chunks];
         if (total > 0 && (!q_chunks || !k_chunks || !v_chunks || !o_chunks)) return fail(APE_ERR_INVALID_ARG, "chunk Q/K/V/O is NULL");
@@ -325,6 +326,7 @@ int ape_encode_chunks(const ape_shape* shape,
         e.cu = cu_dev; e.out = o_chunks; e.lse = lse_chunks;
         e.n_chunks = n_chunks; e.prefix_len = prefix_len; e.total_rows = (int)total; e.max_chunk_len = max_len;
         e.n_q_heads = si.hq; e.n_kv_heads = si.hkv; e.head_dim = si.d;
+        e.uniform_chunks = min_len == max_len;
         hipError_t he = si.mfma ? launch_flash_encode(e, st) : launch_generic_encode(e, si.dtype, st);
         if (he != hipSuccess) return fail(APE_ERR_DEVICE, "encode: %s", hipGetErrorString(he));
     }

@@ -78,8 +78,19 @@ template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 // Rows past n_valid re-read the last valid row: finite data whose probabilities are zero.
 struct LoadOffsets { uint32_t k[2], v[2]; };          // byte offsets of this lane's pieces from a block's row 0
 
-__device__ __forceinline__ LoadOffsets load_offsets(long stride_b, int n_valid) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// The thread index for a tile's set-up (lane offsets, load offsets, query addresses): a kernel that
+// walks several tiles makes it opaque per tile, so that everything derived from it is recomputed
+// per tile instead of being kept in registers across the whole walk (the compiler would hoist it
+// all out of the tile loop, and the block loop has no registers to spare).  Inside the block loop
+// the few uses of the thread index read threadIdx directly, as a one-tile kernel does.
+__device__ __forceinline__ int tile_thread_index() {
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    return tid;
+}
+
+__device__ __forceinline__ LoadOffsets load_offsets(long stride_b, int n_valid, int tid) {
+    const int lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, rl = lane >> 4;
     LoadOffsets o;
 #pragma unroll
@@ -117,7 +128,7 @@ __device__ __forceinline__ void issue_block_load(int i, const char* bk, const ch
 __device__ __forceinline__ void issue_block_loads(const char* bk, const char* bv, int n_valid, long stride_b, char* slot,
                                                   const LoadOffsets& full) {
     LoadOffsets o = full;
-    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets(stride_b, n_valid);
+    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets(stride_b, n_valid, threadIdx.x);
 #pragma unroll
     for (int i = 0; i < LOADS_PER_BLOCK; ++i) issue_block_load(i, bk, bv, slot, o);
 }
@@ -173,8 +184,8 @@ struct LaneOffsets {
     int v[4];                    // V^T fragment for dim block db; + 4096*sl + 2048*half
 };
 
-__device__ __forceinline__ LaneOffsets lane_offsets() {
-    const int lane = threadIdx.x & 63;
+__device__ __forceinline__ LaneOffsets lane_offsets(int tid) {
+    const int lane = tid & 63;
     const int l32 = lane & 31, hi = lane >> 5, g16 = lane >> 4, s16 = lane & 15;
     LaneOffsets o;
     // A operand of K Q^T: token row l32, dims 16*ks + 8*hi .. +7 = chunk 2*ks + hi
@@ -604,16 +615,18 @@ struct RingStart {
     static constexpr int NF = RING - 3;
     RingPlan<RING> plan;
     LoadOffsets full;
+    int tid;                      // the tile's thread index (see tile_thread_index)
     int d0;
     int first[NF + 1];
 };
 
 template <int RING>
-__device__ __forceinline__ void start_stream(RingStart<RING>& rs, const Stream& ld0, char* lds, int vis_lo) {
+__device__ __forceinline__ void start_stream(RingStart<RING>& rs, const Stream& ld0, char* lds, int vis_lo, int tid) {
     constexpr int NF = RING - 3;
     rs.plan.ld = ld0;
     rs.plan.vis_lo = vis_lo;
-    rs.full = load_offsets(ld0.stride_b, BLK);
+    rs.full = load_offsets(ld0.stride_b, BLK, tid);
+    rs.tid = tid;
     rs.d0 = 0;
 #pragma unroll
     for (int i = 0; i <= NF; ++i) rs.first[i] = 0;
@@ -637,7 +650,7 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
     const LoadOffsets full = rs.full;
     const int d0 = rs.d0;
     const int (&first)[NF + 1] = rs.first;
-    const LaneOffsets lo = lane_offsets();
+    const LaneOffsets lo = lane_offsets(rs.tid);
     // block 0 has landed when at most the NF younger blocks are in flight; loads of the caller
     // that are younger still (the query fragments) only make this wait longer
     f32x16 s_b[RB], s_c[RB];
@@ -744,7 +757,8 @@ template <int RB, int G>
 __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, int n_qtiles) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int BM = NW * 32 * RB;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     // Blocks of the context splits come first: they are the long ones, and the grid is planned so
     // that they fill the chip exactly once; the short prefix+self workgroups follow.
@@ -790,7 +804,7 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
         vis_lo = tok_lo + causal_off;
     }
     RingStart<Ring<RB>::slots> rs;
-    start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(vis_lo));
+    start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(vis_lo), tid);
 
     // Q fragments (B operand: row = lane & 31, dims 16*ks + 8*hi .. +7)
     bf16x8 qf[RB][8];
@@ -840,15 +854,15 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
 
 // ------------------------------------------------------------------------------------------
 // Block-diagonal causal encode: team = (chunk, KV head), members = query tiles of the chunk,
-// heaviest (last) tile first.  Writes the final bf16 output.
+// heaviest (last) tile first.  Writes the final bf16 output.  `vblock` is the tile's index in the
+// order team_of_block() defines (the blockIdx of a launch with one workgroup per tile).
 template <int RB, int G>
-__global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, int n_qtiles) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+__device__ __forceinline__ void encode_tile(const EncodeArgs a, const int n_qtiles, const int vblock, char* const lds, const int tid) {
     constexpr int BM = NW * 32 * RB;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     int team, member;
-    team_of_block(blockIdx.x, n_qtiles, team, member);
+    team_of_block(vblock, n_qtiles, team, member);
     if (team >= a.n_chunks * a.n_kv_heads) return;
     const int qtile = n_qtiles - 1 - member;
     const int chunk = team / a.n_kv_heads, hk = team % a.n_kv_heads;
@@ -868,7 +882,7 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
               (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
               wg_tok_hi + 1, stride_b);
     RingStart<Ring<RB>::slots> rs;
-    start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(tok_lo));
+    start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(tok_lo), tid);
 
     bf16x8 qf[RB][8];
     int lim[RB];
@@ -955,6 +969,33 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
     }
 }
 
+// Two launch shapes.  One workgroup per tile (rounds == 0): the hardware hands out the tiles.
+// Resident workgroups (rounds > 0; the grid is 8 * slots_per_xcd workgroups, as many as the chip holds
+// at once): each walks `rounds` tiles of its own XCD's list, so the ~3 us between the end of one
+// workgroup and the start of the next on the same CU are paid once, not per tile.  A tile's weight
+// falls with its index inside a team (the last query tile of a chunk sees the most keys), so the
+// direction of the walk alternates from round to round: the workgroup that drew the heaviest tile
+// of a round draws the lightest of the next.  Used when all chunks have the same length, where this
+// static deal is balanced.
+template <int RB, int G>
+__global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, int n_qtiles, int slots_per_xcd, int rounds) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if constexpr (RB == 2) {
+        // (the wide tile always runs one tile per workgroup: its chunks are long, and a tile loop around
+        // its block loop costs it registers it does not have)
+        encode_tile<RB, G>(a, n_qtiles, blockIdx.x, lds, threadIdx.x);
+    } else {
+        if (rounds == 0) { encode_tile<RB, G>(a, n_qtiles, blockIdx.x, lds, threadIdx.x); return; }
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        for (int k = 0; k < rounds; ++k) {
+            // (every wavefront has read its output rows back from LDS before the next tile's loads overwrite them)
+            if (k > 0) ring_barrier();
+            const int v = k * slots_per_xcd + ((k & 1) ? slots_per_xcd - 1 - slot : slot);
+            encode_tile<RB, G>(a, n_qtiles, v * 8 + xcd, lds, tile_thread_index());
+        }
+    }
+}
+
 template <int RB, int G>
 hipError_t launch_prefill_t(const QueryArgs& a, dim3 grid, int n_qtiles, hipStream_t s) {
     hipError_t e = hipFuncSetAttribute((const void*)flash_prefill_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
@@ -964,10 +1005,10 @@ hipError_t launch_prefill_t(const QueryArgs& a, dim3 grid, int n_qtiles, hipStre
 }
 
 template <int RB, int G>
-hipError_t launch_encode_t(const EncodeArgs& a, unsigned grid, int n_qtiles, hipStream_t s) {
+hipError_t launch_encode_t(const EncodeArgs& a, unsigned grid, int n_qtiles, int slots_per_xcd, int rounds, hipStream_t s) {
     hipError_t e = hipFuncSetAttribute((const void*)flash_encode_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
     if (e != hipSuccess) return e;
-    flash_encode_kernel<RB, G><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles);
+    flash_encode_kernel<RB, G><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles, slots_per_xcd, rounds);
     return hipGetLastError();
 }
 
@@ -982,12 +1023,12 @@ hipError_t launch_prefill_g(int group, const QueryArgs& a, dim3 grid, int n_qtil
 }
 
 template <int RB>
-hipError_t launch_encode_g(int group, const EncodeArgs& a, unsigned grid, int n_qtiles, hipStream_t s) {
+hipError_t launch_encode_g(int group, const EncodeArgs& a, unsigned grid, int n_qtiles, int slots_per_xcd, int rounds, hipStream_t s) {
     switch (group) {
-        case 1: return launch_encode_t<RB, 1>(a, grid, n_qtiles, s);
-        case 2: return launch_encode_t<RB, 2>(a, grid, n_qtiles, s);
-        case 4: return launch_encode_t<RB, 4>(a, grid, n_qtiles, s);
-        default: return launch_encode_t<RB, 8>(a, grid, n_qtiles, s);
+        case 1: return launch_encode_t<RB, 1>(a, grid, n_qtiles, slots_per_xcd, rounds, s);
+        case 2: return launch_encode_t<RB, 2>(a, grid, n_qtiles, slots_per_xcd, rounds, s);
+        case 4: return launch_encode_t<RB, 4>(a, grid, n_qtiles, slots_per_xcd, rounds, s);
+        default: return launch_encode_t<RB, 8>(a, grid, n_qtiles, slots_per_xcd, rounds, s);
     }
 }
 
@@ -1032,8 +1073,27 @@ hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s) {
     const int bm = a.max_chunk_len > 4096 ? flash_block_rows(rows) : 128;
     const int n_qtiles = (rows + bm - 1) / bm;
     const int teams = a.n_chunks * a.n_kv_heads;
-    const unsigned grid = (unsigned)((teams + 7) / 8 * 8 * n_qtiles);
-    return bm == 256 ? launch_encode_g<2>(group, a, grid, n_qtiles, s) : launch_encode_g<1>(group, a, grid, n_qtiles, s);
+    unsigned grid = (unsigned)((teams + 7) / 8 * 8 * n_qtiles);
+    // Resident workgroups (two of the narrow tile per CU, walking the tiles in a fixed deal) for many
+    // short chunks of one length: there a tile is a handful of blocks and the ~3 us between two
+    // workgroups on a CU weigh most (measured: 512 x 256 tokens 0.821 -> 0.798 ms, 20 x 512 0.087 ->
+    // 0.084 ms).  Longer chunks are better off with the hardware handing out the tiles: CUs differ in
+    // speed by a few per cent and a fixed deal ends with the slowest (64 x 2048: 2.34 -> 2.41 ms).
+    int slots_per_xcd = 0, rounds = 0;
+    if (a.uniform_chunks && bm == 128 && a.max_chunk_len <= 1024) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 8) {
+            const int resident = cus / 8 * 2;                                // per XCD
+            const int per_xcd = (int)(grid / 8);
+            if (per_xcd >= 4 * resident) {
+                slots_per_xcd = resident;
+                rounds = (per_xcd + resident - 1) / resident;
+                grid = (unsigned)(8 * resident);
+            }
+        }
+    }
+    return bm == 256 ? launch_encode_g<2>(group, a, grid, n_qtiles, slots_per_xcd, rounds, s)
+                     : launch_encode_g<1>(group, a, grid, n_qtiles, slots_per_xcd, rounds, s);
 }
 
 }  // namespace ape

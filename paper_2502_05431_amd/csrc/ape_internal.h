@@ -130,6 +130,7 @@ struct EncodeArgs {
     int32_t n_q_heads;
     int32_t n_kv_heads;
     int32_t head_dim;
+    int32_t uniform_chunks;     // != 0: every chunk has max_chunk_len tokens (known on the host)
 };
 
 // Kernel-argument block of the rotary embedding + cache write.

@@ -51,13 +51,13 @@ int check_layer(const ape_layer_weights* w, int idx) {
 // What every layer of a call shares, checked once.
 struct Contexts {
     const int32_t* cu_dev;
-    int n_chunks, max_len, prefix_len;
+    int n_chunks, max_len, min_len, prefix_len;
     long rows;
 };
 
 int check_contexts(const ShapeInfo& si, int32_t prefix_len, const int32_t* cu_host, const int32_t* cu_dev, int32_t n_chunks, Contexts* c) {
     if (prefix_len < 0 || n_chunks < 0) return fail(APE_ERR_INVALID_ARG, "prefix_len and n_chunks must be >= 0");
-    c->cu_dev = cu_dev; c->n_chunks = n_chunks; c->prefix_len = prefix_len; c->max_len = 0; c->rows = 0;
+    c->cu_dev = cu_dev; c->n_chunks = n_chunks; c->prefix_len = prefix_len; c->max_len = 0; c->min_len = INT32_MAX; c->rows = 0;
     if (n_chunks == 0) return APE_OK;
     if (!cu_host || !cu_dev) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens (host and device) are required");
     if (cu_host[0] != 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens[0] must be 0");
@@ -65,6 +65,7 @@ int check_contexts(const ShapeInfo& si, int32_t prefix_len, const int32_t* cu_ho
         const long li = (long)cu_host[i + 1] - cu_host[i];
         if (li < 0) return fail(APE_ERR_INVALID_ARG, "cu_chunk_lens is not non-decreasing at %d", i);
         if (li > c->max_len) c->max_len = (int)li;
+        if (li < c->min_len) c->min_len = (int)li;
     }
     c->rows = cu_host[n_chunks];
     return c->rows > 0 ? check_encode_size(si, n_chunks, c->max_len, c->rows) : APE_OK;
@@ -100,7 +101,7 @@ int run_layer(const ShapeInfo& si, const ape_layer_weights* w, const Contexts& c
     e.q = q_rot; e.k = k_cache; e.v = v_cache; e.k_prefix = k_prefix; e.v_prefix = v_prefix;
     e.cu = c.cu_dev; e.out = attn; e.lse = nullptr;
     e.n_chunks = c.n_chunks; e.prefix_len = c.prefix_len; e.total_rows = (int)rows; e.max_chunk_len = c.max_len;
-    e.n_q_heads = si.hq; e.n_kv_heads = si.hkv; e.head_dim = si.d;
+    e.n_q_heads = si.hq; e.n_kv_heads = si.hkv; e.head_dim = si.d; e.uniform_chunks = c.min_len == c.max_len;
     he = si.mfma ? launch_flash_encode(e, st) : launch_generic_encode(e, si.dtype, st);
     if (he != hipSuccess) return dev_fail("encode attention", he);
     if (gemm_xwT(attn, qd, w->w_o, x, x1, hidden, rows, hidden, qd, si.dtype, st)) return fail(APE_ERR_DEVICE, "output projection (rocBLAS) failed");

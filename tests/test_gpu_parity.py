@@ -143,6 +143,18 @@ def test_cfg2_rag_bf16_all_rows():
         _check_decode(spec, r, h, spec.q_len + step + 1, what="cfg2 step %d" % step)
 
 
+@pytest.mark.parametrize("n_chunks, chunk_len, hq, hkv", [(300, 100, 16, 2), (700, 33, 32, 8), (129, 1024, 8, 8)])
+def test_many_short_chunks_of_one_length_all_rows(n_chunks, chunk_len, hq, hkv):
+    """Many short chunks of one length: the encode then runs resident workgroups that each walk
+    several tiles in a fixed deal (rounds that do not fill up, teams that pad the grid, 1, 4 and 8
+    heads per KV head): every row against the oracle."""
+    spec = W.CONFIGS[2].replace(chunk_lens=(chunk_len,) * n_chunks, n_q_heads=hq, n_kv_heads=hkv, q_len=8, decode_steps=0,
+                                prefix_len=19, k_scale=1.0)
+    r = W.make_request(spec, DEV)
+    h = H.HostArrays(r)
+    _check_encode(spec, r, h, what="%d x %d" % (n_chunks, chunk_len))
+
+
 def test_cfg2_generic_path_agrees():
     """The portable kernels on the same bf16 workload (cross-check of the two GPU paths through
     the oracle, each to the bf16 tolerance)."""
