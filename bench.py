@@ -89,6 +89,9 @@ def main():
                     help="also time torch's scaled_dot_product_attention (the vendor's fused attention) on the two "
                          "contractions of config 3: causal attention over 64 sequences of 2048 tokens (the encode without "
                          "its shared prefix) and 256 query rows over 131K keys (the context group of the prefill)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the probes of the box's own ceilings (MFMA rate on zero and on random operands, the same "
+                         "with a softmax's vector work beside it, a read-only HBM stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings in a --pmc run)")
@@ -460,6 +463,31 @@ def main():
                             "same flop convention (unmasked pairs only)")
         del qe, ke, ve, qp, kp, vp
 
+    # ---- what this machine can do at all: the published peaks assume clocks the chip does not hold under
+    # a full matrix-core load on random data (it is power-limited), so the measured ceilings are
+    # reported next to them.  Context for the roofline fractions, which stay against the published peaks.
+    ceilings = None
+    if not args.no_ceilings:
+        sink = torch.zeros(4, dtype=torch.float32, device=dev)
+        ops_zero = torch.zeros(65536 // 2, dtype=torch.bfloat16, device=dev)
+        gp = torch.Generator(device=dev)
+        gp.manual_seed(r.seed + 31)
+        ops_rand = torch.randn(65536 // 2, generator=gp, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        big = torch.empty(1 << 29, dtype=torch.float32, device=dev).normal_()      # 2 GiB, beyond the last-level cache
+        ceilings = {
+            "mfma_bf16_zero_operands_tflops": B.probe_mfma(ops_zero, False, sink),
+            "mfma_bf16_random_operands_tflops": B.probe_mfma(ops_rand, False, sink),
+            "mfma_bf16_random_operands_with_softmax_valu_tflops": B.probe_mfma(ops_rand, True, sink),
+            "hbm_read_only_gbs": B.probe_hbm_read(big, sink),
+            "note": "libape_probe.so: MFMA 32x32x16 bf16 back to back, one wavefront per SIMD on every CU (no LDS, no loads); "
+                    "the third figure adds the vector work of a flash-attention softmax (per pair of scores 2 FMA, 2 exp, 2 add, "
+                    "1 packed conversion) in the MFMAs' shadows; read-only stream over 2 GiB",
+        }
+        for key in ("mfma_bf16_zero_operands_tflops", "mfma_bf16_random_operands_tflops", "mfma_bf16_random_operands_with_softmax_valu_tflops"):
+            ceilings[key.replace("_tflops", "_frac_of_published_peak")] = ceilings[key] / PEAK_BF16_TFLOPS
+        ceilings["hbm_read_only_frac_of_published_peak"] = ceilings["hbm_read_only_gbs"] / PEAK_HBM_GBS
+        del big, ops_zero, ops_rand
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -533,6 +561,8 @@ def main():
         "headline_decode_gbs": phases.get("decode_cfg5_batch32", {}).get("gbs"),
         "phases": phases, "roofline": roof, "cpu_baseline": cpu,
     }
+    if ceilings is not None:
+        line["measured_ceilings"] = ceilings
     if gemm_ref is not None:
         line["gemm_reference"] = gemm_ref
     if sdpa_ref is not None:

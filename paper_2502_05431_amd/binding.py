@@ -17,6 +17,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libape_hip.so")
 LAYER_LIB_PATH = os.path.join(_PKG, "libape_layer.so")
+PROBE_LIB_PATH = os.path.join(_PKG, "libape_probe.so")
 
 APE_OK = 0
 APE_ERR_INVALID_ARG, APE_ERR_UNSUPPORTED, APE_ERR_WORKSPACE, APE_ERR_DEVICE = -1, -2, -3, -4
@@ -28,6 +29,7 @@ EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", 
            "ape_attention_prefill_batch", "ape_attention_decode_static",
            "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
            "ape_status_string", "ape_last_error", "ape_version")
+PROBE_EXPORTS = ("ape_probe_mfma", "ape_probe_hbm_read")
 LAYER_EXPORTS = ("ape_layer_workspace_bytes", "ape_layers_workspace_bytes", "ape_layer_encode", "ape_layers_encode")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
 APE_STATIC_SCRATCH_BYTES = 8 << 20
@@ -138,6 +140,42 @@ def load_layer() -> ctypes.CDLL:
         lib.ape_layers_encode.restype = ctypes.c_int
         _layer_lib = lib
     return _layer_lib
+
+
+_probe_lib = None
+
+
+def load_probe() -> ctypes.CDLL:
+    """Load the probe library (microbenchmarks of the box's ceilings, used by bench.py)."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise RuntimeError("%s is missing: build it with `python -m paper_2502_05431_amd.build`" % PROBE_LIB_PATH)
+        lib = ctypes.CDLL(PROBE_LIB_PATH)
+        vp = ctypes.c_void_p
+        lib.ape_probe_mfma.argtypes = [vp, ctypes.c_int, vp, ctypes.c_float, vp, ctypes.POINTER(ctypes.c_double)]
+        lib.ape_probe_mfma.restype = ctypes.c_int
+        lib.ape_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_float, vp, ctypes.POINTER(ctypes.c_double)]
+        lib.ape_probe_hbm_read.restype = ctypes.c_int
+        _probe_lib = lib
+    return _probe_lib
+
+
+def probe_mfma(operands: torch.Tensor, with_softmax: bool, sink: torch.Tensor, warm_ms: float = 150.0, stream=None) -> float:
+    """``ape_probe_mfma``: TFLOP/s of back-to-back bf16 MFMAs on the given 64 KiB of operand data."""
+    assert operands.numel() * operands.element_size() >= 65536
+    out = ctypes.c_double(0.0)
+    if load_probe().ape_probe_mfma(_ptr(operands), 1 if with_softmax else 0, _ptr(sink), warm_ms, _stream(stream), ctypes.byref(out)):
+        raise RuntimeError("ape_probe_mfma failed")
+    return out.value
+
+
+def probe_hbm_read(buf: torch.Tensor, sink: torch.Tensor, warm_ms: float = 150.0, stream=None) -> float:
+    """``ape_probe_hbm_read``: GB/s of a read-only kernel over ``buf``."""
+    out = ctypes.c_double(0.0)
+    if load_probe().ape_probe_hbm_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), warm_ms, _stream(stream), ctypes.byref(out)):
+        raise RuntimeError("ape_probe_hbm_read failed")
+    return out.value
 
 
 def _check(rc: int):

@@ -1,5 +1,6 @@
 """Builds ``libape_hip.so`` (the C-ABI attention library; depends on the HIP runtime only) and
-``libape_layer.so`` (whole layers around it; links rocBLAS and libape_hip.so) for gfx950 with hipcc.
+``libape_layer.so`` (whole layers around it; links rocBLAS and libape_hip.so) and ``libape_probe.so``
+(microbenchmarks of the box's ceilings for bench.py) for gfx950 with hipcc.
 
 Usage: ``python -m paper_2502_05431_amd.build`` (cross-compiles without a GPU).
 """
@@ -17,6 +18,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libape_hip.so")
 LAYER_LIB = os.path.join(PKG, "libape_layer.so")
+PROBE_LIB = os.path.join(PKG, "libape_probe.so")
 RESOURCES = os.path.join(PKG, "_build", "kernel_resources.json")
 
 # -packed-fp32-ops off: packed fp32 VALU forms are not used on the test machines.
@@ -43,6 +45,10 @@ def layer_sources():
     return sorted(glob.glob(os.path.join(CSRC, "layer", "*.hip")))
 
 
+def probe_sources():
+    return sorted(glob.glob(os.path.join(CSRC, "probe", "*.hip")))
+
+
 _REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|"
                      r"LDS Size \[bytes/block\]|SGPRs): (\S+)")
 
@@ -66,13 +72,14 @@ def build(verbose: bool = True, extra=()) -> str:
     objs = []
     procs = []
     layer_objs = []
-    for src in sources() + layer_sources():
+    probe_objs = []
+    for src in sources() + layer_sources() + probe_sources():
         obj = os.path.join(PKG, "_build", os.path.basename(src) + ".o")
         os.makedirs(os.path.dirname(obj), exist_ok=True)
         cmd = ["hipcc", *[f for f in HIPCC_FLAGS if f != "-shared"], *EXTRA_FLAGS.get(os.path.basename(src), []),
                "-Rpass-analysis=kernel-resource-usage", *extra, "-c", src, "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-        (layer_objs if os.path.dirname(src).endswith("layer") else objs).append(obj)
+        (layer_objs if os.path.dirname(src).endswith("layer") else probe_objs if os.path.dirname(src).endswith("probe") else objs).append(obj)
     failed = False
     resources = {}
     for src, p in procs:
@@ -94,6 +101,10 @@ def build(verbose: bool = True, extra=()) -> str:
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *layer_objs,
                            "-L" + PKG, "-lape_hip", "-Wl,-rpath,$ORIGIN", "-lrocblas"])
     os.replace(tmp, LAYER_LIB)
+    # the probes of the box's ceilings (bench.py): on their own
+    tmp = PROBE_LIB + ".tmp%d" % os.getpid()
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *probe_objs])
+    os.replace(tmp, PROBE_LIB)
     with open(RESOURCES, "w") as f:
         json.dump(resources, f, indent=1, sort_keys=True)
     return LIB

@@ -46,6 +46,17 @@ def test_layer_library_exports_every_declared_symbol_and_the_attention_library_n
     assert B.layer_workspace_bytes(sh, 4095, 14336, 1000) == 0
 
 
+def test_probe_library_exports_every_declared_symbol():
+    lib = B.load_probe()
+    names = header_functions("ape_probe.h")
+    assert set(names) == set(B.PROBE_EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    out = ctypes.c_double(0.0)
+    assert lib.ape_probe_mfma(None, 0, None, 0.0, None, ctypes.byref(out)) != 0      # refused on the host, nothing launched
+    assert lib.ape_probe_hbm_read(None, 0, None, 0.0, None, ctypes.byref(out)) != 0
+
+
 def test_status_strings():
     lib = B.load()
     for code in (0, -1, -2, -3, -4):
