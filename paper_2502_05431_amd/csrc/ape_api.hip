@@ -128,11 +128,18 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     return p;
 }
 
-// Split plan of a decode step: one workgroup per (request, KV head, split) on the matrix-core path,
-// about 2048 of them, splits of at least 512 tokens.
+// Split plan of a decode step.  Matrix-core path: one workgroup per (request, KV head, split).  Rule
+// fitted to a sweep over batches 1..128 of 2K..128K contexts (split lengths 256..16384 each): at least
+// 8 splits per request (fewer leave too few workgroups next to the short prefix+self ones), more
+// when the batch is small -- up to about 2048 workgroups for batches of 8 requests and more, 512 for 2
+// to 4 requests, 256 for a single one (one per CU: with more, the partial results and their merge
+// cost more than the extra workgroups bring) -- never shorter than 256 tokens.
 QueryPlan decode_plan(const ShapeInfo& si, int batch, long max_ctx) {
-    const int base = si.mfma ? batch * si.hkv : batch * si.hq;
-    return plan_query(base, max_ctx, si.mfma ? 512 : 256, si.mfma ? 2048 : 1024);
+    if (!si.mfma) return plan_query(batch * si.hq, max_ctx, 256, 1024);
+    const int base = batch * si.hkv;
+    const int target = base <= 8 ? 256 : base <= 32 ? 512 : 2048;
+    const int want = ceil_div(target, base);
+    return plan_query(base, max_ctx, 256, (want < 8 ? 8 : want) * base);
 }
 
 // Split plan of the query prefill.  Matrix-core path: about one workgroup per CU (two of the narrow
@@ -381,7 +388,8 @@ static int run_query(const ShapeInfo& si, const ape_request* reqs, int batch, in
         a.n_ctx_splits = plan.n_ctx_splits; a.ctx_split_len = plan.ctx_split_len;
         a.units_total = (int)units; a.req_base = b0;
         hipError_t he;
-        if (si.mfma) he = decode ? launch_decode_mfma(a, st) : launch_flash_prefill(a, plan.block_rows, st);
+        // (a decode step is a query of one row: the flash kernel's narrow tile, one wavefront computing)
+        if (si.mfma) he = launch_flash_prefill(a, decode ? 128 : plan.block_rows, st);
         else he = launch_generic_query(a, si.dtype, st);
         if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
 
@@ -545,7 +553,7 @@ int ape_attention_tree(const ape_shape* shape, const ape_request* req,
     a.n_ctx_splits = plan.max_splits; a.ctx_split_len = plan.len;
     a.split_ranges = plan_dev + TreePlanLayout{n_nodes, plan.max_splits}.ranges_at();
     a.units_total = (int)units; a.req_base = 0;
-    if (si.mfma) he = q_len == 1 ? launch_decode_mfma(a, st) : launch_flash_prefill(a, plan.block_rows, st);
+    if (si.mfma) he = launch_flash_prefill(a, q_len == 1 ? 128 : plan.block_rows, st);
     else he = launch_generic_query(a, si.dtype, st);
     if (he != hipSuccess) return fail(APE_ERR_DEVICE, "attention kernel: %s", hipGetErrorString(he));
 

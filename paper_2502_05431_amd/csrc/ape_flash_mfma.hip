@@ -76,7 +76,14 @@ template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 // lane i = (row r = i/16, physical chunk c = i%16) fetches logical chunk c ^ f(r).
 // Wavefront w fills rows 8w .. 8w+7 of K and of V: four instructions per block.
 // Rows past n_valid re-read the last valid row: finite data whose probabilities are zero.
-struct LoadOffsets { uint32_t k[2], v[2]; };          // byte offsets of this lane's pieces from a block's row 0
+// NT: the loads carry the non-temporal hint (the block is read by this workgroup only and will not be
+// read again: a decode step, a query of a few rows).  Streams at 6.2 instead of 5.3 TB/s; K/V that
+// other workgroups re-read from L2 (the encode, a query of several row tiles) must not carry it.
+template <bool NT>
+struct LoadOffsetsT {
+    uint32_t k[2], v[2];                                  // byte offsets of this lane's pieces from a block's row 0
+    static constexpr bool nt = NT;
+};
 
 // The thread index for a tile's set-up (lane offsets, load offsets, query addresses): a kernel that
 // walks several tiles makes it opaque per tile, so that everything derived from it is recomputed
@@ -89,10 +96,11 @@ __device__ __forceinline__ int tile_thread_index() {
     return tid;
 }
 
-__device__ __forceinline__ LoadOffsets load_offsets(long stride_b, int n_valid, int tid) {
+template <bool NT>
+__device__ __forceinline__ LoadOffsetsT<NT> load_offsets(long stride_b, int n_valid, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, rl = lane >> 4;
-    LoadOffsets o;
+    LoadOffsetsT<NT> o;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = 8 * wave + 4 * i + rl;
@@ -109,32 +117,40 @@ __device__ __forceinline__ LoadOffsets load_offsets(long stride_b, int n_valid, 
 // and the compiler then does not track these loads, which is intended -- they are ordered against
 // the LDS reads by the explicit vmcnt waits and barriers of the ring, not by the compiler, which
 // could only wait for all of them.
+template <bool NT>
 __device__ __forceinline__ void dma16(const char* base, uint32_t voff, const char* lds_dst) {
     const uint32_t m0v = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_dst;
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(base), "s"(m0v) : "m0");
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                     :: "v"(voff), "s"(base), "s"(m0v) : "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(voff), "s"(base), "s"(m0v) : "m0");
 }
 
 // Load i (0..3) of a block: wavefront w fills rows 8w + 4(i/2) .. +3 of K (i even) or V (i odd).
-__device__ __forceinline__ void issue_block_load(int i, const char* bk, const char* bv, char* slot, const LoadOffsets& o) {
+template <class LO>
+__device__ __forceinline__ void issue_block_load(int i, const char* bk, const char* bv, char* slot, const LO& o) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const char* dst = slot + (8 * wave + 4 * (i >> 1)) * ROWB;
-    if ((i & 1) == 0) dma16(bk, o.k[i >> 1], dst);
-    else dma16(bv, o.v[i >> 1], dst + KVB);
+    if ((i & 1) == 0) dma16<LO::nt>(bk, o.k[i >> 1], dst);
+    else dma16<LO::nt>(bv, o.v[i >> 1], dst + KVB);
 }
 
 // `full` holds the offsets of a full block (computed once); a partial block recomputes them with
 // its rows clamped.
+template <class LO>
 __device__ __forceinline__ void issue_block_loads(const char* bk, const char* bv, int n_valid, long stride_b, char* slot,
-                                                  const LoadOffsets& full) {
-    LoadOffsets o = full;
-    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets(stride_b, n_valid, threadIdx.x);
+                                                  const LO& full) {
+    LO o = full;
+    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets<LO::nt>(stride_b, n_valid, threadIdx.x);
 #pragma unroll
     for (int i = 0; i < LOADS_PER_BLOCK; ++i) issue_block_load(i, bk, bv, slot, o);
 }
 
 // Takes the stream's next block and starts its loads into `slot`.
-__device__ __forceinline__ int issue_next(Stream& ld, char* slot, const LoadOffsets& full) {
+template <class LO>
+__device__ __forceinline__ int issue_next(Stream& ld, char* slot, const LO& full) {
     const char *bk, *bv;
     const int d = ld.take(bk, bv);
     issue_block_loads(bk, bv, desc_n(d), ld.stride_b, slot, full);
@@ -377,8 +393,8 @@ __device__ __forceinline__ float vmov(float x) {
 // (d_nxt == 0) the scores are computed from a landed slot and dropped.  (Making these MFMAs
 // conditional costs more than it saves: the accumulators then pass through copies.)
 // On return the plan describes the next body.
-template <int RB, int RING, bool FAST>
-__device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
+template <int RB, int RING, bool FAST, class LO>
+__device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                               const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
                                               f32x16 (&s_b)[RB], u32x4 (&p)[RB][2], bf16x8 (&vf)[8],
                                               RingPlan<RING>& plan, const int (&lim)[RB]) {
@@ -468,8 +484,8 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
 // blocks the softmax of row block 0 runs in the PV half (the PV MFMAs take row block 0 first,
 // which frees its probability registers for the second eight slices), that of row block 1 in the
 // K Q^T half; with one row block its first four slices run in the last four of the PV half.
-template <int RB, int RING>
-__device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
+template <int RB, int RING, class LO>
+__device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                                  const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
                                                  const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB], u32x4 (&p)[RB][2],
                                                  bf16x8 (&vf)[8], RingPlan<RING>& plan) {
@@ -538,8 +554,8 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
 // wait for the MFMAs that read the registers it overwrites, and every one of the 16*RB MFMAs of the
 // body carries half a slice (two exponentials, or two adds and a conversion) in its shadow instead
 // of half of them carrying a whole one.
-template <int RB, int RING>
-__device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const LaneOffsets& lo, const LoadOffsets& full,
+template <int RB, int RING, class LO>
+__device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                                    const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
                                                    const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB],
                                                    const u32x4 (&p_in)[RB][2], u32x4 (&p_out)[RB][2],
@@ -610,22 +626,22 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
 
 // The loads of the first blocks of a stream (blocks 0 .. RING-3), started before anything else in
 // the kernel -- the query fragments are fetched while they fly.
-template <int RING>
+template <int RING, bool NT>
 struct RingStart {
     static constexpr int NF = RING - 3;
     RingPlan<RING> plan;
-    LoadOffsets full;
+    LoadOffsetsT<NT> full;
     int tid;                      // the tile's thread index (see tile_thread_index)
     int d0;
     int first[NF + 1];
 };
 
-template <int RING>
-__device__ __forceinline__ void start_stream(RingStart<RING>& rs, const Stream& ld0, char* lds, int vis_lo, int tid) {
+template <int RING, bool NT>
+__device__ __forceinline__ void start_stream(RingStart<RING, NT>& rs, const Stream& ld0, char* lds, int vis_lo, int tid) {
     constexpr int NF = RING - 3;
     rs.plan.ld = ld0;
     rs.plan.vis_lo = vis_lo;
-    rs.full = load_offsets(ld0.stride_b, BLK, tid);
+    rs.full = load_offsets<NT>(ld0.stride_b, BLK, tid);
     rs.tid = tid;
     rs.d0 = 0;
 #pragma unroll
@@ -640,14 +656,14 @@ __device__ __forceinline__ void start_stream(RingStart<RING>& rs, const Stream& 
 // barriers and the same instruction stream; causal blocks a wavefront's rows do not see are
 // simply masked.  (vis_lo, given to start_stream: the smallest causal limit among this
 // wavefront's rows; blocks up to it need no causal mask.)
-template <int RB>
-__device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char* lds, const bf16x8 (&qf)[RB][8],
+template <int RB, bool NT>
+__device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT>& rs, char* lds, const bf16x8 (&qf)[RB][8],
                                            WaveState<RB>& st, float sc2, const int (&lim)[RB]) {
     constexpr int RING = Ring<RB>::slots;
     constexpr int NF = RING - 3;
     if (rs.d0 == 0) return;
     RingPlan<RING>& plan = rs.plan;
-    const LoadOffsets full = rs.full;
+    const LoadOffsetsT<NT> full = rs.full;
     const int d0 = rs.d0;
     const int (&first)[NF + 1] = rs.first;
     const LaneOffsets lo = lane_offsets(rs.tid);
@@ -728,6 +744,48 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots>& rs, char*
     }
 }
 
+// The block loop of a wavefront NONE of whose rows is a query row (a decode step fills 4 of a
+// workgroup's 128 rows: one wavefront computes, the others only fetch).  Same control flow, same
+// loads, waits and barriers as run_blocks, no matrix or vector work and no LDS reads.
+template <int RB, bool NT>
+__device__ __forceinline__ void run_blocks_idle(RingStart<Ring<RB>::slots, NT>& rs, char* lds) {
+    constexpr int RING = Ring<RB>::slots;
+    constexpr int NF = RING - 3;
+    if (rs.d0 == 0) return;
+    RingPlan<RING>& plan = rs.plan;
+    const LoadOffsetsT<NT> full = rs.full;
+    if (rs.first[NF - 1] != 0) wait_blocks<NF>(); else wait_blocks<0>();
+    ring_barrier();
+    plan.d_cur = rs.d0;
+    plan.d_nxt = rs.first[0];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) plan.fifo[i] = rs.first[i + 1];
+    plan.deep = NF >= 2 && plan.fifo[NF >= 2 ? NF - 2 : 0] != 0;
+    plan.o_pv = (RING - 1) * SLOTB; plan.o_cur = 0; plan.o_nxt = SLOTB; plan.o_new = (RING - 2) * SLOTB;
+    plan.piece(2);
+    plan.piece(3);
+    for (;;) {
+        const int n_fast = plan.fast_bodies();
+        for (int i = 0; i < n_fast; ++i) {
+            wait_blocks<NF >= 2 ? NF - 1 : 0>();
+            ring_barrier();
+#pragma unroll
+            for (int n = 0; n < LOADS_PER_BLOCK; ++n) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+            plan.fast_piece(0); plan.fast_piece(1); plan.fast_piece(2);
+        }
+        if (n_fast > 0) plan.finish_fast(n_fast);
+        const int d_nxt = plan.d_nxt;
+        if (d_nxt != 0) {
+            if (plan.deep) wait_blocks<NF >= 2 ? NF - 1 : 0>(); else wait_blocks<0>();
+            ring_barrier();
+        }
+        if (plan.d_new != 0)
+            issue_block_loads(plan.new_k, plan.new_v, desc_n(plan.d_new), plan.ld.stride_b, lds + plan.o_new, full);
+        if (d_nxt == 0) break;
+        plan.piece(0); plan.piece(1); plan.piece(2); plan.piece(3);
+    }
+}
+
 template <int RB>
 __device__ __forceinline__ void init_state(WaveState<RB>& st) {
 #pragma unroll
@@ -753,7 +811,7 @@ __device__ __forceinline__ void team_of_block(int block, int team_size, int& tea
 // Query prefill: team = (split, KV head); grid = the context teams (padded to a multiple of 8) times
 // n_qtiles, then the prefix+self teams likewise.
 // Rows: R = qtile*BM + wave*32*RB + rb*32 + (lane & 31); query token = R / G, head = hk*G + R % G.
-template <int RB, int G>
+template <int RB, int G, bool NTL>
 __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, int n_qtiles) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int BM = NW * 32 * RB;
@@ -803,7 +861,7 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
                       (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
         vis_lo = tok_lo + causal_off;
     }
-    RingStart<Ring<RB>::slots> rs;
+    RingStart<Ring<RB>::slots, NTL> rs;
     start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(vis_lo), tid);
 
     // Q fragments (B operand: row = lane & 31, dims 16*ks + 8*hi .. +7)
@@ -826,7 +884,9 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
 
     WaveState<RB> st;
     init_state<RB>(st);
-    run_blocks<RB>(rs, lds, qf, st, sc2, lim);
+    // a wavefront without a single query row (R_lo is its first row) only fetches
+    if (RB == 1 && __builtin_amdgcn_readfirstlane(R_lo / G) >= q_len) run_blocks_idle<RB>(rs, lds);
+    else run_blocks<RB>(rs, lds, qf, st, sc2, lim);
 
     // ---- block result (Appendix C.1): normalised values + natural-log LogSumExp
 #pragma unroll
@@ -881,7 +941,7 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs a, const int n_qtil
     walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
               (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
               wg_tok_hi + 1, stride_b);
-    RingStart<Ring<RB>::slots> rs;
+    RingStart<Ring<RB>::slots, false> rs;
     start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(tok_lo), tid);
 
     bf16x8 qf[RB][8];
@@ -996,11 +1056,11 @@ __global__ __launch_bounds__(NT) void flash_encode_kernel(const EncodeArgs a, in
     }
 }
 
-template <int RB, int G>
+template <int RB, int G, bool NTL>
 hipError_t launch_prefill_t(const QueryArgs& a, dim3 grid, int n_qtiles, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute((const void*)flash_prefill_kernel<RB, G>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
+    hipError_t e = hipFuncSetAttribute((const void*)flash_prefill_kernel<RB, G, NTL>, hipFuncAttributeMaxDynamicSharedMemorySize, Ring<RB>::slots * SLOTB);
     if (e != hipSuccess) return e;
-    flash_prefill_kernel<RB, G><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles);
+    flash_prefill_kernel<RB, G, NTL><<<grid, NT, Ring<RB>::slots * SLOTB, s>>>(a, n_qtiles);
     return hipGetLastError();
 }
 
@@ -1012,13 +1072,13 @@ hipError_t launch_encode_t(const EncodeArgs& a, unsigned grid, int n_qtiles, int
     return hipGetLastError();
 }
 
-template <int RB>
+template <int RB, bool NTL>
 hipError_t launch_prefill_g(int group, const QueryArgs& a, dim3 grid, int n_qtiles, hipStream_t s) {
     switch (group) {
-        case 1: return launch_prefill_t<RB, 1>(a, grid, n_qtiles, s);
-        case 2: return launch_prefill_t<RB, 2>(a, grid, n_qtiles, s);
-        case 4: return launch_prefill_t<RB, 4>(a, grid, n_qtiles, s);
-        default: return launch_prefill_t<RB, 8>(a, grid, n_qtiles, s);
+        case 1: return launch_prefill_t<RB, 1, NTL>(a, grid, n_qtiles, s);
+        case 2: return launch_prefill_t<RB, 2, NTL>(a, grid, n_qtiles, s);
+        case 4: return launch_prefill_t<RB, 4, NTL>(a, grid, n_qtiles, s);
+        default: return launch_prefill_t<RB, 8, NTL>(a, grid, n_qtiles, s);
     }
 }
 
@@ -1059,7 +1119,9 @@ hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t 
     const int ctx_teams = a.n_ctx_splits * a.n_kv_heads;
     // x is a multiple of 8, so the workgroups of every request start on the same XCD phase
     const dim3 grid((unsigned)(((ctx_teams + 7) / 8 * 8 + (a.n_kv_heads + 7) / 8 * 8) * n_qtiles), (unsigned)a.n_req);
-    return bm == 256 ? launch_prefill_g<2>(group, a, grid, n_qtiles, s) : launch_prefill_g<1>(group, a, grid, n_qtiles, s);
+    if (bm == 256) return launch_prefill_g<2, false>(group, a, grid, n_qtiles, s);
+    // one row tile: every K/V block is fetched by one workgroup and never again -> non-temporal loads
+    return n_qtiles == 1 ? launch_prefill_g<1, true>(group, a, grid, n_qtiles, s) : launch_prefill_g<1, false>(group, a, grid, n_qtiles, s);
 }
 
 hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s) {

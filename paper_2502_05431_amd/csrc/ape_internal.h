@@ -277,7 +277,6 @@ hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s);
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s);
 hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t s);     // bf16, d = 128; block_rows from the plan
 hipError_t launch_flash_encode(const EncodeArgs& a, hipStream_t s);     // bf16, d = 128
-hipError_t launch_decode_mfma(const QueryArgs& a, hipStream_t s);       // bf16, d = 128, q_len = 1
 
 // rows of (token, group-head) pairs one flash workgroup covers for a given amount of rows
 int flash_block_rows(int rows_per_kv_head);

@@ -84,7 +84,7 @@ def test_workspace_bytes():
     assert B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 0) < 2 * 32 * unit + 512
     d128k = B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 131072)
     d16k = B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 16384)
-    assert 0 < d16k < d128k <= B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, -1)
+    assert 0 < B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, 1024) < d16k <= d128k <= B.workspace_bytes(B.APE_OP_DECODE, sh, 1, 1, -1)
     p128k = B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256, 131072)
     assert 0 < p128k <= p and B.workspace_bytes(B.APE_OP_PREFILL, sh, 1, 256, 1 << 40) == p
     assert p128k < 12 * 8192 * unit                        # config 3: 8 context splits + 1, not the 65-split worst case

@@ -42,13 +42,11 @@ def test_flash_kernels_keep_their_register_budget():
                 # 134..147 when the block loop is undisturbed (the encode, whose tile is a function shared
                 # with the narrow tile's walk over several tiles, sits at 158)
                 assert r["AGPRs"] <= (160 if m.group(1) == "encode" else 150), (name, r)
-    assert seen == 16
+    assert seen == 20                                     # 8 encode, 8 prefill, 4 prefill with non-temporal loads
 
 
-def test_decode_and_merge_kernels_occupancy():
+def test_merge_kernels_occupancy():
     rep = _report()
-    for name, r in rep["ape_decode_mfma.hip"].items():
-        assert r["Occupancy"] >= 2 and r["AGPRs"] == 0, (name, r)
     for name, r in rep["ape_generic.hip"].items():
         if "merge_kernel" in name:
             assert r["Occupancy"] >= 4, (name, r)

@@ -26,20 +26,3 @@ def test_ring_bookkeeping_simulation(tmp_path):
     # the fast path is exercised, not only the generic one
     n_fast = int(last.split(";")[1].split()[0])
     assert n_fast > 1000, last
-
-
-@pytest.mark.skipif(shutil.which("g++") is None, reason="needs a host C++ compiler")
-def test_decode_stream_bookkeeping_simulation(tmp_path):
-    """The decode kernel's token stream (csrc/ape_decode_stream.h: wavefront shares of a split, the
-    walk through the chunk table, prefix and own-KV shares) compiled for the host and driven through
-    ~12 000 cases by tests/decode_stream_sim.cpp: every token once, in order, inside its chunk."""
-    exe = str(tmp_path / "decode_stream_sim")
-    cmd = ["g++", "-O1", "-std=c++17", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-           "-o", exe, os.path.join(HERE, "decode_stream_sim.cpp")]
-    build = subprocess.run(cmd, capture_output=True, text=True)
-    assert build.returncode == 0, build.stderr[-4000:]
-    run = subprocess.run([exe], capture_output=True, text=True, timeout=600)
-    assert run.returncode == 0, (run.stdout[-4000:], run.stderr[-4000:])
-    last = run.stdout.strip().splitlines()[-1]
-    assert " 0 failed" in last, last
-    assert int(last.split(";")[1].split()[0]) > 100000, last          # tiles walked
