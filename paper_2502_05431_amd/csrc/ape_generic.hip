@@ -311,6 +311,108 @@ __global__ __launch_bounds__(kWave * W) void merge_kernel(const MergeArgs a) {
     }
 }
 
+// The same merge for MANY units of head_dim 128 (a query prefill: 8192 units of 9 splits; a batched
+// decode step): a workgroup per unit spends its time being launched (8192 workgroups took 25 us for
+// 40 MB).  Here half a wavefront owns a unit -- lane j holds dims 4j .. 4j+3, so a split's row is one
+// 16-byte load per lane -- eight units per workgroup, no LDS and no barrier: one round trip for the
+// LogSumExps (lane j reads splits j, j + 32, j + 64), the weights by half-wavefront reductions, then
+// the rows with eight loads in flight.
+constexpr int kMergeUnitsPerBlock = 8;
+template <typename T>
+__global__ __launch_bounds__(256) void merge_units_kernel(const MergeArgs a) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int half = lane >> 5, j = lane & 31;
+    const long n_units = (long)a.n_req * a.q_len * a.n_q_heads;
+    const long unit_raw = ((long)blockIdx.x * 4 + wave) * 2 + half;
+    const bool valid = unit_raw < n_units;
+    const long unit = valid ? unit_raw : n_units - 1;                // (a spare half-wavefront recomputes the last unit and stores nothing)
+    const int hq = a.n_q_heads;
+    const int rq = (int)(unit / ((long)hq * a.q_len));
+    const long gunit = (long)a.req_base * a.q_len * hq + unit;
+    auto ka = kernarg<MergeArgs>();
+    const float S = ka->scale[rq];                                   // (per lane: the two halves may belong to different requests)
+    const int tc = ka->total_ctx[rq];
+    const int n_split = a.n_ctx_splits;                              // slots of the context group; slot n_split is prefix + self
+    const int n_ctx = min(n_split, (tc + a.ctx_split_len - 1) / a.ctx_split_len);   // those this request wrote
+    // LogSumExps: slot s lives in lane s % 32 of this half, register s / 32 (at most 65 slots)
+    float l[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int sl = j + 32 * r;
+        const bool used = sl < n_ctx || sl == n_split;
+        l[r] = used ? a.part_lse[(long)sl * a.units_total + gunit] : -INFINITY;
+    }
+    auto half_max = [](float x) {
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+        return x;
+    };
+    auto half_sum = [](float x) {
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) x += __shfl_xor(x, o);
+        return x;
+    };
+    float lc[3];                                                     // context slots only
+#pragma unroll
+    for (int r = 0; r < 3; ++r) lc[r] = (j + 32 * r) < n_ctx ? l[r] : -INFINITY;
+    const float mc = half_max(fmaxf(fmaxf(lc[0], lc[1]), lc[2]));
+    float e[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) e[r] = mc > -INFINITY ? expf(lc[r] - mc) : 0.f;   // 0 for empty and unused slots
+    const float zc = half_sum(e[0] + e[1] + e[2]);
+    const float lse_o = __shfl(l[n_split >> 5], (n_split & 31) + 32 * half);       // prefix + self: never empty
+    // the context splits are pooled first; only then is their LogSumExp multiplied by S
+    const float lse_c = zc > 0.f ? mc + logf(zc) : -INFINITY;
+    const float ac = lse_c > -INFINITY ? S * lse_c : -INFINITY;
+    const float mx = fmaxf(ac, lse_o);
+    const float ec = expf(ac - mx), eo = expf(lse_o - mx);
+    const float wc = ec / (ec + eo), wo = eo / (ec + eo);
+    float w[3];                                                      // weight of this lane's slots in the output
+#pragma unroll
+    for (int r = 0; r < 3; ++r) w[r] = (j + 32 * r) == n_split ? wo : (zc > 0.f ? wc * e[r] / zc : 0.f);
+
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* base = a.part_o + gunit * 128 + 4 * j;
+    const long slot_stride = (long)a.units_total * 128;
+    const int n_slots = n_split + 1;                                 // wavefront-uniform loop bound
+    constexpr int UN = 8;
+    for (int s0 = 0; s0 < n_slots; s0 += UN) {
+        float4 v[UN];
+        float ws[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int sl = min(s0 + u, n_slots - 1);
+            const float wl = __shfl(sl < 32 ? w[0] : sl < 64 ? w[1] : w[2], (sl & 31) + 32 * half);
+            ws[u] = s0 + u < n_slots ? wl : 0.f;
+            // a slot this request did not write is never read (its weight is 0; read the prefix + self slot instead)
+            const int src = (sl < n_ctx || sl == n_split) ? sl : n_split;
+            v[u] = *(const float4*)(base + src * slot_stride);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            acc.x = fmaf(ws[u], v[u].x, acc.x); acc.y = fmaf(ws[u], v[u].y, acc.y);
+            acc.z = fmaf(ws[u], v[u].z, acc.z); acc.w = fmaf(ws[u], v[u].w, acc.w);
+        }
+    }
+    if (!valid) return;
+    T* out = (T*)a.out + gunit * 128 + 4 * j;
+    if constexpr (sizeof(T) == 4) {
+        *(float4*)out = acc;
+    } else {
+        const T o4[4] = {(T)acc.x, (T)acc.y, (T)acc.z, (T)acc.w};
+        *(uint2*)out = *(const uint2*)o4;
+    }
+    if (a.lse_out && j == 0) {
+        const float lse = mx + logf(ec + eo);
+        if (a.lse_head_major) {                                     // [request, head, row]
+            const int h = (int)(unit % hq), row = (int)((unit / hq) % a.q_len);
+            a.lse_out[((long)(a.req_base + rq) * hq + h) * a.q_len + row] = lse;
+        } else {
+            a.lse_out[gunit] = lse;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Tree of contexts (Appendix C.2 applied at every node, Appendix C.5).
 //
@@ -559,6 +661,12 @@ hipError_t launch_generic_encode(const EncodeArgs& a, int dtype, hipStream_t s) 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
     dim3 grid((unsigned)(a.n_req * a.q_len * a.n_q_heads));
     const bool few = a.n_ctx_splits >= 32 && (long)grid.x * a.n_splits_total <= 4096;
+    if (!few && a.head_dim == 128 && grid.x >= 256 && a.n_splits_total <= 65) {
+        const unsigned blocks = (grid.x + kMergeUnitsPerBlock - 1) / kMergeUnitsPerBlock;
+        if (a.dtype == APE_F32) merge_units_kernel<float><<<blocks, 256, 0, s>>>(a);
+        else merge_units_kernel<__bf16><<<blocks, 256, 0, s>>>(a);
+        return hipGetLastError();
+    }
     if (a.dtype == APE_F32) {
         if (few) merge_kernel<float, kMergeWavesFew><<<grid, kWave * kMergeWavesFew, 0, s>>>(a);
         else merge_kernel<float, kMergeWaves><<<grid, kWave * kMergeWaves, 0, s>>>(a);
