@@ -826,7 +826,12 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
     if ((int)blockIdx.x < ctx_blocks) {
         team_of_block(blockIdx.x, n_qtiles, team, qtile);
         if (team >= ctx_teams) return;
-        split = team % a.n_ctx_splits; hk = team / a.n_ctx_splits;
+        // Under a tree plan the slots past the splits in use are empty and leave at once: with the
+        // KV head as the fastest index they are the last workgroups of the context part instead of
+        // sitting between the working ones (where they upset the even deal of one workgroup per CU:
+        // 128K decode 99 us against 84 us for the same splits without empty slots in between).
+        if (a.split_ranges != nullptr) { hk = team % a.n_kv_heads; split = team / a.n_kv_heads; }
+        else { split = team % a.n_ctx_splits; hk = team / a.n_ctx_splits; }
     } else {
         team_of_block(blockIdx.x - ctx_blocks, n_qtiles, team, qtile);
         if (team >= a.n_kv_heads) return;
