@@ -128,17 +128,24 @@ QueryPlan plan_query(int base_workgroups, long max_ctx, int min_len, int target_
     return p;
 }
 
-// Split plan of a decode step.  Matrix-core path: one workgroup per (request, KV head, split).  Rule
-// fitted to a sweep over batches 1..128 of 2K..128K contexts (split lengths 256..16384 each): at least
-// 8 splits per request (fewer leave too few workgroups next to the short prefix+self ones), more
-// when the batch is small -- up to about 2048 workgroups for batches of 8 requests and more, 512 for 2
-// to 4 requests, 256 for a single one (one per CU: with more, the partial results and their merge
-// cost more than the extra workgroups bring) -- never shorter than 256 tokens.
+// Split plan of a decode step.  Matrix-core path: one workgroup per (request, KV head, split), two
+// of them resident per CU.  What decides the rate is how evenly the long (context) workgroups fill the
+// 256 CUs: a count that is a multiple of 256 streams at 81-84 % of the HBM peak (256 itself is best:
+// one long workgroup per CU, the short prefix+self ones run beside them), other counts at 72-79 %
+// (32 requests x 16K: 1 / 2 / 3 / 4 / 8 splits = 84.1 / 82.2 / 76.0 / 80.4 / 80.2 %; 48 requests: 1 / 2 / 4 =
+// 72.1 / 82.0 / 78.9 %; 16 requests: 1 / 2 / 4 = 57.2 / 83.1 / 78.4 %).  So: the smallest number of splits
+// that makes requests x KV heads x splits a multiple of 256, if the splits stay at 256 tokens or more
+// and the count at 2048 or less; otherwise many workgroups (at least 8 splits per request, about
+// 2048 workgroups), where the remainder of the last round matters less.
 QueryPlan decode_plan(const ShapeInfo& si, int batch, long max_ctx) {
     if (!si.mfma) return plan_query(batch * si.hq, max_ctx, 256, 1024);
     const int base = batch * si.hkv;
-    const int target = base <= 8 ? 256 : base <= 32 ? 512 : 2048;
-    const int want = ceil_div(target, base);
+    int g = base, r = 256;
+    while (r != 0) { const int t = g % r; g = r; r = t; }          // g = gcd(base, 256)
+    const int n_even = 256 / g;
+    if ((long)n_even * 256 <= (max_ctx > 256 ? max_ctx : 256) && n_even <= kMaxSplits && (long)base * n_even <= 2048)
+        return plan_query(base, max_ctx, 256, base * n_even);
+    const int want = ceil_div(2048, base);
     return plan_query(base, max_ctx, 256, (want < 8 ? 8 : want) * base);
 }
 
