@@ -946,8 +946,9 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs a, const int n_qtil
     if (team >= a.n_chunks * a.n_kv_heads) return;
     const int qtile = n_qtiles - 1 - member;
     const int chunk = team / a.n_kv_heads, hk = team % a.n_kv_heads;
-    const int c0 = a.cu ? a.cu[chunk] : 0;
-    const int len = a.cu ? a.cu[chunk + 1] - c0 : a.total_rows;
+    // (chunks of one length: no table read in front of the tile's first loads)
+    const int c0 = a.uniform_chunks ? chunk * a.max_chunk_len : a.cu ? a.cu[chunk] : 0;
+    const int len = a.uniform_chunks ? a.max_chunk_len : a.cu ? a.cu[chunk + 1] - c0 : a.total_rows;
     if ((long)qtile * BM >= (long)len * G) return;
     const int hq = a.n_q_heads;
     const long stride_b = (long)a.n_kv_heads * ROWB, head_b = (long)hk * ROWB;

@@ -221,10 +221,12 @@ def test_chunk_table_order_and_separate_buffers():
         H.check_close(H.f64(outd).reshape(-1, spec.head_dim), refd, "bf16", "decode order %s" % (order,))
 
 
-def test_batched_decode_mixed_requests():
-    """Requests of different context sizes, T and S in one decode call (more than one launch's
-    worth of descriptors)."""
-    base = W.CONFIGS[5].replace(batch=35, decode_steps=9)
+@pytest.mark.parametrize("batch", [35, 16, 2])
+def test_batched_decode_mixed_requests(batch):
+    """Requests of different context sizes, T and S in one decode call: more than one launch's
+    worth of descriptors (35), and batches whose split plan differs (the number of context splits
+    depends on the batch; the shorter requests leave some of them empty)."""
+    base = W.CONFIGS[5].replace(batch=batch, decode_steps=9)
     rs, hs, lens = [], [], []
     for b in range(base.batch):
         n_chunks = 1 + b % 4
