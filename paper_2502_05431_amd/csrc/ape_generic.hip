@@ -641,6 +641,154 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const T
     }
 }
 
+// The same tree merge for MANY units of a small tree (a query prefill: 8192 units): one WAVEFRONT per
+// unit, four units per workgroup.  The tree's bookkeeping (nodes, first split and split count of every
+// node) is read once per workgroup and shared; every wavefront has its own node and split values in
+// LDS and walks the levels with no workgroup barrier (the LDS operations of one wavefront complete
+// in order; the fences below only keep the compiler from moving them).  The workgroup-per-unit
+// kernel above spends 19-38 us on 8192 units of a 1- or 9-node tree, most of it barriers and launches.
+constexpr int kTreeUnitsPerBlock = 4;
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+__host__ __device__ inline size_t tree_wave_lds_bytes(int n_nodes, int max_splits) {
+    return (size_t)n_nodes * (sizeof(ape_tree_node) + 2 * sizeof(int)) +
+           (size_t)kTreeUnitsPerBlock * ((size_t)n_nodes * 2 * sizeof(float) + (size_t)max_splits * sizeof(float));
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWave * kTreeUnitsPerBlock) void tree_merge_wave_kernel(const TreeMergeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char tree_lds[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    constexpr int NT = kWave * kTreeUnitsPerBlock;
+    const int d = a.head_dim, U = a.units_total, n_nodes = a.n_nodes;
+    const bool valid = (int)blockIdx.x * kTreeUnitsPerBlock + wave < U;
+    const int unit = valid ? (int)blockIdx.x * kTreeUnitsPerBlock + wave : U - 1;   // (a spare wavefront recomputes the last unit and stores nothing)
+    const TreePlanLayout lay{a.n_nodes, a.max_splits};
+    const int n_used = a.plan[0];
+
+    ape_tree_node* nd = (ape_tree_node*)tree_lds;                  // [n_nodes], shared
+    int* first_split = (int*)(nd + n_nodes);                       // [n_nodes], shared
+    int* n_splits = first_split + n_nodes;                         // [n_nodes], shared
+    float* mine = (float*)(n_splits + n_nodes) + (size_t)wave * (2 * n_nodes + a.max_splits);
+    float* node_l = mine;                                          // [n_nodes] LogSumExp of the children's values
+    float* node_w = node_l + n_nodes;                              // [n_nodes] log-weight in the result
+    float* split_v = node_w + n_nodes;                             // [max_splits] LogSumExp, later log-weight
+
+    for (int n = tid; n < n_nodes; n += NT) {
+        nd[n] = a.nodes[n];
+        first_split[n] = a.plan[lay.first_split_at() + n];
+        n_splits[n] = a.plan[lay.n_splits_at() + n];
+    }
+    for (int s = lane; s < n_used; s += kWave) split_v[s] = a.part_lse[(long)s * U + unit];
+    const float l_other = a.part_lse[(long)a.max_splits * U + unit];
+    __syncthreads();                                               // the only workgroup barrier: the shared bookkeeping
+    const TreeLds t{nd, first_split, node_l, split_v};
+
+    // ---- bottom-up
+    for (int lv = a.n_levels - 1; lv >= 0; --lv) {
+        const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
+        if (n1 - n0 >= kWave) {
+            for (int n = n0 + lane; n < n1; n += kWave) {
+                const int cn = child_count(t, n_splits, n);
+                float m = -INFINITY;
+                for (int i = 0; i < cn; ++i) m = fmaxf(m, child_value(t, n, i));
+                float z = 0.f;
+                if (m > -INFINITY)
+                    for (int i = 0; i < cn; ++i) z += expf(child_value(t, n, i) - m);
+                node_l[n] = m > -INFINITY ? m + logf(z) : -INFINITY;
+            }
+        } else {
+            for (int n = n0; n < n1; ++n) {
+                const int cn = child_count(t, n_splits, n);
+                float m = -INFINITY;
+                for (int i = lane; i < cn; i += kWave) m = fmaxf(m, child_value(t, n, i));
+                m = wave_max(m);
+                float z = 0.f;
+                if (m > -INFINITY)
+                    for (int i = lane; i < cn; i += kWave) z += expf(child_value(t, n, i) - m);
+                z = wave_sum(z);
+                if (lane == 0) node_l[n] = m > -INFINITY ? m + logf(z) : -INFINITY;
+            }
+        }
+        wave_lds_sync();
+    }
+
+    // ---- the root against the prefix + self block (never empty); every lane computes the same
+    const float a_root = nd[0].scale * node_l[0];
+    const float mx = fmaxf(a_root, l_other);
+    const float ltot = mx + logf(expf(a_root - mx) + expf(l_other - mx));
+    if (lane == 0) node_w[0] = a_root > -INFINITY ? a_root - ltot : -INFINITY;
+    wave_lds_sync();
+
+    // ---- top-down: log-weights of nodes, and of splits in place of their LogSumExps
+    for (int lv = 0; lv < a.n_levels; ++lv) {
+        const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
+        const bool per_thread = n1 - n0 >= kWave;
+        for (int n = n0 + (per_thread ? lane : 0); n < n1; n += per_thread ? kWave : 1) {
+            const int cn = child_count(t, n_splits, n);
+            const float w_n = node_w[n], l_n = node_l[n];
+            const bool leaf = nd[n].leaf_children != 0;
+            for (int i = per_thread ? 0 : lane; i < cn; i += per_thread ? 1 : kWave) {
+                const float v = child_value(t, n, i);
+                const float w = (w_n > -INFINITY && v > -INFINITY) ? w_n + v - l_n : -INFINITY;
+                if (leaf) split_v[first_split[n] + i] = w; else node_w[nd[n].first + i] = w;
+            }
+        }
+        wave_lds_sync();
+    }
+
+    // ---- weighted sum of the split results; index n_used stands for the prefix + self block
+    float acc[kMaxDimRegs];
+#pragma unroll
+    for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = 0.f;
+    for (int s0 = 0; s0 <= n_used; s0 += kWave) {
+        const int s = s0 + lane;
+        float w_mine = 0.f;
+        if (s < n_used) w_mine = expf(split_v[s]);                 // exp(-inf) = 0
+        else if (s == n_used) w_mine = expf(l_other - ltot);
+        const int cnt = min(kWave, n_used + 1 - s0);
+        // eight rows in flight; a row of weight zero (an empty split, a slot past the end) is
+        // replaced by the prefix+self row, which always holds finite values
+        constexpr int UN = 8;
+        for (int i = 0; i < cnt; i += UN) {
+            float w[UN];
+            const float* o[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int ii = i + u;
+                w[u] = ii < cnt ? __shfl(w_mine, min(ii, kWave - 1)) : 0.f;
+                const int sp = (w[u] != 0.f && s0 + ii < n_used) ? s0 + ii : a.max_splits;
+                o[u] = a.part_o + ((long)sp * U + unit) * d;
+            }
+            float v[UN][kMaxDimRegs];
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+#pragma unroll
+                for (int r = 0; r < kMaxDimRegs; ++r) {
+                    const int c = lane + kWave * r;
+                    v[u][r] = c < d ? o[u][c] : 0.f;
+                }
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+#pragma unroll
+                for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = fmaf(w[u], v[u][r], acc[r]);
+        }
+    }
+    if (!valid) return;
+    T* out = (T*)a.out + (long)unit * d;
+#pragma unroll
+    for (int r = 0; r < kMaxDimRegs; ++r) {
+        const int c = lane + kWave * r;
+        if (c < d) out[c] = (T)acc[r];
+    }
+    if (a.lse_out && lane == 0) {
+        const int h = unit % a.n_q_heads, row = unit / a.n_q_heads;
+        a.lse_out[(long)h * a.q_len + row] = ltot;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_generic_query(const QueryArgs& a, int dtype, hipStream_t s) {
@@ -683,6 +831,14 @@ hipError_t launch_tree_plan(const TreePlanArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s) {
+    // many units of a small tree: a wavefront per unit
+    const size_t wave_lds = tree_wave_lds_bytes(a.n_nodes, a.max_splits);
+    if (a.units_total >= 256 && wave_lds <= 32 * 1024) {
+        dim3 wgrid((unsigned)((a.units_total + kTreeUnitsPerBlock - 1) / kTreeUnitsPerBlock));
+        if (a.dtype == APE_F32) tree_merge_wave_kernel<float><<<wgrid, kWave * kTreeUnitsPerBlock, wave_lds, s>>>(a);
+        else tree_merge_wave_kernel<__bf16><<<wgrid, kWave * kTreeUnitsPerBlock, wave_lds, s>>>(a);
+        return hipGetLastError();
+    }
     dim3 grid((unsigned)a.units_total);
     const size_t lds = (size_t)a.n_nodes * (sizeof(ape_tree_node) + 4 * sizeof(float)) + (size_t)a.max_splits * sizeof(float);
     hipError_t e;
