@@ -648,6 +648,9 @@ __global__ __launch_bounds__(kWave * kMergeWaves) void tree_merge_kernel(const T
 // in order; the fences below only keep the compiler from moving them).  The workgroup-per-unit
 // kernel above spends 19-38 us on 8192 units of a 1- or 9-node tree, most of it barriers and launches.
 constexpr int kTreeUnitsPerBlock = 4;
+// a level of at least this many nodes gives every lane a node (children read serially); a narrower one
+// takes its nodes one after the other with the children across the lanes (the root and its 64 contexts)
+constexpr int kLanePerNodeMin = 4;
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -657,7 +660,9 @@ __host__ __device__ inline size_t tree_wave_lds_bytes(int n_nodes, int max_split
            (size_t)kTreeUnitsPerBlock * ((size_t)n_nodes * 2 * sizeof(float) + (size_t)max_splits * sizeof(float));
 }
 
-template <typename T>
+// D128: head_dim is 128 and a lane owns dims 2 lane, 2 lane + 1 (one 8-byte load per row); otherwise dims
+// lane + 64 r as in the kernel above.
+template <typename T, bool D128>
 __global__ __launch_bounds__(kWave * kTreeUnitsPerBlock) void tree_merge_wave_kernel(const TreeMergeArgs a) {
     extern __shared__ __attribute__((aligned(16))) char tree_lds[];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -689,7 +694,7 @@ __global__ __launch_bounds__(kWave * kTreeUnitsPerBlock) void tree_merge_wave_ke
     // ---- bottom-up
     for (int lv = a.n_levels - 1; lv >= 0; --lv) {
         const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
-        if (n1 - n0 >= kWave) {
+        if (n1 - n0 >= kLanePerNodeMin) {
             for (int n = n0 + lane; n < n1; n += kWave) {
                 const int cn = child_count(t, n_splits, n);
                 float m = -INFINITY;
@@ -725,7 +730,7 @@ __global__ __launch_bounds__(kWave * kTreeUnitsPerBlock) void tree_merge_wave_ke
     // ---- top-down: log-weights of nodes, and of splits in place of their LogSumExps
     for (int lv = 0; lv < a.n_levels; ++lv) {
         const int n0 = kernarg<TreeMergeArgs>()->level_start[lv], n1 = kernarg<TreeMergeArgs>()->level_start[lv + 1];
-        const bool per_thread = n1 - n0 >= kWave;
+        const bool per_thread = n1 - n0 >= kLanePerNodeMin;
         for (int n = n0 + (per_thread ? lane : 0); n < n1; n += per_thread ? kWave : 1) {
             const int cn = child_count(t, n_splits, n);
             const float w_n = node_w[n], l_n = node_l[n];
@@ -740,9 +745,10 @@ __global__ __launch_bounds__(kWave * kTreeUnitsPerBlock) void tree_merge_wave_ke
     }
 
     // ---- weighted sum of the split results; index n_used stands for the prefix + self block
-    float acc[kMaxDimRegs];
+    constexpr int DR = D128 ? 2 : kMaxDimRegs;
+    float acc[DR];
 #pragma unroll
-    for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = 0.f;
+    for (int r = 0; r < DR; ++r) acc[r] = 0.f;
     for (int s0 = 0; s0 <= n_used; s0 += kWave) {
         const int s = s0 + lane;
         float w_mine = 0.f;
@@ -762,26 +768,41 @@ __global__ __launch_bounds__(kWave * kTreeUnitsPerBlock) void tree_merge_wave_ke
                 const int sp = (w[u] != 0.f && s0 + ii < n_used) ? s0 + ii : a.max_splits;
                 o[u] = a.part_o + ((long)sp * U + unit) * d;
             }
-            float v[UN][kMaxDimRegs];
+            float v[UN][DR];
 #pragma unroll
-            for (int u = 0; u < UN; ++u)
+            for (int u = 0; u < UN; ++u) {
+                if constexpr (D128) {
+                    const float2 x = *(const float2*)(o[u] + 2 * lane);
+                    v[u][0] = x.x; v[u][1] = x.y;
+                } else {
 #pragma unroll
-                for (int r = 0; r < kMaxDimRegs; ++r) {
-                    const int c = lane + kWave * r;
-                    v[u][r] = c < d ? o[u][c] : 0.f;
+                    for (int r = 0; r < DR; ++r) {
+                        const int c = lane + kWave * r;
+                        v[u][r] = c < d ? o[u][c] : 0.f;
+                    }
                 }
+            }
 #pragma unroll
             for (int u = 0; u < UN; ++u)
 #pragma unroll
-                for (int r = 0; r < kMaxDimRegs; ++r) acc[r] = fmaf(w[u], v[u][r], acc[r]);
+                for (int r = 0; r < DR; ++r) acc[r] = fmaf(w[u], v[u][r], acc[r]);
         }
     }
     if (!valid) return;
     T* out = (T*)a.out + (long)unit * d;
+    if constexpr (D128) {
+        if constexpr (sizeof(T) == 4) {
+            *(float2*)(out + 2 * lane) = make_float2(acc[0], acc[1]);
+        } else {
+            const T o2[2] = {(T)acc[0], (T)acc[1]};
+            *(uint32_t*)(out + 2 * lane) = *(const uint32_t*)o2;
+        }
+    } else {
 #pragma unroll
-    for (int r = 0; r < kMaxDimRegs; ++r) {
-        const int c = lane + kWave * r;
-        if (c < d) out[c] = (T)acc[r];
+        for (int r = 0; r < DR; ++r) {
+            const int c = lane + kWave * r;
+            if (c < d) out[c] = (T)acc[r];
+        }
     }
     if (a.lse_out && lane == 0) {
         const int h = unit % a.n_q_heads, row = unit / a.n_q_heads;
@@ -835,8 +856,14 @@ hipError_t launch_tree_merge(const TreeMergeArgs& a, hipStream_t s) {
     const size_t wave_lds = tree_wave_lds_bytes(a.n_nodes, a.max_splits);
     if (a.units_total >= 256 && wave_lds <= 32 * 1024) {
         dim3 wgrid((unsigned)((a.units_total + kTreeUnitsPerBlock - 1) / kTreeUnitsPerBlock));
-        if (a.dtype == APE_F32) tree_merge_wave_kernel<float><<<wgrid, kWave * kTreeUnitsPerBlock, wave_lds, s>>>(a);
-        else tree_merge_wave_kernel<__bf16><<<wgrid, kWave * kTreeUnitsPerBlock, wave_lds, s>>>(a);
+        const unsigned nt = kWave * kTreeUnitsPerBlock;
+        if (a.head_dim == 128) {
+            if (a.dtype == APE_F32) tree_merge_wave_kernel<float, true><<<wgrid, nt, wave_lds, s>>>(a);
+            else tree_merge_wave_kernel<__bf16, true><<<wgrid, nt, wave_lds, s>>>(a);
+        } else {
+            if (a.dtype == APE_F32) tree_merge_wave_kernel<float, false><<<wgrid, nt, wave_lds, s>>>(a);
+            else tree_merge_wave_kernel<__bf16, false><<<wgrid, nt, wave_lds, s>>>(a);
+        }
         return hipGetLastError();
     }
     dim3 grid((unsigned)a.units_total);
