@@ -67,9 +67,17 @@ constexpr float kPsumMax = 0x1p40f;          // a lane's block sum above this: s
 // leaves room for two workgroups per CU, whose wavefronts fill each other's issue gaps.
 template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 
-// LDS layout of a block: K row r at r*256, 16-byte chunk index XOR (r & 15) (conflict-free 16-byte
-// reads down a column of rows); V row r at 8192 + r*256, chunk index XOR 4*(r & 3) (the four rows
-// of one transposing read land in distinct 64-byte windows).
+// LDS layout of a block, two forms for K.
+// Row-major (loads with the non-temporal hint: the bandwidth-bound decode): K row r at r*256, 16-byte
+// chunk index XOR (r & 15) (conflict-free 16-byte reads down a column of rows).
+// Column-major (all other kernels): chunk c of row r at (r >> 4)*4096 + c*256 + (r & 15)*16 -- the 16
+// rows a fragment read touches per pass are 256 consecutive bytes (no conflicts, no swizzle), and the
+// fragment of k-slab ks is at one per-lane offset + 512*ks, an immediate: ONE address register and one
+// addition per body instead of eight of each (a wavefront's instruction issue is what bounds the
+// block loop).  Its loads gather 64 bytes from each of 16 rows per instruction instead of whole rows,
+// which costs streaming rate from HBM -- hence not for the decode.
+// V row r at 8192 + r*256, chunk index XOR 4*(r & 3) (the four rows of one transposing read land in
+// distinct 64-byte windows).
 //
 // Direct global->LDS loads write lane i's 16 bytes at (wave-uniform LDS base) + 16*i, so one
 // instruction fills four consecutive 256-byte rows; the swizzle is applied on the global side:
@@ -79,10 +87,12 @@ template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 // NT: the loads carry the non-temporal hint (the block is read by this workgroup only and will not be
 // read again: a decode step, a query of a few rows).  Streams at 6.2 instead of 5.3 TB/s; K/V that
 // other workgroups re-read from L2 (the encode, a query of several row tiles) must not carry it.
-template <bool NT>
+template <bool NT, bool KCOL>
 struct LoadOffsetsT {
     uint32_t k[2], v[2];                                  // byte offsets of this lane's pieces from a block's row 0
-    static constexpr bool nt = NT;
+    static constexpr bool nt = NT;                        // non-temporal loads
+    static constexpr bool kcol = KCOL;                    // column-major K in LDS
+    static_assert(!(NT && KCOL), "the column-major form gathers 64-byte pieces: not for streams bound by HBM");
 };
 
 // The thread index for a tile's set-up (lane offsets, load offsets, query addresses): a kernel that
@@ -96,17 +106,25 @@ __device__ __forceinline__ int tile_thread_index() {
     return tid;
 }
 
-template <bool NT>
-__device__ __forceinline__ LoadOffsetsT<NT> load_offsets(long stride_b, int n_valid, int tid) {
+template <bool NT, bool KCOL>
+__device__ __forceinline__ LoadOffsetsT<NT, KCOL> load_offsets(long stride_b, int n_valid, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, rl = lane >> 4;
-    LoadOffsetsT<NT> o;
+    LoadOffsetsT<NT, KCOL> o;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = 8 * wave + 4 * i + rl;
         const int rr = r < n_valid ? r : n_valid - 1;
-        o.k[i] = (uint32_t)rr * (uint32_t)stride_b + ((c ^ (r & 15)) << 4);
         o.v[i] = (uint32_t)rr * (uint32_t)stride_b + ((c ^ ((r & 3) << 2)) << 4);
+        if constexpr (!KCOL) {
+            o.k[i] = (uint32_t)rr * (uint32_t)stride_b + ((c ^ (r & 15)) << 4);
+        } else {
+            // column-major K: the wavefront's load i fills LDS bytes 1024*(2*wave + i) .. +1023 of the K part, i.e.
+            // rows 16*(wave >> 1) .. +15 of chunks 8*(wave & 1) + 4*i .. +3; lane = (chunk within those, row)
+            const int rk = 16 * (wave >> 1) + (lane & 15);
+            const int rrk = rk < n_valid ? rk : n_valid - 1;
+            o.k[i] = (uint32_t)rrk * (uint32_t)stride_b + ((8 * (wave & 1) + 4 * i + (lane >> 4)) << 4);
+        }
     }
     return o;
 }
@@ -128,7 +146,8 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t voff, const cha
                      :: "v"(voff), "s"(base), "s"(m0v) : "m0");
 }
 
-// Load i (0..3) of a block: wavefront w fills rows 8w + 4(i/2) .. +3 of K (i even) or V (i odd).
+// Load i (0..3) of a block: wavefront w fills rows 8w + 4(i/2) .. +3 of V (i odd), and of K (i even) in the
+// row-major form; in the column-major form the same 1 KB of the slot holds what load_offsets says.
 template <class LO>
 __device__ __forceinline__ void issue_block_load(int i, const char* bk, const char* bv, char* slot, const LO& o) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -143,7 +162,7 @@ template <class LO>
 __device__ __forceinline__ void issue_block_loads(const char* bk, const char* bv, int n_valid, long stride_b, char* slot,
                                                   const LO& full) {
     LO o = full;
-    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets<LO::nt>(stride_b, n_valid, threadIdx.x);
+    if (__builtin_expect(n_valid < BLK, 0)) o = load_offsets<LO::nt, LO::kcol>(stride_b, n_valid, threadIdx.x);
 #pragma unroll
     for (int i = 0; i < LOADS_PER_BLOCK; ++i) issue_block_load(i, bk, bv, slot, o);
 }
@@ -196,16 +215,18 @@ struct WaveState {
 
 // per-lane LDS byte offsets inside a slot (constant over the loop)
 struct LaneOffsets {
-    int k;                       // K fragment for k-slab ks: k ^ (32*ks)
+    int k;                       // K fragment for k-slab ks: k ^ (32*ks) (row-major), k + 512*ks (column-major)
     int v[4];                    // V^T fragment for dim block db; + 4096*sl + 2048*half
 };
 
+template <bool KCOL>
 __device__ __forceinline__ LaneOffsets lane_offsets(int tid) {
     const int lane = tid & 63;
     const int l32 = lane & 31, hi = lane >> 5, g16 = lane >> 4, s16 = lane & 15;
     LaneOffsets o;
     // A operand of K Q^T: token row l32, dims 16*ks + 8*hi .. +7 = chunk 2*ks + hi
-    o.k = l32 * ROWB + ((hi ^ (l32 & 15)) << 4);
+    if constexpr (KCOL) o.k = (l32 >> 4) * 4096 + hi * 256 + (l32 & 15) * 16;
+    else o.k = l32 * ROWB + ((hi ^ (l32 & 15)) << 4);
     // A operand of V^T P^T via the transposing read: this lane supplies the address of token row
     // 16*sl + 4*(g16 >> 1) + (s16 >> 2) (+8 for the second half), dims 32*db + 16*(g16 & 1) + 4*(s16 & 3) .. +3
     const int row0 = 4 * (g16 >> 1) + (s16 >> 2);
@@ -217,7 +238,7 @@ __device__ __forceinline__ LaneOffsets lane_offsets(int tid) {
 }
 
 // S^T = K Q^T for one block (both row blocks share each K fragment).
-template <int RB>
+template <int RB, bool KCOL>
 __device__ __forceinline__ void scores(const char* slot, const LaneOffsets& lo, const bf16x8 (&qf)[RB][8], f32x16 (&s)[RB]) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
@@ -225,7 +246,7 @@ __device__ __forceinline__ void scores(const char* slot, const LaneOffsets& lo, 
         for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
+        const bf16x8 a = *(const bf16x8*)(slot + (KCOL ? lo.k + 512 * ks : lo.k ^ (32 * ks)));
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
             s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], s[rb], 0, 0, 0);
@@ -335,8 +356,10 @@ __device__ __forceinline__ void rescale(WaveState<RB>& st, const float (&alpha)[
     asm volatile("s_nop 7");
 }
 
+template <bool KCOL>
 __device__ __forceinline__ bf16x8 read_k_frag(const char* slot, const LaneOffsets& lo, int ks) {
-    return *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
+    if constexpr (KCOL) return *(const bf16x8*)(slot + lo.k + 512 * ks);
+    else return *(const bf16x8*)(slot + (lo.k ^ (32 * ks)));
 }
 // V^T fragment f = sl*4 + db
 __device__ __forceinline__ bf16x8 read_v_frag(const char* slot, const LaneOffsets& lo, int f) {
@@ -421,13 +444,13 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
             vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
         }
         if (RB == 2) {                                               // K fragments: slices 2, 3, 4
-            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
-            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
-            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+            if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); kf[4] = read_k_frag<LO::kcol>(slot_nxt, lo, 4); kf[5] = read_k_frag<LO::kcol>(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag<LO::kcol>(slot_nxt, lo, 6); kf[7] = read_k_frag<LO::kcol>(slot_nxt, lo, 7); }
         } else {                                                     // ... after the wait for the V^T fragments: slices 4, 5
             if (n == 4 || n == 5) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag(slot_nxt, lo, 4 * (n - 4) + q);
+                for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
             }
         }
         if (FAST) {
@@ -509,12 +532,12 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
             vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
         }
         if (RB == 2) {
-            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
-            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
-            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+            if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); kf[4] = read_k_frag<LO::kcol>(slot_nxt, lo, 4); kf[5] = read_k_frag<LO::kcol>(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag<LO::kcol>(slot_nxt, lo, 6); kf[7] = read_k_frag<LO::kcol>(slot_nxt, lo, 7); }
         } else if (n == 4 || n == 5) {                               // (after the wait for the V^T fragments)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag(slot_nxt, lo, 4 * (n - 4) + q);
+            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
         }
         if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
         else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
@@ -587,12 +610,12 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
             vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
         }
         if (RB == 2) {
-            if (n == 2) { kf[0] = read_k_frag(slot_nxt, lo, 0); kf[1] = read_k_frag(slot_nxt, lo, 1); kf[2] = read_k_frag(slot_nxt, lo, 2); }
-            if (n == 3) { kf[3] = read_k_frag(slot_nxt, lo, 3); kf[4] = read_k_frag(slot_nxt, lo, 4); kf[5] = read_k_frag(slot_nxt, lo, 5); }
-            if (n == 4) { kf[6] = read_k_frag(slot_nxt, lo, 6); kf[7] = read_k_frag(slot_nxt, lo, 7); }
+            if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
+            if (n == 3) { kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); kf[4] = read_k_frag<LO::kcol>(slot_nxt, lo, 4); kf[5] = read_k_frag<LO::kcol>(slot_nxt, lo, 5); }
+            if (n == 4) { kf[6] = read_k_frag<LO::kcol>(slot_nxt, lo, 6); kf[7] = read_k_frag<LO::kcol>(slot_nxt, lo, 7); }
         } else if (n == 4 || n == 5) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag(slot_nxt, lo, 4 * (n - 4) + q);
+            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
         }
         if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
         else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
@@ -626,22 +649,22 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
 
 // The loads of the first blocks of a stream (blocks 0 .. RING-3), started before anything else in
 // the kernel -- the query fragments are fetched while they fly.
-template <int RING, bool NT>
+template <int RING, bool NT, bool KCOL = false>
 struct RingStart {
     static constexpr int NF = RING - 3;
     RingPlan<RING> plan;
-    LoadOffsetsT<NT> full;
+    LoadOffsetsT<NT, KCOL> full;
     int tid;                      // the tile's thread index (see tile_thread_index)
     int d0;
     int first[NF + 1];
 };
 
-template <int RING, bool NT>
-__device__ __forceinline__ void start_stream(RingStart<RING, NT>& rs, const Stream& ld0, char* lds, int vis_lo, int tid) {
+template <int RING, bool NT, bool KCOL>
+__device__ __forceinline__ void start_stream(RingStart<RING, NT, KCOL>& rs, const Stream& ld0, char* lds, int vis_lo, int tid) {
     constexpr int NF = RING - 3;
     rs.plan.ld = ld0;
     rs.plan.vis_lo = vis_lo;
-    rs.full = load_offsets<NT>(ld0.stride_b, BLK, tid);
+    rs.full = load_offsets<NT, KCOL>(ld0.stride_b, BLK, tid);
     rs.tid = tid;
     rs.d0 = 0;
 #pragma unroll
@@ -656,23 +679,23 @@ __device__ __forceinline__ void start_stream(RingStart<RING, NT>& rs, const Stre
 // barriers and the same instruction stream; causal blocks a wavefront's rows do not see are
 // simply masked.  (vis_lo, given to start_stream: the smallest causal limit among this
 // wavefront's rows; blocks up to it need no causal mask.)
-template <int RB, bool NT>
-__device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT>& rs, char* lds, const bf16x8 (&qf)[RB][8],
+template <int RB, bool NT, bool KCOL>
+__device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>& rs, char* lds, const bf16x8 (&qf)[RB][8],
                                            WaveState<RB>& st, float sc2, const int (&lim)[RB]) {
     constexpr int RING = Ring<RB>::slots;
     constexpr int NF = RING - 3;
     if (rs.d0 == 0) return;
     RingPlan<RING>& plan = rs.plan;
-    const LoadOffsetsT<NT> full = rs.full;
+    const LoadOffsetsT<NT, KCOL> full = rs.full;
     const int d0 = rs.d0;
     const int (&first)[NF + 1] = rs.first;
-    const LaneOffsets lo = lane_offsets(rs.tid);
+    const LaneOffsets lo = lane_offsets<KCOL>(rs.tid);
     // block 0 has landed when at most the NF younger blocks are in flight; loads of the caller
     // that are younger still (the query fragments) only make this wait longer
     f32x16 s_b[RB], s_c[RB];
     if (first[NF - 1] != 0) wait_blocks<NF>(); else wait_blocks<0>();
     ring_barrier();
-    scores<RB>(lds, lo, qf, s_b);
+    scores<RB, KCOL>(lds, lo, qf, s_b);
 
     // the plan of body 0, as the pieces would leave it
     plan.d_cur = d0;
@@ -747,13 +770,13 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT>& rs, c
 // The block loop of a wavefront NONE of whose rows is a query row (a decode step fills 4 of a
 // workgroup's 128 rows: one wavefront computes, the others only fetch).  Same control flow, same
 // loads, waits and barriers as run_blocks, no matrix or vector work and no LDS reads.
-template <int RB, bool NT>
-__device__ __forceinline__ void run_blocks_idle(RingStart<Ring<RB>::slots, NT>& rs, char* lds) {
+template <int RB, bool NT, bool KCOL>
+__device__ __forceinline__ void run_blocks_idle(RingStart<Ring<RB>::slots, NT, KCOL>& rs, char* lds) {
     constexpr int RING = Ring<RB>::slots;
     constexpr int NF = RING - 3;
     if (rs.d0 == 0) return;
     RingPlan<RING>& plan = rs.plan;
-    const LoadOffsetsT<NT> full = rs.full;
+    const LoadOffsetsT<NT, KCOL> full = rs.full;
     if (rs.first[NF - 1] != 0) wait_blocks<NF>(); else wait_blocks<0>();
     ring_barrier();
     plan.d_cur = rs.d0;
@@ -881,7 +904,9 @@ __global__ __launch_bounds__(NT) void flash_prefill_kernel(const QueryArgs a, in
                       (const char*)kv.k_self + head_b, (const char*)kv.v_self + head_b, wg_tok_hi + causal_off + 1, stride_b);
         vis_lo = tok_lo + causal_off;
     }
-    RingStart<Ring<RB>::slots, NTL> rs;
+    // the wide tile reads K from the column-major form (measured: wide prefill 0.524 -> 0.513 ms; the narrow
+    // tile, bound by its LDS and load traffic rather than by instruction issue, loses 1 % with it)
+    RingStart<Ring<RB>::slots, NTL, RB == 2 && !NTL> rs;
     start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(vis_lo), tid);
 
     // Q fragments (B operand: row = lane & 31, dims 16*ks + 8*hi .. +7)
