@@ -90,6 +90,7 @@ template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 template <bool NT, bool KCOL>
 struct LoadOffsetsT {
     uint32_t k[2], v[2];                                  // byte offsets of this lane's pieces from a block's row 0
+    int wave_dst;                                         // where in a slot's K (and V) part this wavefront's loads land; wavefront-uniform
     static constexpr bool nt = NT;                        // non-temporal loads
     static constexpr bool kcol = KCOL;                    // column-major K in LDS
     static_assert(!(NT && KCOL), "the column-major form gathers 64-byte pieces: not for streams bound by HBM");
@@ -111,6 +112,7 @@ __device__ __forceinline__ LoadOffsetsT<NT, KCOL> load_offsets(long stride_b, in
     const int lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, rl = lane >> 4;
     LoadOffsetsT<NT, KCOL> o;
+    o.wave_dst = __builtin_amdgcn_readfirstlane(wave) * (8 * ROWB);   // (kept in a scalar register over the block loop)
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = 8 * wave + 4 * i + rl;
@@ -150,8 +152,7 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t voff, const cha
 // row-major form; in the column-major form the same 1 KB of the slot holds what load_offsets says.
 template <class LO>
 __device__ __forceinline__ void issue_block_load(int i, const char* bk, const char* bv, char* slot, const LO& o) {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const char* dst = slot + (8 * wave + 4 * (i >> 1)) * ROWB;
+    const char* dst = slot + o.wave_dst + 4 * (i >> 1) * ROWB;
     if ((i & 1) == 0) dma16<LO::nt>(bk, o.k[i >> 1], dst);
     else dma16<LO::nt>(bv, o.v[i >> 1], dst + KVB);
 }
