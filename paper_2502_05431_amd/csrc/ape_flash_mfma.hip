@@ -318,6 +318,10 @@ __device__ __forceinline__ void softmax_slice(const f32x16 (&s)[RB], int rb, int
     const int r = 2 * k;
     const float e0 = __builtin_amdgcn_exp2f(fmaf(s[rb][r], sc2, -m));
     const float e1 = __builtin_amdgcn_exp2f(fmaf(s[rb][r + 1], sc2, -m));
+    // (The additions also keep the conversion below, which the compiler does not look into, one
+    // instruction away from the exponentials: a vector instruction that reads a transcendental's result
+    // in the very next issue slot gets a stale value.  Starting the sums by assignment in slice 0 saved
+    // two instructions per row block and produced exactly that.)
     psum[rb][0] += e0;
     psum[rb][1] += e1;
     uint32_t pk;
@@ -366,6 +370,28 @@ __device__ __forceinline__ bf16x8 read_k_frag(const char* slot, const LaneOffset
 __device__ __forceinline__ bf16x8 read_v_frag(const char* slot, const LaneOffsets& lo, int f) {
     const bf16x4 lo4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2));
     const bf16x4 hi4 = lds_read_tr(slot + lo.v[f & 3] + 4096 * (f >> 2) + 2048);
+    return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+// The narrow tile keeps the lane's four V^T addresses (slot + lane offset, one per dim block) from body
+// to body: a block's fragments are read in two bodies (tokens 0..15 while it is block j, tokens 16..31
+// while it is block j-1), and one addition per dim block moves an address on to the next block's slot
+// -- four additions per body instead of eight.  (CARRY false, the wide tile: the same change made the
+// compiler shuffle a hundred values per body through the accumulation registers; it adds slot and
+// lane offset at every read and leaves `va` alone.)
+struct VAddr { const char* a[4]; };
+template <bool CARRY>
+__device__ __forceinline__ bf16x8 read_v_pv(const VAddr& va, const char* slot_pv, const LaneOffsets& lo, int f) {
+    if constexpr (!CARRY) return read_v_frag(slot_pv, lo, f);
+    const bf16x4 lo4 = lds_read_tr(va.a[f & 3] + 4096 * (f >> 2));
+    const bf16x4 hi4 = lds_read_tr(va.a[f & 3] + 4096 * (f >> 2) + 2048);
+    return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+template <bool CARRY>
+__device__ __forceinline__ bf16x8 read_v_cur(VAddr& va, const char* slot_cur, const char* slot_pv, const LaneOffsets& lo, int f) {
+    if constexpr (!CARRY) return read_v_frag(slot_cur, lo, f);
+    va.a[f] += slot_cur - slot_pv;                                   // (f < 4: the dim block)
+    const bf16x4 lo4 = lds_read_tr(va.a[f]);
+    const bf16x4 hi4 = lds_read_tr(va.a[f] + 2048);
     return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
@@ -420,7 +446,7 @@ __device__ __forceinline__ float vmov(float x) {
 template <int RB, int RING, bool FAST, class LO>
 __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                               const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
-                                              f32x16 (&s_b)[RB], u32x4 (&p)[RB][2], bf16x8 (&vf)[8],
+                                              f32x16 (&s_b)[RB], u32x4 (&p)[RB][2], bf16x8 (&vf)[8], VAddr& va,
                                               RingPlan<RING>& plan, const int (&lim)[RB]) {
     constexpr int NS = 8 * RB;                                       // MFMAs per half
     const int d_cur = plan.d_cur, d_nxt = FAST ? BLK : plan.d_nxt;
@@ -441,8 +467,8 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
                                                                   st.o[rb][f & 3], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (n < 2) {
-            vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
-            vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+            vf[4 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + 2 * n);
+            vf[5 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 5 + 2 * n);
         }
         if (RB == 2) {                                               // K fragments: slices 2, 3, 4
             if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
@@ -487,7 +513,7 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
         s_b[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_b[rb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         softmax_slice<RB>(s_a, n / 8, n % 8, sc2, st.m[n / 8], psum, p);
-        if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);             // for the next body's PV
+        if (n < 4) vf[n] = read_v_cur<RB == 1>(va, slot_cur, slot_pv, lo, n);   // for the next body's PV
         __builtin_amdgcn_sched_barrier(0);
     }
     // ---- did every probability stay in range?  (kUnset rows that saw a key did not)
@@ -512,7 +538,7 @@ template <int RB, int RING, class LO>
 __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                                  const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
                                                  const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB], u32x4 (&p)[RB][2],
-                                                 bf16x8 (&vf)[8], RingPlan<RING>& plan) {
+                                                 bf16x8 (&vf)[8], VAddr& va, RingPlan<RING>& plan) {
     constexpr int NS = 8 * RB;
     const char* slot_pv = lds + pv_off;
     const char* slot_cur = lds + plan.o_cur;
@@ -529,13 +555,14 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
                                                                   st.o[rb][f & 3], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (n < 2) {
-            vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
-            vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+            vf[4 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + 2 * n);
+            vf[5 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 5 + 2 * n);
         }
         if (RB == 2) {
-            if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
-            if (n == 3) { kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); kf[4] = read_k_frag<LO::kcol>(slot_nxt, lo, 4); kf[5] = read_k_frag<LO::kcol>(slot_nxt, lo, 5); }
-            if (n == 4) { kf[6] = read_k_frag<LO::kcol>(slot_nxt, lo, 6); kf[7] = read_k_frag<LO::kcol>(slot_nxt, lo, 7); }
+            // (the fragments of k-slabs 4..7 are read in the K Q^T half, when the scores of block j are
+            // mostly consumed: sixteen registers fewer at the body's fullest point)
+            if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); }
+            if (n == 3) { kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); }
         } else if (n == 4 || n == 5) {                               // (after the wait for the V^T fragments)
 #pragma unroll
             for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
@@ -558,7 +585,8 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
         __builtin_amdgcn_sched_barrier(0);
         if (RB == 2 && n < 8) softmax_slice<RB>(s_in, 1, n, sc2, st.m[1], psum, p);
         if (RB == 1 && n < 4) softmax_slice<RB>(s_in, 0, n + 4, sc2, st.m[0], psum, p);
-        if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);             // for the next body's PV
+        if (n < 4) vf[n] = read_v_cur<RB == 1>(va, slot_cur, slot_pv, lo, n);   // for the next body's PV
+        if (RB == 2 && n < 4) kf[4 + n] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 + n);   // first used by MFMA 8
         __builtin_amdgcn_sched_barrier(0);
     }
     bool bad = false;
@@ -583,7 +611,7 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
                                                    const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
                                                    const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB],
                                                    const u32x4 (&p_in)[RB][2], u32x4 (&p_out)[RB][2],
-                                                   bf16x8 (&vf)[8], RingPlan<RING>& plan) {
+                                                   bf16x8 (&vf)[8], VAddr& va, RingPlan<RING>& plan) {
     constexpr int NS = 8 * RB;
     const char* slot_pv = lds + pv_off;
     const char* slot_cur = lds + plan.o_cur;
@@ -607,8 +635,8 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
                                                                   st.o[rb][f & 3], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (n < 2) {
-            vf[4 + 2 * n] = read_v_frag(slot_pv, lo, 4 + 2 * n);
-            vf[5 + 2 * n] = read_v_frag(slot_pv, lo, 5 + 2 * n);
+            vf[4 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + 2 * n);
+            vf[5 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 5 + 2 * n);
         }
         if (RB == 2) {
             if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
@@ -634,7 +662,7 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
         s_out[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_out[rb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         half_slice(NS + n);
-        if (n < 4) vf[n] = read_v_frag(slot_cur, lo, n);             // for the next body's PV
+        if (n < 4) vf[n] = read_v_cur<RB == 1>(va, slot_cur, slot_pv, lo, n);   // for the next body's PV
         __builtin_amdgcn_sched_barrier(0);
     }
     bool bad = false;
@@ -714,6 +742,9 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>&
     bf16x8 vf[8];
 #pragma unroll
     for (int f = 0; f < 4; ++f) vf[f] = read_v_frag(lds, lo, f);
+    VAddr va;                                                        // (body 0: block -1 is block 0's slot, see below)
+#pragma unroll
+    for (int db = 0; db < 4; ++db) va.a[db] = lds + lo.v[db];
     int pv_off = 0;
     for (;;) {
         // ---- fast stretch: bodies that need no descriptor, no mask and no table look-up
@@ -726,21 +757,21 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>&
             // probability registers does not fit next to the 128 accumulators (the compiler parks 16
             // more values in the accumulation registers and copies them in and out, 18 instructions per
             // body), which eats the gain: it keeps the paired body.
-            if constexpr (RB == 1) pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, p2, vf, plan);
-            else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, vf, plan);
+            if constexpr (RB == 1) pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, p2, vf, va, plan);
+            else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, vf, va, plan);
             pv_off = next_pv_off;
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             next_pv_off = plan.o_cur;
-            if constexpr (RB == 1) pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p2, p, vf, plan);
-            else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, plan);
+            if constexpr (RB == 1) pipeline_body_even<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p2, p, vf, va, plan);
+            else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, va, plan);
             pv_off = next_pv_off;
         }
         if (n_fast & 1) {
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             const int next_pv_off = plan.o_cur;
-            pipeline_body<RB, RING, true>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, plan, lim);
+            pipeline_body<RB, RING, true>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, va, plan, lim);
             pv_off = next_pv_off;
         }
         if (n_fast > 0) plan.finish_fast(n_fast);
@@ -753,14 +784,14 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>&
             ring_barrier();
         }
         const int next_pv_off = plan.o_cur;
-        pipeline_body<RB, RING, false>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, plan, lim);
+        pipeline_body<RB, RING, false>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, va, plan, lim);
         pv_off = next_pv_off;
         if (d_nxt == 0) break;
     }
     // the last block's PV product
 #pragma unroll
     for (int f = 0; f < 8; ++f) {
-        if (f >= 4) vf[f] = read_v_frag(lds + pv_off, lo, f);
+        if (f >= 4) vf[f] = read_v_pv<RB == 1>(va, lds + pv_off, lo, f);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
             st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
