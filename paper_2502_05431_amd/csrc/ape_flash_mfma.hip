@@ -148,6 +148,19 @@ __device__ __forceinline__ void dma16(const char* base, uint32_t voff, const cha
                      :: "v"(voff), "s"(base), "s"(m0v) : "m0");
 }
 
+// The same load inside a chain of loads: M0 is taken from `m0v`, and the instruction that must stand
+// between the write of M0 and the load (a wait state) is the addition that moves `m0v` on to the next
+// load's LDS address -- no s_nop, and no separate address arithmetic per load.
+template <bool NT, int DELTA>
+__device__ __forceinline__ void dma16_chain(const char* base, uint32_t voff, uint32_t& m0v) {
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %0\n\ts_add_i32 %0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                     : "+s"(m0v) : "v"(voff), "s"(base), "n"(DELTA) : "m0", "scc");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_add_i32 %0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
+                     : "+s"(m0v) : "v"(voff), "s"(base), "n"(DELTA) : "m0", "scc");
+}
+
 // Load i (0..3) of a block: wavefront w fills rows 8w + 4(i/2) .. +3 of V (i odd), and of K (i even) in the
 // row-major form; in the column-major form the same 1 KB of the slot holds what load_offsets says.
 template <class LO>
@@ -155,6 +168,16 @@ __device__ __forceinline__ void issue_block_load(int i, const char* bk, const ch
     const char* dst = slot + o.wave_dst + 4 * (i >> 1) * ROWB;
     if ((i & 1) == 0) dma16<LO::nt>(bk, o.k[i >> 1], dst);
     else dma16<LO::nt>(bv, o.v[i >> 1], dst + KVB);
+}
+// Loads 0..3 of a block issued in this order, one per call, with `m0v` carried between the calls
+// (set by load 0): K rows +0, V rows +0 (KVB further on), K rows +4, V rows +4.
+template <class LO>
+__device__ __forceinline__ void issue_block_load_chain(int i, const char* bk, const char* bv, char* slot, const LO& o, uint32_t& m0v) {
+    if (i == 0) m0v = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)(slot + o.wave_dst);
+    if (i == 0) dma16_chain<LO::nt, KVB>(bk, o.k[0], m0v);
+    else if (i == 1) dma16_chain<LO::nt, 4 * ROWB - KVB>(bv, o.v[0], m0v);
+    else if (i == 2) dma16_chain<LO::nt, KVB>(bk, o.k[1], m0v);
+    else dma16_chain<LO::nt, 0>(bv, o.v[1], m0v);
 }
 
 // `full` holds the offsets of a full block (computed once); a partial block recomputes them with
@@ -460,6 +483,7 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
     // use), the new block's loads and the ring bookkeeping; then s_a <- s_b.
     f32x16 s_a[RB];
     bf16x8 kf[8];
+    uint32_t m0v = 0;                                             // LDS address of the next load of the new block (see issue_block_load_chain)
 #pragma unroll
     for (int n = 0; n < NS; ++n) {
         const int f = n / RB, rb = n % RB;                           // fragment f = sl*4 + db
@@ -481,7 +505,7 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
             }
         }
         if (FAST) {
-            if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+            if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, lds + plan.o_new, full, m0v);
             else
             if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
         } else if (n == 0) {
@@ -544,6 +568,7 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
     const char* slot_cur = lds + plan.o_cur;
     const char* slot_nxt = lds + plan.o_nxt;
     bf16x8 kf[8];
+    uint32_t m0v = 0;                                             // LDS address of the next load of the new block (see issue_block_load_chain)
     float psum[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) psum[rb][0] = psum[rb][1] = 0.f;
@@ -567,7 +592,7 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
 #pragma unroll
             for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
         }
-        if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+        if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, lds + plan.o_new, full, m0v);
         else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
         if (RB == 2 && n >= 8) softmax_slice<RB>(s_in, 0, n - 8, sc2, st.m[0], psum, p);
         if (RB == 1 && n >= 4) softmax_slice<RB>(s_in, 0, n - 4, sc2, st.m[0], psum, p);   // slab 0, last read by MFMA 3
@@ -617,6 +642,7 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
     const char* slot_cur = lds + plan.o_cur;
     const char* slot_nxt = lds + plan.o_nxt;
     bf16x8 kf[8];
+    uint32_t m0v = 0;                                             // LDS address of the next load of the new block (see issue_block_load_chain)
     float psum[RB][2];
     float e[2];
 #pragma unroll
@@ -646,7 +672,7 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
 #pragma unroll
             for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
         }
-        if (n < LOADS_PER_BLOCK) issue_block_load(n, plan.new_k, plan.new_v, lds + plan.o_new, full);
+        if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, lds + plan.o_new, full, m0v);
         else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
         half_slice(n);
         __builtin_amdgcn_sched_barrier(0);
