@@ -558,15 +558,19 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
 // blocks the softmax of row block 0 runs in the PV half (the PV MFMAs take row block 0 first,
 // which frees its probability registers for the second eight slices), that of row block 1 in the
 // K Q^T half; with one row block its first four slices run in the last four of the PV half.
-template <int RB, int RING, class LO>
+template <int RB, int RING, class LO, int PH = -1>
 __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                                  const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
                                                  const f32x16 (&s_in)[RB], f32x16 (&s_out)[RB], u32x4 (&p)[RB][2],
                                                  bf16x8 (&vf)[8], VAddr& va, RingPlan<RING>& plan) {
     constexpr int NS = 8 * RB;
-    const char* slot_pv = lds + pv_off;
-    const char* slot_cur = lds + plan.o_cur;
-    const char* slot_nxt = lds + plan.o_nxt;
+    // PH >= 0: block j sits in ring slot PH, known at compile time (the slot offsets then fold into
+    // the LDS instructions' offset fields); the ring offsets of the plan stay where they are (see run_blocks)
+    constexpr bool STATIC = PH >= 0;
+    const char* slot_pv = STATIC ? lds + ((PH + RING - 1) % RING) * SLOTB : lds + pv_off;
+    const char* slot_cur = STATIC ? lds + (PH % RING) * SLOTB : lds + plan.o_cur;
+    const char* slot_nxt = STATIC ? lds + ((PH + 1) % RING) * SLOTB : lds + plan.o_nxt;
+    char* slot_new = STATIC ? lds + ((PH + RING - 2) % RING) * SLOTB : lds + plan.o_new;
     bf16x8 kf[8];
     uint32_t m0v = 0;                                             // LDS address of the next load of the new block (see issue_block_load_chain)
     float psum[RB][2];
@@ -592,8 +596,8 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
 #pragma unroll
             for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
         }
-        if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, lds + plan.o_new, full, m0v);
-        else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
+        if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, slot_new, full, m0v);
+        else if (n < LOADS_PER_BLOCK + (STATIC ? 2 : 3)) plan.fast_piece(n - LOADS_PER_BLOCK);   // (piece 2 turns the ring offsets)
         if (RB == 2 && n >= 8) softmax_slice<RB>(s_in, 0, n - 8, sc2, st.m[0], psum, p);
         if (RB == 1 && n >= 4) softmax_slice<RB>(s_in, 0, n - 4, sc2, st.m[0], psum, p);   // slab 0, last read by MFMA 3
         __builtin_amdgcn_sched_barrier(0);
@@ -734,11 +738,32 @@ __device__ __forceinline__ void start_stream(RingStart<RING, NT, KCOL>& rs, cons
 // barriers and the same instruction stream; causal blocks a wavefront's rows do not see are
 // simply masked.  (vis_lo, given to start_stream: the smallest causal limit among this
 // wavefront's rows; blocks up to it need no causal mask.)
+// RING fast bodies, pair by pair, with block j of the first one in ring slot 0: every slot offset is a
+// compile-time constant, so slot and lane offset of an LDS read need no addition (the slot goes into
+// the instruction's offset field) and the loads' LDS addresses are constants plus the wavefront's share.
+// The plan's ring offsets are not turned (after RING bodies they would be back where they are), and
+// neither is the caller's pv_off.
+template <int RB, int RING, int PH, class LO>
+__device__ __forceinline__ void static_bodies(char* lds, const LaneOffsets& lo, const LO& full, const bf16x8 (&qf)[RB][8],
+                                              WaveState<RB>& st, float sc2, f32x16 (&s_b)[RB], f32x16 (&s_c)[RB],
+                                              u32x4 (&p)[RB][2], bf16x8 (&vf)[8], VAddr& va, RingPlan<RING>& plan) {
+    constexpr int NF = RING - 3;
+    static_assert(RING % 2 == 0, "pairs of bodies must tile the ring");
+    if constexpr (PH < RING) {
+        wait_blocks<NF - 1>(); ring_barrier();
+        pipeline_body_pp<RB, RING, LO, PH>(lds, 0, lo, full, qf, st, sc2, s_b, s_c, p, vf, va, plan);
+        wait_blocks<NF - 1>(); ring_barrier();
+        pipeline_body_pp<RB, RING, LO, PH + 1>(lds, 0, lo, full, qf, st, sc2, s_c, s_b, p, vf, va, plan);
+        static_bodies<RB, RING, PH + 2>(lds, lo, full, qf, st, sc2, s_b, s_c, p, vf, va, plan);
+    }
+}
+
 template <int RB, bool NT, bool KCOL>
 __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>& rs, char* lds, const bf16x8 (&qf)[RB][8],
                                            WaveState<RB>& st, float sc2, const int (&lim)[RB]) {
     constexpr int RING = Ring<RB>::slots;
     constexpr int NF = RING - 3;
+    constexpr bool STATIC_RING = RB == 2 && KCOL;        // the wide prefill tile (the wide encode tile's register assignment does not survive it)
     if (rs.d0 == 0) return;
     RingPlan<RING>& plan = rs.plan;
     const LoadOffsetsT<NT, KCOL> full = rs.full;
@@ -775,7 +800,38 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>&
     for (;;) {
         // ---- fast stretch: bodies that need no descriptor, no mask and no table look-up
         const int n_fast = plan.fast_bodies();
-        for (int i = 0; i + 1 < n_fast; i += 2) {                     // in pairs: the scores ping-pong between s_b and s_c
+        int n_left = n_fast;
+        auto single = [&]() {
+            wait_blocks<NF >= 2 ? NF - 1 : 0>();
+            ring_barrier();
+            const int next_pv_off = plan.o_cur;
+            pipeline_body<RB, RING, true>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, va, plan, lim);
+            pv_off = next_pv_off;
+        };
+        if constexpr (STATIC_RING) {
+            // Long stretches (a query prefill's context split): groups of RING bodies with the ring slots
+            // as compile-time constants (209-222 instead of 218-222 instructions per body; config-3 prefill
+            // 0.503 -> 0.493 ms).  Bodies with run-time offsets first bring the ring round to slot 0: one
+            // single body if that takes an odd number, then pairs.
+            const FastSplit fs = split_fast<RING>(n_fast, plan.o_cur / SLOTB, pv_off == plan.o_cur);
+            if (fs.supers > 0) {
+                if (fs.pre & 1) single();
+                for (int i = 0; i + 1 < fs.pre; i += 2) {
+                    wait_blocks<NF - 1>(); ring_barrier();
+                    int next_pv_off = plan.o_cur;
+                    pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_b, s_c, p, vf, va, plan);
+                    pv_off = next_pv_off;
+                    wait_blocks<NF - 1>(); ring_barrier();
+                    next_pv_off = plan.o_cur;
+                    pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, va, plan);
+                    pv_off = next_pv_off;
+                }
+                for (int g = 0; g < fs.supers; ++g)
+                    static_bodies<RB, RING, 0>(lds, lo, full, qf, st, sc2, s_b, s_c, p, vf, va, plan);
+                n_left -= fs.pre + fs.supers * RING;
+            }
+        }
+        for (int i = 0; i + 1 < n_left; i += 2) {                     // in pairs: the scores ping-pong between s_b and s_c
             wait_blocks<NF >= 2 ? NF - 1 : 0>();
             ring_barrier();
             int next_pv_off = plan.o_cur;
@@ -793,13 +849,7 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>&
             else pipeline_body_pp<RB, RING>(lds, pv_off, lo, full, qf, st, sc2, s_c, s_b, p, vf, va, plan);
             pv_off = next_pv_off;
         }
-        if (n_fast & 1) {
-            wait_blocks<NF >= 2 ? NF - 1 : 0>();
-            ring_barrier();
-            const int next_pv_off = plan.o_cur;
-            pipeline_body<RB, RING, true>(lds, pv_off, lo, full, qf, st, sc2, s_b, p, vf, va, plan, lim);
-            pv_off = next_pv_off;
-        }
+        if (n_left & 1) single();
         if (n_fast > 0) plan.finish_fast(n_fast);
         // ---- generic body
         const int d_nxt = plan.d_nxt;

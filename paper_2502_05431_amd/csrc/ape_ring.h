@@ -198,4 +198,20 @@ struct RingPlan {
     }
 };
 
+// How a fast stretch of n bodies is run when block j of its first body sits in ring slot `phase`:
+// `pre` bodies with run-time slot offsets bring the ring round to slot 0, then `supers` groups of RING
+// bodies run with compile-time slots, the rest again with run-time offsets.  For long stretches only
+// (the groups are a second copy of the loop body, RING times over).
+struct FastSplit { int pre, supers; };
+// `first`: the stretch starts with the stream's very first body, whose "block j-1" is block 0's own
+// slot and not the slot before it in the ring: that body must run with run-time offsets.
+template <int RING>
+APE_RING_FN FastSplit split_fast(int n, int phase, bool first) {
+    FastSplit f{0, 0};
+    if (n < 4 * RING) return f;
+    f.pre = phase == 0 && !first ? 0 : RING - phase;
+    f.supers = (n - f.pre) / RING;
+    return f;
+}
+
 }  // namespace ape

@@ -37,7 +37,8 @@ struct Sim {
     std::vector<int> ref_desc;                                  // descriptor of every block, from a plain walk
     std::vector<std::pair<const char*, const char*>> valid;     // valid K row ranges
     std::vector<int> slot_block;                                // which block each ring slot holds
-    int next_to_issue = 0, barriers = 0, bodies = 0, fast = 0;
+    int next_to_issue = 0, barriers = 0, bodies = 0, fast = 0, static_bodies = 0;
+    bool static_ring = false;                                   // run fast stretches as the wide prefill tile does
     std::string err;
     void fail(const std::string& m) { if (err.empty()) err = m; }
     void issue(const char* bk, int n_valid, long stride_b, int slot_off, int busy0, int busy1, int busy2) {
@@ -95,15 +96,34 @@ void run(Sim& sim, const Stream& ld0, int vis_lo) {
     };
     for (int guard = 0; guard < 1000000 && sim.err.empty(); ++guard) {
         const int n_fast = plan.fast_bodies();
+        // the kernels' split of a stretch (wide prefill tile): bodies with run-time slots until the ring is
+        // back at slot 0, then groups of RING bodies whose slots are compile-time constants and which
+        // leave the plan's ring offsets and pv_off alone
+        const FastSplit fs = sim.static_ring ? split_fast<RING>(n_fast, plan.o_cur / SLOTB, pv_off == plan.o_cur) : FastSplit{0, 0};
         for (int i = 0; i < n_fast && sim.err.empty(); ++i) {             // fast bodies
             if (j + 1 >= n_blocks) { sim.fail("fast body without a next block"); break; }
             sim.barriers++;
-            const int next_pv_off = plan.o_cur;
-            check_slots(true);
-            if (desc_n(ref[j]) != BLK || masked(ref[j])) sim.fail("fast body on a block that needs a mask, body " + std::to_string(j));
-            sim.issue(plan.new_k, BLK, plan.ld.stride_b, plan.o_new, plan.o_cur / SLOTB, plan.o_nxt / SLOTB, j > 0 ? pv_off / SLOTB : -1);
-            plan.fast_piece(0); plan.fast_piece(1); plan.fast_piece(2);
-            pv_off = next_pv_off; ++j; sim.bodies++; sim.fast++;
+            const bool is_static = fs.supers > 0 && i >= fs.pre && i < fs.pre + fs.supers * RING;
+            if (!is_static) {
+                const int next_pv_off = plan.o_cur;
+                check_slots(true);
+                if (desc_n(ref[j]) != BLK || masked(ref[j])) sim.fail("fast body on a block that needs a mask, body " + std::to_string(j));
+                sim.issue(plan.new_k, BLK, plan.ld.stride_b, plan.o_new, plan.o_cur / SLOTB, plan.o_nxt / SLOTB, j > 0 ? pv_off / SLOTB : -1);
+                plan.fast_piece(0); plan.fast_piece(1); plan.fast_piece(2);
+                pv_off = next_pv_off;
+            } else {
+                const int ph = (i - fs.pre) % RING;                        // the body's compile-time phase
+                const int s_cur = ph, s_nxt = (ph + 1) % RING, s_pv = (ph + RING - 1) % RING, s_new = (ph + RING - 2) % RING;
+                if (ph == 0 && (plan.o_cur != 0 || pv_off != (RING - 1) * SLOTB)) sim.fail("a group of static bodies does not start at slot 0, body " + std::to_string(j));
+                if (sim.slot_block[s_cur] != j) sim.fail("static body: block j not in its slot, body " + std::to_string(j));
+                if (sim.slot_block[s_nxt] != j + 1) sim.fail("static body: block j+1 not in its slot, body " + std::to_string(j));
+                if (sim.slot_block[s_pv] != j - 1) sim.fail("static body: block j-1 not in its slot, body " + std::to_string(j));
+                if (desc_n(ref[j]) != BLK || masked(ref[j])) sim.fail("fast body on a block that needs a mask, body " + std::to_string(j));
+                sim.issue(plan.new_k, BLK, plan.ld.stride_b, s_new * SLOTB, s_cur, s_nxt, s_pv);
+                plan.fast_piece(0); plan.fast_piece(1);                    // (piece 2, the ring's turn, is left out)
+                sim.static_bodies++;
+            }
+            ++j; sim.bodies++; sim.fast++;
         }
         if (n_fast > 0) plan.finish_fast(n_fast);
         if (!sim.err.empty()) break;
@@ -137,15 +157,17 @@ static void walk(Stream ld, Sim& sim) {
     }
 }
 
-struct Tally { int cases = 0, failed = 0, fast = 0, bodies = 0; };
+struct Tally { int cases = 0, failed = 0, fast = 0, bodies = 0, static_bodies = 0; };
 
 template <typename MakeStream>
 static void run_case(Tally& t, const char* what, MakeStream make, const std::vector<std::pair<const char*, const char*>>& valid,
                      const std::vector<int>& vis_los, int expect_rows) {
-    for (int ring : {5, 6, 8}) {
+    // (ring 6 twice: the second time with fast stretches split as the wide prefill tile splits them)
+    for (int variant = 0; variant < 4; ++variant) {
+        const int ring = variant == 0 ? 5 : variant == 3 ? 8 : 6;
         int barriers = -1;
         for (int vis_lo : vis_los) {
-            Sim sim; sim.valid = valid;
+            Sim sim; sim.valid = valid; sim.static_ring = variant == 2;
             Stream ld = make();
             walk(ld, sim);
             int rows = 0; for (int d : sim.ref_desc) rows += desc_n(d);
@@ -153,7 +175,7 @@ static void run_case(Tally& t, const char* what, MakeStream make, const std::vec
             if (ring == 5) run<5>(sim, ld, vis_lo); else if (ring == 6) run<6>(sim, ld, vis_lo); else run<8>(sim, ld, vis_lo);
             if (sim.err.empty() && barriers >= 0 && sim.barriers != barriers) sim.fail("wavefronts with different causal limits execute different numbers of barriers");
             barriers = sim.barriers;
-            ++t.cases; t.fast += sim.fast; t.bodies += sim.bodies;
+            ++t.cases; t.fast += sim.fast; t.bodies += sim.bodies; t.static_bodies += sim.static_bodies;
             if (!sim.err.empty() && t.failed++ < 20) std::printf("%s ring=%d vis_lo=%d: %s\n", what, ring, vis_lo, sim.err.c_str());
         }
     }
@@ -167,12 +189,12 @@ int main() {
     char what[256];
     // sequence streams (encode tiles, the prefix+self split): a plain segment, then a causal one
     for (int np : {0, 5, 7, 31, 32, 33, 40, 64, 100})
-        for (int nc = 1; nc <= 700; nc += (nc < 70 ? 1 : 29)) {
+        for (int nc = 1; nc <= 4200; nc += (nc < 70 ? 1 : nc < 700 ? 29 : 1171)) {
             const char* kp = base; const char* kc = base + (long)(np + 8) * stride_b + (1 << 19);
             std::vector<std::pair<const char*, const char*>> valid = {{kp, kp + (long)np * stride_b}, {kc, kc + (long)nc * stride_b}};
             std::snprintf(what, sizeof what, "seq prefix=%d causal=%d", np, nc);
             run_case(t, what, [&] { Stream ld; ld.init_seq(kp, kp + (1 << 25), np, kc, kc + (1 << 25), nc, stride_b); return ld; }, valid,
-                     {0, 8, 24, 31, 32, 48, 63, 64, 100, 200, 399, 699, 5000}, np + nc);
+                     {0, 8, 24, 31, 32, 48, 63, 64, 100, 200, 399, 699, 2500, 5000}, np + nc);
         }
     // context streams: ranges of the pooled contexts through a chunk table
     const std::vector<std::vector<int>> tables = {{64, 64}, {100, 1, 65, 300, 31}, {2048, 2048, 2048, 2048}, {257, 255}, {512, 512, 512}, {130},
@@ -212,6 +234,6 @@ int main() {
                              {0}, t1 - t0);
                 }
     }
-    std::printf("%d streams, %d failed; %d of %d bodies fast\n", t.cases, t.failed, t.fast, t.bodies);
+    std::printf("%d streams, %d failed; %d of %d bodies fast; %d in groups with compile-time slots\n", t.cases, t.failed, t.fast, t.bodies, t.static_bodies);
     return t.failed != 0;
 }

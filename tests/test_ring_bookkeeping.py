@@ -1,6 +1,6 @@
 """Host logic of the flash kernels: the scalar bookkeeping of the K/V block stream and of the ring
 of LDS slots (csrc/ape_ring.h) compiles for the host, and tests/ring_sim.cpp drives it through
-~22 000 streams (prefix + causal segments of every length up to several tiles, ragged chunk tables,
+~30 000 streams (prefix + causal segments of every length up to several tiles, ragged chunk tables,
 splits that start and end inside chunks, every wavefront's causal limit) in place of the MFMA work.
 No GPU is needed."""
 import os
@@ -26,3 +26,6 @@ def test_ring_bookkeeping_simulation(tmp_path):
     # the fast path is exercised, not only the generic one
     n_fast = int(last.split(";")[1].split()[0])
     assert n_fast > 1000, last
+    # ... and so are the groups of bodies whose ring slots are compile-time constants (wide prefill tile)
+    n_static = int(last.split(";")[2].split()[0])
+    assert n_static > 1000 and n_static % 6 == 0, last
