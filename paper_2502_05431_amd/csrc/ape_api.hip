@@ -156,7 +156,13 @@ QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) 
     const long units = (long)batch * q_len * si.hq;
     const int bm = si.mfma ? flash_prefill_block_rows(rows, max_ctx) : 0;
     const int base = si.mfma ? batch * si.hkv * ceil_div(rows, bm) : (int)units;
-    QueryPlan p = plan_query(base, max_ctx, 256, si.mfma ? flash_prefill_target_workgroups(max_ctx) : 1024);
+    int target = si.mfma ? flash_prefill_target_workgroups(max_ctx) : 1024;
+    // Two workgroups per CU only pay when their streams stay long: with few query rows (few row tiles)
+    // the same target cuts the context into splits of a few hundred tokens, whose fixed cost per
+    // workgroup outweighs the second workgroup (64 rows over 16K: 0.049 ms with 32 splits of 512 tokens,
+    // 0.036 ms with 16 of 1024).
+    if (si.mfma && target > 256 && max_ctx / ceil_div(target, base) < 2048) target = 256;
+    QueryPlan p = plan_query(base, max_ctx, 256, target);
     p.block_rows = bm;
     return p;
 }

@@ -32,7 +32,7 @@ BASE_SEED = 20250205
 @dataclass(frozen=True)
 class WorkloadSpec:
     name: str
-    cfg: int                       # 1..5 (index into BASELINE.json "configs" + 1)
+    cfg: int                       # 1..5: which of the five benchmark configurations
     dtype: str                     # "f32" | "bf16"
     n_q_heads: int
     n_kv_heads: int
