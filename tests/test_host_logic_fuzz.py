@@ -195,3 +195,31 @@ def test_prefill_workspace_bound_over_a_sweep_of_context_lengths(hq, q_len, batc
                 assert need <= capped <= bound, (ctx, cap, need, capped, bound)
         worst = max(worst, need)
     assert worst > bound // 2                              # and the bound is not idle: some length comes within a factor of two
+
+
+def _decode_splits(sh, batch, ctx):
+    """Context splits per request that a decode step over contexts of `ctx` tokens uses, read off the
+    workspace it asks for (partial results of (splits + 1) groups per (request, head))."""
+    units = batch * sh.n_q_heads
+    for n in range(1, 66):
+        need = -(-units * (n + 1) * sh.head_dim * 4 // 256) * 256 + -(-units * (n + 1) * 4 // 256) * 256
+        if need == B.workspace_bytes(B.APE_OP_DECODE, sh, batch, 1, ctx):
+            return n
+    raise AssertionError("no split count explains the workspace size")
+
+
+@pytest.mark.parametrize("batch,ctx,splits", [
+    (32, 16384, 1),      # 32 x 8 KV heads = 256 long workgroups: one per CU
+    (16, 16384, 2), (8, 131072, 4), (1, 131072, 32), (2, 131072, 16), (64, 8192, 1), (24, 16384, 4), (48, 16384, 2),
+    (128, 4096, 1),      # 1024 = 4 x 256
+    (1, 2048, 8),        # a short context: never splits below 256 tokens
+    (17, 16384, 16),     # 136 x n is a multiple of 256 only at n = 32 (4352 workgroups: too many) -> many workgroups
+])
+def test_decode_split_plan_fills_the_cus_evenly(batch, ctx, splits):
+    """The decode plan takes the smallest number of context splits that makes requests x KV heads x
+    splits a multiple of 256 (the CUs), as long as the splits keep 256 tokens and the count 2048."""
+    sh = B.make_shape(32, 8, 128, B.APE_BF16)
+    n = _decode_splits(sh, batch, ctx)
+    assert n == splits, (batch, ctx, n)
+    if batch * 8 * n <= 2048 and ctx >= 256 * n and (batch * 8 * n) % 256 == 0:
+        assert all((batch * 8 * m) % 256 != 0 for m in range(1, n))
