@@ -1,5 +1,7 @@
 // Matrix-core flash attention for gfx950 (bf16, head_dim 128): query prefill over the cached
-// contexts (split over the keys) and the block-diagonal causal encoding of the contexts.
+// contexts (split over the keys), the decode step (the same kernel on a tile of which one wavefront has
+// query rows and the other three only fetch: it is bound by HBM) and the block-diagonal causal encoding
+// of the contexts.
 //
 // Math (arXiv 2502.05431): Section 2.3 softmax attention evaluated block by block as in
 // Appendix C.1 (each block: softmax-weighted values + LogSumExp); context blocks use scores
@@ -12,7 +14,8 @@
 //     share a KV head also share every K/V block staged in LDS;
 //   - keys/values stream in blocks of 32 tokens through a ring of LDS slots filled by direct
 //     global->LDS loads (16 bytes per lane, no staging registers), several blocks ahead of the
-//     compute; rows are 256 bytes and XOR-swizzled so that every LDS read is conflict-free;
+//     compute; rows are 256 bytes and XOR-swizzled so that every LDS read is conflict-free (the wide
+//     prefill tile keeps K column-major instead: one address register, k-slabs as immediates);
 //   - scores are computed TRANSPOSED, S^T = K Q^T: the accumulator layout then puts one query
 //     row in one lane (and its partner lane +32), so the softmax row reductions are in-lane,
 //     and the bf16 probabilities are already laid out as the B operand of O^T += V^T P^T;
@@ -21,8 +24,13 @@
 //     then K Q^T of block j+1 with the softmax of block j in the shadow of its MFMAs;
 //   - the softmax keeps a lazily updated reference instead of a running maximum, so its fast
 //     path is two exponentials, two adds and a conversion per pair of scores;
-//   - stretches of full, unmasked blocks of one segment run a branch-free body; segment ends,
-//     partial blocks and the causal diagonal take a generic body with the same arithmetic.
+//   - stretches of full, unmasked blocks of one segment run a branch-free body (in the wide prefill
+//     tile, long stretches in groups of bodies whose ring slots are compile-time constants); segment
+//     ends, partial blocks and the causal diagonal take a generic body with the same arithmetic;
+//   - what bounds the block loop is the instruction issue of the one wavefront per SIMD (wide tile:
+//     about 180 instructions next to every 32 MFMAs, 112 of them the softmax), so the code below
+//     counts instructions: addresses as immediates, values carried instead of recomputed, the wait
+//     state after a write of M0 filled with the next address step.
 // The file is compiled with the MFMA accumulators in the vector registers (VGPR form).
 #include "ape_internal.h"
 
@@ -85,7 +93,7 @@ template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 // Wavefront w fills rows 8w .. 8w+7 of K and of V: four instructions per block.
 // Rows past n_valid re-read the last valid row: finite data whose probabilities are zero.
 // NT: the loads carry the non-temporal hint (the block is read by this workgroup only and will not be
-// read again: a decode step, a query of a few rows).  Streams at 6.2 instead of 5.3 TB/s; K/V that
+// read again: a decode step, a query of a few rows).  Streams at 6.5 instead of 6.1 TB/s; K/V that
 // other workgroups re-read from L2 (the encode, a query of several row tiles) must not carry it.
 template <bool NT, bool KCOL>
 struct LoadOffsetsT {
