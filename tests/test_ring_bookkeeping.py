@@ -1,6 +1,6 @@
 """Host logic of the flash kernels: the scalar bookkeeping of the K/V block stream and of the ring
 of LDS slots (csrc/ape_ring.h) compiles for the host, and tests/ring_sim.cpp drives it through
-~30 000 streams (prefix + causal segments of every length up to several tiles, ragged chunk tables,
+~52 000 streams (prefix + causal segments of every length up to several tiles, ragged chunk tables,
 splits that start and end inside chunks, every wavefront's causal limit) in place of the MFMA work.
 No GPU is needed."""
 import os
