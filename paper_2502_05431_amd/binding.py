@@ -29,7 +29,7 @@ EXPORTS = ("ape_workspace_bytes", "ape_encode_chunks", "ape_attention_prefill", 
            "ape_attention_prefill_batch", "ape_attention_decode_static",
            "ape_tree_workspace_bytes", "ape_attention_tree", "ape_rope_write_cache",
            "ape_status_string", "ape_last_error", "ape_version")
-PROBE_EXPORTS = ("ape_probe_mfma", "ape_probe_hbm_read")
+PROBE_EXPORTS = ("ape_probe_mfma", "ape_probe_hbm_read", "ape_probe_valu_issue")
 LAYER_EXPORTS = ("ape_layer_workspace_bytes", "ape_layers_workspace_bytes", "ape_layer_encode", "ape_layers_encode")
 APE_TREE_MAX_NODES, APE_TREE_MAX_CONTEXTS, APE_TREE_MAX_DEPTH = 2048, 4096, 16
 APE_STATIC_SCRATCH_BYTES = 8 << 20
@@ -157,16 +157,27 @@ def load_probe() -> ctypes.CDLL:
         lib.ape_probe_mfma.restype = ctypes.c_int
         lib.ape_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_float, vp, ctypes.POINTER(ctypes.c_double)]
         lib.ape_probe_hbm_read.restype = ctypes.c_int
+        lib.ape_probe_valu_issue.argtypes = [ctypes.c_int, vp, ctypes.c_float, vp, ctypes.POINTER(ctypes.c_double)]
+        lib.ape_probe_valu_issue.restype = ctypes.c_int
         _probe_lib = lib
     return _probe_lib
 
 
-def probe_mfma(operands: torch.Tensor, with_softmax: bool, sink: torch.Tensor, warm_ms: float = 150.0, stream=None) -> float:
-    """``ape_probe_mfma``: TFLOP/s of back-to-back bf16 MFMAs on the given 64 KiB of operand data."""
-    assert operands.numel() * operands.element_size() >= 65536
+def probe_mfma(operands: torch.Tensor, level, sink: torch.Tensor, warm_ms: float = 150.0, stream=None) -> float:
+    """``ape_probe_mfma``: TFLOP/s of back-to-back bf16 MFMAs on the given 64 KiB of operand data; level 0..3
+    (False/True = 0/1) adds the softmax's vector work, LDS operand reads, and a block loop's loads and barrier."""
+    assert operands.is_cuda and operands.numel() * operands.element_size() >= 65536
     out = ctypes.c_double(0.0)
-    if load_probe().ape_probe_mfma(_ptr(operands), 1 if with_softmax else 0, _ptr(sink), warm_ms, _stream(stream), ctypes.byref(out)):
+    if load_probe().ape_probe_mfma(_ptr(operands), int(level), _ptr(sink), warm_ms, _stream(stream), ctypes.byref(out)):
         raise RuntimeError("ape_probe_mfma failed")
+    return out.value
+
+
+def probe_valu_issue(waves_per_simd: int, sink: torch.Tensor, warm_ms: float = 50.0, stream=None) -> float:
+    """``ape_probe_valu_issue``: ns per softmax vector instruction per SIMD with 1, 2 or 4 wavefronts per SIMD."""
+    out = ctypes.c_double(0.0)
+    if load_probe().ape_probe_valu_issue(int(waves_per_simd), _ptr(sink), warm_ms, _stream(stream), ctypes.byref(out)):
+        raise RuntimeError("ape_probe_valu_issue failed")
     return out.value
 
 
