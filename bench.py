@@ -480,17 +480,20 @@ def main():
             "mfma_bf16_random_operands_with_softmax_valu_tflops": B.probe_mfma(ops_rand, 1, sink),
             "mfma_bf16_random_operands_softmax_lds_fragments_tflops": B.probe_mfma(ops_rand, 2, sink),
             "mfma_bf16_random_operands_block_loop_skeleton_tflops": B.probe_mfma(ops_rand, 3, sink),
+            "mfma_bf16_random_operands_block_loop_skeleton_narrow_tile_tflops": B.probe_mfma(ops_rand, 4, sink),
             "hbm_read_only_gbs": B.probe_hbm_read(big, sink),
             "softmax_valu_ns_per_instruction_per_simd": {str(w): B.probe_valu_issue(w, sink) for w in (1, 2, 4)},
             "note": "libape_probe.so: MFMA 32x32x16 bf16 back to back, one wavefront per SIMD on every CU (no LDS, no loads); "
                     "the third figure adds the vector work of a flash-attention softmax (per pair of scores 2 FMA, 2 exp, 2 add, "
                     "1 packed conversion) in the MFMAs' shadows; the fourth also fetches the A operands from LDS as a flash body "
                     "fetches its K and V^T fragments; the fifth also loads a 16 KB block per 32 MFMAs straight into an LDS ring (out of "
-                    "the cache), waits and passes a workgroup barrier: a flash block loop without bookkeeping, masks and HBM traffic; "
+                    "the cache), waits and passes a workgroup barrier: a flash block loop without bookkeeping, masks and HBM traffic "
+                    "(the sixth: the same for the narrow tile, 32 rows per wavefront, two workgroups per CU); "
                     "read-only stream over 2 GiB; the softmax's vector instructions alone with 1, 2 and 4 wavefronts per SIMD",
         }
         for key in ("mfma_bf16_zero_operands_tflops", "mfma_bf16_random_operands_tflops", "mfma_bf16_random_operands_with_softmax_valu_tflops",
-                    "mfma_bf16_random_operands_softmax_lds_fragments_tflops", "mfma_bf16_random_operands_block_loop_skeleton_tflops"):
+                    "mfma_bf16_random_operands_softmax_lds_fragments_tflops", "mfma_bf16_random_operands_block_loop_skeleton_tflops",
+                    "mfma_bf16_random_operands_block_loop_skeleton_narrow_tile_tflops"):
             ceilings[key.replace("_tflops", "_frac_of_published_peak")] = ceilings[key] / PEAK_BF16_TFLOPS
         ceilings["hbm_read_only_frac_of_published_peak"] = ceilings["hbm_read_only_gbs"] / PEAK_HBM_GBS
         del big, ops_zero, ops_rand

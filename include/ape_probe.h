@@ -25,6 +25,8 @@ extern "C" {
  *                 32 MFMAs).  3: every 32 MFMAs also load a 16 KB block straight into a ring of LDS
  *                 slots (out of the cache: the 64 KiB of operands), wait for an older block and pass a
  *                 workgroup barrier -- a flash block loop without bookkeeping, masks and HBM traffic.
+ *                 4: the same for the narrow tile (a wavefront has 32 rows: 16 MFMAs and half the softmax per
+ *                 block next to the same fragment reads and loads, two workgroups per CU).
  *                 Anything else is an error.
  *   sink          DEVICE, 4 bytes, never written in practice (keeps the arithmetic alive)
  *   tflops        HOST, receives the rate

@@ -164,8 +164,8 @@ def load_probe() -> ctypes.CDLL:
 
 
 def probe_mfma(operands: torch.Tensor, level, sink: torch.Tensor, warm_ms: float = 150.0, stream=None) -> float:
-    """``ape_probe_mfma``: TFLOP/s of back-to-back bf16 MFMAs on the given 64 KiB of operand data; level 0..3
-    (False/True = 0/1) adds the softmax's vector work, LDS operand reads, and a block loop's loads and barrier."""
+    """``ape_probe_mfma``: TFLOP/s of back-to-back bf16 MFMAs on the given 64 KiB of operand data; level 0..4
+    adds the softmax's vector work, LDS operand reads, a block loop's loads and barrier; 4 is the narrow tile's loop."""
     assert operands.is_cuda and operands.numel() * operands.element_size() >= 65536
     out = ctypes.c_double(0.0)
     if load_probe().ape_probe_mfma(_ptr(operands), int(level), _ptr(sink), warm_ms, _stream(stream), ctypes.byref(out)):

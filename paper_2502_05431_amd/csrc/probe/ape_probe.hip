@@ -30,7 +30,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 // LEVEL 3: every iteration also loads a 16 KB block straight into a ring of six LDS slots (four 1 KB
 // loads per wavefront, from the 64 KiB of operands, i.e. out of the cache), waits for the block of two
 // iterations ago and passes a workgroup barrier: a flash block loop without its bookkeeping and its HBM traffic.
-constexpr int kSlotBytes = 16384, kRingSlots = 6;
+// LEVEL 4: the same for the narrow tile -- a wavefront has 32 rows instead of 64, i.e. 16 MFMAs and half the
+// softmax per block next to the same fragment reads and loads, a ring of five slots, two workgroups per CU.
+constexpr int kSlotBytes = 16384;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 __device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
@@ -41,7 +43,8 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
 template <int LEVEL>
 __global__ __launch_bounds__(256) void mfma_kernel(const uint32_t* __restrict__ operands, float* __restrict__ sink, int iters, float sc) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    constexpr bool SOFTMAX = LEVEL >= 1, LDSOPS = LEVEL >= 2, RING = LEVEL >= 3;
+    constexpr bool SOFTMAX = LEVEL >= 1, LDSOPS = LEVEL >= 2, RING = LEVEL >= 3, NARROW = LEVEL == 4;
+    constexpr int kRingSlots = NARROW ? 5 : 6;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     bf16x8 a[8], b[8], kf[8];
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(256) void mfma_kernel(const uint32_t* __restrict__ 
     uint32_t pk[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) pk[i] = 0;
-    int slot_rd = 0, slot_wr = 4 * kSlotBytes;                 // ring offsets: the block read now, the block whose loads start now
+    int slot_rd = 0, slot_wr = (kRingSlots - 2) * kSlotBytes;                 // ring offsets: the block read now, the block whose loads start now
     const uint32_t src_off = (uint32_t)(wave * 4096 + lane * 16);
     for (int it = 0; it < iters; ++it) {
         const char* slot = lds + slot_rd;
@@ -97,7 +100,10 @@ __global__ __launch_bounds__(256) void mfma_kernel(const uint32_t* __restrict__ 
         }
 #pragma unroll
         for (int n = 0; n < 32; ++n) {
-            if (n < 16) o[n & 7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n & 7], b[(n >> 3) * 4 + (n & 3)], o[n & 7], 0, 0, 0);
+            if (NARROW && (n & 1)) {
+                // (the narrow tile: every second slot has no MFMA)
+            } else if (n < 16) o[n & 7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n & 7], b[(n >> 3) * 4 + (n & 3)], o[n & 7], 0, 0, 0);
+            else if (NARROW) s[(n >> 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(n >> 1) & 7], b[n & 7], s[(n >> 1) & 1], 0, 0, 0);
             else s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(n >> 1) & 7], b[n & 7], s[n & 1], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (LDSOPS) {
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(256) void mfma_kernel(const uint32_t* __restrict__ 
                 const uint32_t voff = src_off + n * 1024 + ((it & 3) << 14);
                 asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(operands), "s"(m0v) : "m0", "memory");
             }
-            if (SOFTMAX) {
+            if (SOFTMAX && !(NARROW && (n & 2))) {
                 const int k = n >> 1;
                 if ((n & 1) == 0) {
                     e0 = __builtin_amdgcn_exp2f(fmaf(sv[2 * k], sc, -m));
@@ -216,23 +222,26 @@ int timed(F launch, int reps, float warm_ms, hipStream_t s, float* ms_per_launch
 extern "C" {
 
 int ape_probe_mfma(const void* operands, int level, float* sink, float warm_ms, void* stream, double* tflops) {
-    if (!operands || !sink || !tflops || level < 0 || level > 3) return -1;
+    if (!operands || !sink || !tflops || level < 0 || level > 4) return -1;
     hipStream_t s = (hipStream_t)stream;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return -1;
     const int iters = 4000;
-    const int lds_bytes = level >= 3 ? kRingSlots * kSlotBytes : level == 2 ? kSlotBytes : 0;
-    if (level >= 3 && hipFuncSetAttribute((const void*)mfma_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) return -1;
+    const int lds_bytes = level == 4 ? 5 * kSlotBytes : level == 3 ? 6 * kSlotBytes : level == 2 ? kSlotBytes : 0;
+    if (level == 3 && hipFuncSetAttribute((const void*)mfma_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) return -1;
+    if (level == 4 && hipFuncSetAttribute((const void*)mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) return -1;
     float ms = 0.f;
     auto launch = [&] {
         const uint32_t* ops = (const uint32_t*)operands;
         if (level == 0) mfma_kernel<0><<<cus, 256, lds_bytes, s>>>(ops, sink, iters, 1.0001f);
         else if (level == 1) mfma_kernel<1><<<cus, 256, lds_bytes, s>>>(ops, sink, iters, 1.0001f);
         else if (level == 2) mfma_kernel<2><<<cus, 256, lds_bytes, s>>>(ops, sink, iters, 1.0001f);
-        else mfma_kernel<3><<<cus, 256, lds_bytes, s>>>(ops, sink, iters, 1.0001f);
+        else if (level == 3) mfma_kernel<3><<<cus, 256, lds_bytes, s>>>(ops, sink, iters, 1.0001f);
+        else mfma_kernel<4><<<2 * cus, 256, lds_bytes, s>>>(ops, sink, iters, 1.0001f);
     };
     if (timed(launch, 5, warm_ms, s, &ms)) return -1;
-    // one workgroup per CU, 4 wavefronts, 32 MFMAs of 32*32*16*2 flop per iteration
+    // levels 0..3: one workgroup per CU, 4 wavefronts, 32 MFMAs of 32*32*16*2 flop per iteration; level 4: two
+    // workgroups per CU with 16 MFMAs per wavefront and iteration -- the same number per CU
     *tflops = (double)cus * 4 * 32 * 32768.0 * iters / (ms * 1e-3) / 1e12;
     return 0;
 }
