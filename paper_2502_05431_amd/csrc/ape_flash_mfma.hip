@@ -563,9 +563,10 @@ __device__ __forceinline__ void pipeline_body(char* lds, int pv_off, const LaneO
 // The fast body again, for pairs of bodies: it reads the scores of block j from s_in and writes
 // those of block j+1 to s_out, two different register sets that swap roles from one body to the
 // next, so no score is ever copied and the softmax is free to sit in either half.  With two row
-// blocks the softmax of row block 0 runs in the PV half (the PV MFMAs take row block 0 first,
-// which frees its probability registers for the second eight slices), that of row block 1 in the
-// K Q^T half; with one row block its first four slices run in the last four of the PV half.
+// blocks it is dealt over the MFMA slots in half-slices, behind the PV MFMAs that still read the
+// probabilities of block j-1 (see wide_half_slice below; measured against whole slices in the sixteen
+// middle slots: config-3 prefill 0.508 -> 0.4925 ms, 16384-token chunks' encode 15.29 -> 14.65 ms);
+// with one row block its first four slices run in the last four of the PV half.
 template <int RB, int RING, class LO, int PH = -1>
 __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const LaneOffsets& lo, const LO& full,
                                                  const bf16x8 (&qf)[RB][8], WaveState<RB>& st, float sc2,
@@ -584,6 +585,22 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
     float psum[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) psum[rb][0] = psum[rb][1] = 0.f;
+    // Wide tile: the softmax in half-slices (two exponentials; then, a slot later, the sums and the
+    // conversion), one per MFMA slot from slot 2 on, so that no slot carries more vector work than its MFMA
+    // covers.  The probabilities of block j overwrite those of block j-1 as the PV MFMAs let go of them: the
+    // MFMAs of slots 0..3 read p[0][0], 4..7 p[0][1], 8..11 p[1][0], 12..15 p[1][1], and slice i = (row block
+    // i / 8, register pair i % 8) writes p[i / 8][(i % 8) / 4] in slot 2 i + 3 or later.
+    float e_half[2];
+    auto wide_half_slice = [&](int t) {                              // t = 0 .. 31: half-slice t
+        const int i = t >> 1, rb = i / 8, k = i % 8;
+        if ((t & 1) == 0) softmax_half_a<RB>(s_in, rb, k, sc2, st.m[rb], e_half);
+        else softmax_half_b<RB>(e_half, rb, k, psum, p);
+    };
+    auto wide_slot = [&](int n) {                                    // n = 0 .. 31: the MFMA slot
+        if (n < 2) return;
+        if (n < 30) wide_half_slice(n - 2);
+        else { wide_half_slice(2 * n - 32); wide_half_slice(2 * n - 31); }   // slots 30, 31: two each
+    };
     // ---- O += P V of block j-1
 #pragma unroll
     for (int n = 0; n < NS; ++n) {
@@ -606,7 +623,7 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
         }
         if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, slot_new, full, m0v);
         else if (n < LOADS_PER_BLOCK + (STATIC ? 2 : 3)) plan.fast_piece(n - LOADS_PER_BLOCK);   // (piece 2 turns the ring offsets)
-        if (RB == 2 && n >= 8) softmax_slice<RB>(s_in, 0, n - 8, sc2, st.m[0], psum, p);
+        if (RB == 2) wide_slot(n);
         if (RB == 1 && n >= 4) softmax_slice<RB>(s_in, 0, n - 4, sc2, st.m[0], psum, p);   // slab 0, last read by MFMA 3
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -620,7 +637,7 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
         const int ks = n / RB, rb = n % RB;
         s_out[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], s_out[rb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (RB == 2 && n < 8) softmax_slice<RB>(s_in, 1, n, sc2, st.m[1], psum, p);
+        if (RB == 2) wide_slot(NS + n);
         if (RB == 1 && n < 4) softmax_slice<RB>(s_in, 0, n + 4, sc2, st.m[0], psum, p);
         if (n < 4) vf[n] = read_v_cur<RB == 1>(va, slot_cur, slot_pv, lo, n);   // for the next body's PV
         if (RB == 2 && n < 4) kf[4 + n] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 + n);   // first used by MFMA 8
