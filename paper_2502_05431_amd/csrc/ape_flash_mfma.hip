@@ -608,15 +608,16 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
         st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p[rb][f >> 2]),
                                                                   st.o[rb][f & 3], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (n < 2) {
+        if (RB == 2) {
+            // one fragment per slot: V^T fragments 4..7 of block j-1 in slots 0..3 (each used four slots later),
+            // K fragments 0..3 of block j+1 in slots 4..7 (the fragments of k-slabs 4..7 are read in the K Q^T
+            // half, when the scores of block j are mostly consumed: sixteen registers fewer at the body's
+            // fullest point)
+            if (n < 4) vf[4 + n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + n);
+            else if (n < 8) kf[n - 4] = read_k_frag<LO::kcol>(slot_nxt, lo, n - 4);
+        } else if (n < 2) {
             vf[4 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + 2 * n);
             vf[5 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 5 + 2 * n);
-        }
-        if (RB == 2) {
-            // (the fragments of k-slabs 4..7 are read in the K Q^T half, when the scores of block j are
-            // mostly consumed: sixteen registers fewer at the body's fullest point)
-            if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); }
-            if (n == 3) { kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); }
         } else if (n == 4 || n == 5) {                               // (after the wait for the V^T fragments)
 #pragma unroll
             for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
@@ -640,7 +641,7 @@ __device__ __forceinline__ void pipeline_body_pp(char* lds, int pv_off, const La
         if (RB == 2) wide_slot(NS + n);
         if (RB == 1 && n < 4) softmax_slice<RB>(s_in, 0, n + 4, sc2, st.m[0], psum, p);
         if (n < 4) vf[n] = read_v_cur<RB == 1>(va, slot_cur, slot_pv, lo, n);   // for the next body's PV
-        if (RB == 2 && n < 4) kf[4 + n] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 + n);   // first used by MFMA 8
+        if (RB == 2 && n >= 4 && n < 8) kf[n] = read_k_frag<LO::kcol>(slot_nxt, lo, n);   // first used by MFMA 8
         __builtin_amdgcn_sched_barrier(0);
     }
     bool bad = false;
@@ -689,17 +690,19 @@ __device__ __forceinline__ void pipeline_body_even(char* lds, int pv_off, const 
         st.o[rb][f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f], __builtin_bit_cast(bf16x8, p_in[rb][f >> 2]),
                                                                   st.o[rb][f & 3], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (n < 2) {
-            vf[4 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + 2 * n);
-            vf[5 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 5 + 2 * n);
-        }
         if (RB == 2) {
+            if (n < 2) {
+                vf[4 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + 2 * n);
+                vf[5 + 2 * n] = read_v_pv<RB == 1>(va, slot_pv, lo, 5 + 2 * n);
+            }
             if (n == 2) { kf[0] = read_k_frag<LO::kcol>(slot_nxt, lo, 0); kf[1] = read_k_frag<LO::kcol>(slot_nxt, lo, 1); kf[2] = read_k_frag<LO::kcol>(slot_nxt, lo, 2); }
             if (n == 3) { kf[3] = read_k_frag<LO::kcol>(slot_nxt, lo, 3); kf[4] = read_k_frag<LO::kcol>(slot_nxt, lo, 4); kf[5] = read_k_frag<LO::kcol>(slot_nxt, lo, 5); }
             if (n == 4) { kf[6] = read_k_frag<LO::kcol>(slot_nxt, lo, 6); kf[7] = read_k_frag<LO::kcol>(slot_nxt, lo, 7); }
-        } else if (n == 4 || n == 5) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) kf[4 * (n - 4) + q] = read_k_frag<LO::kcol>(slot_nxt, lo, 4 * (n - 4) + q);
+        } else {
+            // narrow tile: the reads spread over the slots -- one V^T fragment of block j-1 in each of slots 0..3 (used
+            // four slots later), two K fragments of block j+1 in each of slots 4..7
+            if (n < 4) vf[4 + n] = read_v_pv<RB == 1>(va, slot_pv, lo, 4 + n);
+            else { kf[2 * (n - 4)] = read_k_frag<LO::kcol>(slot_nxt, lo, 2 * (n - 4)); kf[2 * (n - 4) + 1] = read_k_frag<LO::kcol>(slot_nxt, lo, 2 * (n - 4) + 1); }
         }
         if (n < LOADS_PER_BLOCK) issue_block_load_chain(n, plan.new_k, plan.new_v, lds + plan.o_new, full, m0v);
         else if (n < LOADS_PER_BLOCK + 3) plan.fast_piece(n - LOADS_PER_BLOCK);
