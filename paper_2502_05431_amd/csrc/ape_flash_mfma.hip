@@ -15,7 +15,7 @@
 //   - keys/values stream in blocks of 32 tokens through a ring of LDS slots filled by direct
 //     global->LDS loads (16 bytes per lane, no staging registers), several blocks ahead of the
 //     compute; rows are 256 bytes and XOR-swizzled so that every LDS read is conflict-free (the wide
-//     prefill tile keeps K column-major instead: one address register, k-slabs as immediates);
+//     tile keeps K column-major instead: one address register, k-slabs as immediates);
 //   - scores are computed TRANSPOSED, S^T = K Q^T: the accumulator layout then puts one query
 //     row in one lane (and its partner lane +32), so the softmax row reductions are in-lane,
 //     and the bf16 probabilities are already laid out as the B operand of O^T += V^T P^T;
@@ -24,7 +24,7 @@
 //     then K Q^T of block j+1 with the softmax of block j in the shadow of its MFMAs;
 //   - the softmax keeps a lazily updated reference instead of a running maximum, so its fast
 //     path is two exponentials, two adds and a conversion per pair of scores;
-//   - stretches of full, unmasked blocks of one segment run a branch-free body (in the wide prefill
+//   - stretches of full, unmasked blocks of one segment run a branch-free body (in the wide
 //     tile, long stretches in groups of bodies whose ring slots are compile-time constants); segment
 //     ends, partial blocks and the causal diagonal take a generic body with the same arithmetic;
 //   - what bounds the block loop is the instruction issue of the one wavefront per SIMD (wide tile:
@@ -76,9 +76,9 @@ constexpr float kPsumMax = 0x1p40f;          // a lane's block sum above this: s
 template <int RB> struct Ring { static constexpr int slots = RB == 2 ? 6 : 5; };
 
 // LDS layout of a block, two forms for K.
-// Row-major (loads with the non-temporal hint: the bandwidth-bound decode): K row r at r*256, 16-byte
+// Row-major (the narrow tile, and with it the bandwidth-bound decode): K row r at r*256, 16-byte
 // chunk index XOR (r & 15) (conflict-free 16-byte reads down a column of rows).
-// Column-major (all other kernels): chunk c of row r at (r >> 4)*4096 + c*256 + (r & 15)*16 -- the 16
+// Column-major (the wide tile): chunk c of row r at (r >> 4)*4096 + c*256 + (r & 15)*16 -- the 16
 // rows a fragment read touches per pass are 256 consecutive bytes (no conflicts, no swizzle), and the
 // fragment of k-slab ks is at one per-lane offset + 512*ks, an immediate: ONE address register and one
 // addition per body instead of eight of each (a wavefront's instruction issue is what bounds the
@@ -791,7 +791,7 @@ __device__ __forceinline__ void run_blocks(RingStart<Ring<RB>::slots, NT, KCOL>&
                                            WaveState<RB>& st, float sc2, const int (&lim)[RB]) {
     constexpr int RING = Ring<RB>::slots;
     constexpr int NF = RING - 3;
-    constexpr bool STATIC_RING = RB == 2 && KCOL;        // the wide prefill tile (the wide encode tile's register assignment does not survive it)
+    constexpr bool STATIC_RING = RB == 2 && KCOL;        // the wide tile
     if (rs.d0 == 0) return;
     RingPlan<RING>& plan = rs.plan;
     const LoadOffsetsT<NT, KCOL> full = rs.full;
@@ -1123,7 +1123,7 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs a, const int n_qtil
     walk.init_seq((const char*)a.k_prefix + head_b, (const char*)a.v_prefix + head_b, a.prefix_len,
               (const char*)a.k + (long)c0 * stride_b + head_b, (const char*)a.v + (long)c0 * stride_b + head_b,
               wg_tok_hi + 1, stride_b);
-    RingStart<Ring<RB>::slots, false> rs;
+    RingStart<Ring<RB>::slots, false, RB == 2> rs;
     start_stream(rs, walk, lds, __builtin_amdgcn_readfirstlane(tok_lo), tid);
 
     bf16x8 qf[RB][8];
