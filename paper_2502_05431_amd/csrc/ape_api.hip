@@ -156,7 +156,7 @@ QueryPlan prefill_plan(const ShapeInfo& si, int batch, int q_len, long max_ctx) 
     const long units = (long)batch * q_len * si.hq;
     const int bm = si.mfma ? flash_prefill_block_rows(rows, max_ctx) : 0;
     const int base = si.mfma ? batch * si.hkv * ceil_div(rows, bm) : (int)units;
-    int target = si.mfma ? flash_prefill_target_workgroups(max_ctx) : 1024;
+    int target = si.mfma ? flash_prefill_target_workgroups(rows, max_ctx) : 1024;
     // Two workgroups per CU only pay when their streams stay long: with few query rows (few row tiles)
     // the same target cuts the context into splits of a few hundred tokens, whose fixed cost per
     // workgroup outweighs the second workgroup (64 rows over 16K: 0.049 ms with 32 splits of 512 tokens,
@@ -282,7 +282,7 @@ size_t ape_workspace_bytes(int op, const ape_shape* shape, int32_t batch, int32_
     if (op == APE_OP_DECODE) {
         n_max = decode_plan(si, batch, cap).n_bound;
     } else {
-        for (long ctx : {kPrefillOneWorkgroupPerCuMaxCtx, kPrefillNarrowTileMaxCtx, cap}) {
+        for (long ctx : {kPrefillOneWorkgroupPerCuMaxCtx, flash_prefill_narrow_tile_max_ctx(q_len * si.group), cap}) {
             if (ctx > cap) continue;
             const int n = prefill_plan(si, batch, q_len, ctx).n_bound;
             if (n > n_max) n_max = n;

@@ -1285,12 +1285,19 @@ int flash_block_rows(int rows_per_kv_head) { return rows_per_kv_head > 128 ? 256
 // query rows (64 tokens x 4 heads per KV head give the same picture): 2.5K context 0.047 against
 // 0.064 ms, 10K 0.078 / 0.089, 16K 0.102 / 0.113, 32K 0.160 / 0.168, 48K 0.229 / 0.232, 64K equal, 128K
 // 0.537 / 0.527.  Up to 12K tokens one narrow workgroup per CU is enough, beyond that two.
+// With more query rows there are more row tiles per KV head, fewer splits and longer streams, and the
+// wide tile's better steady state wins sooner (narrow / wide, ms): 512 tokens x 4 heads over 24K and 32K
+// equal; 1024 x 4 over 16K 0.295 / 0.300, 24K 0.422 / 0.415, 32K 0.539 / 0.526, 40K 0.638 / 0.614;
+// 2048 x 4 over 8K 0.341 / 0.335, 16K 0.572 / 0.551, 24K 0.806 / 0.767, 32K 1.037 / 0.977.
+long flash_prefill_narrow_tile_max_ctx(int rows_per_kv_head) {
+    return rows_per_kv_head >= 8192 ? 6144 : rows_per_kv_head >= 4096 ? 20480 : 40960;
+}
 int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx) {
-    if (max_ctx <= kPrefillNarrowTileMaxCtx) return 128;
+    if (max_ctx <= flash_prefill_narrow_tile_max_ctx(rows_per_kv_head)) return 128;
     return flash_block_rows(rows_per_kv_head);
 }
-int flash_prefill_target_workgroups(long max_ctx) {
-    return max_ctx > kPrefillOneWorkgroupPerCuMaxCtx && max_ctx <= kPrefillNarrowTileMaxCtx ? 512 : 256;
+int flash_prefill_target_workgroups(int rows_per_kv_head, long max_ctx) {
+    return max_ctx > kPrefillOneWorkgroupPerCuMaxCtx && max_ctx <= flash_prefill_narrow_tile_max_ctx(rows_per_kv_head) ? 512 : 256;
 }
 
 hipError_t launch_flash_prefill(const QueryArgs& a, int block_rows, hipStream_t s) {

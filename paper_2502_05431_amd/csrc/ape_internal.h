@@ -283,9 +283,10 @@ int flash_block_rows(int rows_per_kv_head);
 // the same for the query prefill, which also looks at the context length (see the definition), and
 // the number of workgroups its split plan aims at
 int flash_prefill_block_rows(int rows_per_kv_head, long max_ctx);
-int flash_prefill_target_workgroups(long max_ctx);
-// the context lengths at which those two change their answer (each holds up to and including its value)
+int flash_prefill_target_workgroups(int rows_per_kv_head, long max_ctx);
+// the context lengths at which those two change their answer (each holds up to and including its value):
+// one narrow workgroup per CU, then two, then the wide tile -- the sooner the more query rows there are
 constexpr long kPrefillOneWorkgroupPerCuMaxCtx = 12288;
-constexpr long kPrefillNarrowTileMaxCtx = 40960;
+long flash_prefill_narrow_tile_max_ctx(int rows_per_kv_head);
 
 }  // namespace ape

@@ -147,11 +147,14 @@ def test_long_chunks_take_the_wide_tile_encode_sampled():
     ((30000, 10959), 32, 3),                              # 128 rows per KV head just below the switch: the most splits of any plan
     ((40960,), 50, 0),                                    # the last context length on the narrow tile
     ((40961,), 50, 0),                                    # the first one on the wide tile
+    ((20000, 480), 1024, 0),                              # 4096 rows per KV head: the last context length on the narrow tile
+    ((20000, 481), 1024, 0),                              # ... and the first on the wide one
+    ((6145,), 2048, 0),                                   # 8192 rows per KV head: the wide tile from 6145 context tokens
 ])
 def test_prefill_tile_switch_by_context_length_sampled(chunk_lens, q_len, self_extra):
-    """The query prefill takes the narrow query tile up to 40960 context tokens and the wide one
-    beyond (when a KV head has more than 128 query rows): ragged contexts on both sides of the
-    switch, sampled rows at tile edges."""
+    """The query prefill takes the narrow query tile up to 40960 context tokens (20480 with 4096 or more
+    query rows per KV head, 6144 with 8192 or more) and the wide one beyond (when a KV head has more than
+    128 query rows): ragged contexts on both sides of the switch, sampled rows at tile edges."""
     spec = W.CONFIGS[3].replace(chunk_lens=chunk_lens, q_len=q_len, prefix_len=7, decode_steps=self_extra, k_scale=1.0)
     r = W.make_request(spec, DEV)
     h = H.HostArrays(r)

@@ -134,15 +134,16 @@ def _needed(call):
 @pytest.mark.parametrize("seed", range(8))
 def test_workspace_bound_covers_every_context_length(seed):
     """ape_workspace_bytes knows batch and rows only; whatever the context length makes of the split
-    plan (the query tile and the workgroup target change at 12 288 and 40 960 context tokens), the
-    demand stays within it."""
+    plan (the workgroup target changes at 12 288 context tokens, the query tile at 40 960, 20 480 or
+    6144 depending on the number of query rows), the demand stays within it."""
     rng = random.Random(500 + seed)
     lib = B.load()
     sh = B.make_shape(32, 8, 128, B.APE_BF16) if seed % 2 == 0 else B.make_shape(rng.choice([8, 16, 64]), 8, 128, B.APE_BF16)
-    edges = [0, 1, 63, 64, 65, 255, 256, 257, 4096, 12287, 12288, 12289, 16384, 40959, 40960, 40961, 65536, 131072, 1 << 20, (1 << 31) - 1]
+    edges = [0, 1, 63, 64, 65, 255, 256, 257, 4096, 6143, 6144, 6145, 12287, 12288, 12289, 16384, 20479, 20480, 20481, 40959, 40960, 40961, 65536,
+             131072, 1 << 20, (1 << 31) - 1]
     for _ in range(60):
         batch = rng.choice([1, 1, 2, 4, 7, 32, 33])
-        q_len = rng.choice([1, 2, 31, 32, 33, 64, 100, 128, 256, 1000])
+        q_len = rng.choice([1, 2, 31, 32, 33, 64, 100, 128, 256, 1000, 1024, 2048])
         ctx = rng.choice(edges + [rng.randint(1, 300000)])
         arr = (B.ApeRequest * batch)()
         for b in range(batch):
