@@ -35,9 +35,9 @@ PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 # each scaled by the same counter's reading for the 1 GiB device copy of --calibrate-copy in the same
 # run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  TRAFFIC_SOURCE names the summary that holds the commands
 # and the raw readings; the line printed below carries it next to the number.
-MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": (786729 * 2 + 1048580) * 1024,     # 2.685 GB
-                          "flash_prefill_kernel": (272247 * 2 + 42587) * 1024,     # 0.601 GB
-                          "flash_prefill_kernel (decode)": (262909 * 2 + 536) * 1024}    # 0.539 GB
+MEASURED_TRAFFIC_BYTES = {"flash_encode_kernel": (786711 * 2 + 1048580) * 1024,     # 2.685 GB
+                          "flash_prefill_kernel": (272240 * 2 + 45082) * 1024,     # 0.604 GB
+                          "flash_prefill_kernel (decode)": (262914 * 2 + 536) * 1024}    # 0.539 GB
 TRAFFIC_SOURCE = "profiles/bench_cfg3_hbm_traffic_pmc.md"
 WARM_MS = 150.0                    # GPU time of untimed load in front of every timed region
 
