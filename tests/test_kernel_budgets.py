@@ -38,9 +38,9 @@ def test_flash_kernels_keep_their_register_budget():
             assert r["Occupancy"] == 2 and r["AGPRs"] == 0, (name, r)
         else:
             assert r["Occupancy"] == 1 and r["VGPRs"] == 256, (name, r)
-            # 137..138 (prefill) and 144 (encode) when the block loop is undisturbed; the builds that lost
-            # speed to accumulator-register copies sat at 158..256
-            assert r["AGPRs"] <= (150 if m.group(1) == "encode" else 145), (name, r)
+            # 116..130 when the block loop is undisturbed; the builds that lost speed to accumulator-register
+            # copies sat at 158..256
+            assert r["AGPRs"] <= 138, (name, r)
     assert seen == 20                                     # 8 encode, 8 prefill, 4 prefill with non-temporal loads
 
 
