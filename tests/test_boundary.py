@@ -55,6 +55,12 @@ def test_probe_library_exports_every_declared_symbol():
     out = ctypes.c_double(0.0)
     assert lib.ape_probe_mfma(None, 0, None, 0.0, None, ctypes.byref(out)) != 0      # refused on the host, nothing launched
     assert lib.ape_probe_hbm_read(None, 0, None, 0.0, None, ctypes.byref(out)) != 0
+    # a level or a wavefront count the probes do not have: refused before anything touches the GPU
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.ape_probe_mfma(fake, 5, fake, 0.0, None, ctypes.byref(out)) != 0
+    assert lib.ape_probe_mfma(fake, -1, fake, 0.0, None, ctypes.byref(out)) != 0
+    assert lib.ape_probe_valu_issue(3, fake, 0.0, None, ctypes.byref(out)) != 0
+    assert lib.ape_probe_valu_issue(1, None, 0.0, None, ctypes.byref(out)) != 0
 
 
 def test_status_strings():
