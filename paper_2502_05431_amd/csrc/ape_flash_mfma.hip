@@ -1102,6 +1102,10 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs a, const int n_qtil
     constexpr int BM = NW * 32 * RB;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
+    // Narrow tile: a wavefront outside its block loop (set-up, first loads, output) goes ahead of the wavefronts
+    // of the CU's other workgroup that are inside theirs, so that the CU spends more of its time with both
+    // workgroups in their loops (512 chunks of 256 tokens: 0.773 -> 0.764 ms; 2048-token chunks unchanged).
+    if constexpr (RB == 1) __builtin_amdgcn_s_setprio(3);
     int team, member;
     team_of_block(vblock, n_qtiles, team, member);
     if (team >= a.n_chunks * a.n_kv_heads) return;
@@ -1145,7 +1149,9 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs a, const int n_qtil
 
     WaveState<RB> st;
     init_state<RB>(st);
+    if constexpr (RB == 1) __builtin_amdgcn_s_setprio(0);
     run_blocks<RB>(rs, lds, qf, st, 0.08838834764831845f * LOG2E, lim);
+    if constexpr (RB == 1) __builtin_amdgcn_s_setprio(3);
 
     if constexpr (RB == 2) {
         // Wide tile (chunks beyond 4096 tokens: long streams, the output is a small part of a tile's
