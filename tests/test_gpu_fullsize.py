@@ -140,6 +140,42 @@ def test_long_chunks_take_the_wide_tile_encode_sampled():
     assert torch.isfinite(o_ctx.float()).all()
 
 
+def test_outlier_keys_move_the_softmax_reference_on_the_wide_tile():
+    """The lazily updated softmax reference on the WIDE tile, whose long stretches of full blocks run in
+    groups of bodies with the softmax dealt over the MFMA slots: keys planted deep inside long contexts
+    (prefill over 50K tokens) and deep inside a long chunk (encode), each aligned with one query row so
+    that its score towers over everything before it, force the rare path in the middle of such a stretch."""
+    spec = W.CONFIGS[3].replace(chunk_lens=(30000, 20000), q_len=64, prefix_len=32, decode_steps=0)
+    r = W.make_request(spec, DEV)
+    g = spec.n_q_heads // spec.n_kv_heads
+    rows = []
+    for hk in range(spec.n_kv_heads):
+        r.k_ctx[15000 + 40 * hk, hk] = 6.0 * r.q_self[5 + hk, hk * g]             # chunk 0, deep inside a split
+        r.k_ctx[30000 + 17000, hk] = 6.0 * r.q_self[40, hk * g + g - 1]           # chunk 1
+        r.k_ctx[9000, hk] = 5.0 * r.q_ctx[20000, hk * g + 1]                      # encode: row 20000 of chunk 0 sees token 9000
+        r.k_ctx[30000 + 5000, hk] = 5.0 * r.q_ctx[30000 + 19999, hk * g + 2]      # ... chunk 1: its last row, token 5000
+        rows.append(5 + hk)
+    h = H.HostArrays(r)
+    rng = np.random.default_rng(23)
+    out, lse = H.run_prefill(spec, r, spec.q_len, spec.q_len)
+    pairs = _pairs(rng, spec.q_len, spec.n_q_heads, 160, must_rows=rows + [40])
+    pairs += [pr for pr in ([(5 + hk, hk * g) for hk in range(spec.n_kv_heads)] + [(40, hk * g + g - 1) for hk in range(spec.n_kv_heads)]) if pr not in pairs]
+    ref, ref_lse, _ = H.oracle_prefill(h, spec.q_len, spec.q_len, r.temperature, r.scale, pairs=pairs)
+    H.check_close(_gather(out, pairs), ref, "bf16", "wide prefill with outliers")
+    assert np.abs(_gather(lse, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    o_ctx, lse_ctx, _, _ = H.run_encode(spec, r, with_prefix_rows=False)
+    m = spec.total_ctx_len
+    pairs = _pairs(rng, m, spec.n_q_heads, 96, must_rows=[20000, 49999, 9000, 35000])
+    pairs += [pr for pr in ([(20000, hk * g + 1) for hk in range(spec.n_kv_heads)] + [(49999, hk * g + 2) for hk in range(spec.n_kv_heads)]) if pr not in pairs]
+    ref, ref_lse = H.oracle_encode(h, pairs=pairs)
+    H.check_close(_gather(o_ctx, pairs), ref, "bf16", "wide encode with outliers")
+    assert np.abs(_gather(lse_ctx, pairs, head_major=True) - ref_lse).max() <= H.lse_tol("bf16")
+    assert torch.isfinite(out.float()).all() and torch.isfinite(o_ctx.float()).all()
+    # the planted keys really are beyond the lazy threshold (2^40 ~ 27.7 in natural-log units)
+    qk = (r.q_self[5].float()[0] * r.k_ctx[15000, 0].float()).sum().item() / spec.head_dim ** 0.5 / r.temperature
+    assert qk > 40.0
+
+
 @pytest.mark.parametrize("chunk_lens, q_len, self_extra", [
     ((20000, 1, 13000, 333, 9000, 64, 31), 50, 0),        # just above the switch; 200 ragged rows on one wide tile
     ((12000, 0, 12000, 12000, 6999, 3), 130, 70),         # three wide tiles, the last ragged; long own span
